@@ -1,0 +1,178 @@
+/*
+ * lcn.h -- C ABI of the MI355X LCN-Sinkhorn library.
+ *
+ * Entropy-regularised optimal transport between two point sets X (n x d) and
+ * Y (m x d) with marginals a, b (Sec. 2 of Gasteiger, Lienen & Guennemann,
+ * "Scalable Optimal Transport in High Dimensions ...", ICML 2021), where the
+ * Gibbs kernel K = exp(-C / lambda) is replaced by one of
+ *     dense    K itself                                   (Sec. 2, eq. 2)
+ *     sparse   K^sp: K on pairs that share an LSH bucket  (Sec. 3, eq. 3)
+ *     nystrom  K_Nys = U A^{-1} V from l landmarks        (Sec. 4)
+ *     lcn      K_LCN = K_Nys + (K^sp - K^sp_Nys)          (Sec. 4)
+ * and Sinkhorn's scaling iteration is run on that kernel without ever forming
+ * it ("LCN-Sinkhorn", Sec. 4).
+ *
+ * General conventions
+ *   - "device" pointers are HIP device memory on the current device, "host"
+ *     pointers ordinary host memory.  All matrices are row-major and dense.
+ *   - The caller owns every buffer it passes in, including the workspace, and
+ *     must keep the workspace alive and untouched until lcn_destroy.  X, Y, a,
+ *     b and the projections are read during lcn_build only (the build
+ *     synchronises the stream before it returns).
+ *   - All work is enqueued on the HIP stream given to lcn_build (a
+ *     hipStream_t passed as void*; NULL = the default stream).  Calls that
+ *     return host scalars synchronise that stream.
+ *   - Every function returns an lcn_status and never throws or aborts.  On
+ *     LCN_ERR_INVALID_ARG nothing has been written or launched.
+ *   - Same inputs and seeds give bit-identical landmarks, buckets, block
+ *     structure, factors and scalings.
+ *   - A handle must not be used from two threads at once.
+ */
+#ifndef LCN_H
+#define LCN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lcn_handle_s *lcn_handle; /* opaque; host memory owned by the library */
+
+typedef enum {
+    LCN_OK = 0,
+    LCN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size/lambda, l > n + m, odd bucket count ... */
+    LCN_ERR_ALLOC = 2,       /* workspace too small; *bytes_needed says how much is required */
+    LCN_ERR_DEVICE = 3,      /* a HIP call failed */
+    LCN_ERR_STATE = 4,       /* handle is null, destroyed, or of the wrong kind for this call */
+    LCN_ERR_SINGULAR = 5,    /* A (+ ridge I) is not positive definite (App. "Limitations") */
+    LCN_ERR_NONPOSITIVE = 6, /* some (K~ v)_i or (K~^T u)_j was <= 0: the Nystrom part is not
+                                guaranteed non-negative (App. "Limitations") */
+    LCN_WARN_NO_SUPPORT = 7  /* sparse kernel only: some row/column has no entry at all; such points
+                                get scaling 0 and carry no mass (App. "Limitations") -- the results
+                                are still valid */
+} lcn_status;
+
+typedef enum { LCN_COST_SQEUCLID = 0, LCN_COST_EUCLID = 1, LCN_COST_COSINE = 2 } lcn_cost;
+typedef enum { LCN_MODE_DENSE = 0, LCN_MODE_SPARSE = 1, LCN_MODE_NYSTROM = 2, LCN_MODE_LCN = 3 } lcn_mode;
+typedef enum { LCN_HASH_KMEANS = 0, LCN_HASH_CROSSPOLYTOPE = 1 } lcn_hash;
+typedef enum { LCN_F32 = 0, LCN_BF16 = 1 } lcn_dtype; /* storage type of X and Y only */
+
+/* Landmarks of the Nystrom part: centroids of Lloyd's k-means on X u Y
+ * ("k-means Nystrom", Sec. 4; fixed iteration count, App. "Complexity
+ * analysis").  The start is num_landmarks distinct points chosen by a
+ * splitmix64-driven partial Fisher-Yates shuffle from `seed`.
+ * ridge: A + ridge*I is inverted; 0 is the paper's plain inverse. */
+typedef struct {
+    int32_t num_landmarks; /* l, 1 .. 512, <= n + m */
+    int32_t kmeans_iters;  /* >= 1 */
+    uint64_t seed;
+    double ridge;          /* >= 0 */
+} lcn_landmark_params;
+
+/* Locality-sensitive hashing of X u Y (Sec. 3; App. "Choosing LSH neighbors
+ * and Nystrom landmarks").  Two points are neighbours if they share a bucket
+ * in at least one of num_rounds independent hash rounds (OR construction with
+ * one hash per band, App. "Complexity analysis").
+ *   LCN_HASH_KMEANS: round r = a k-means run with num_buckets clusters and
+ *     seed + r; bucket = cluster.
+ *   LCN_HASH_CROSSPOLYTOPE: round r = argmax([x^T R_r || -x^T R_r]) with
+ *     R_r = projections + r*d*(num_buckets/2), a d x num_buckets/2 row-major
+ *     device matrix supplied by the caller; num_buckets must be even.
+ * Ties go to the lowest bucket index. */
+typedef struct {
+    int32_t hash;         /* lcn_hash */
+    int32_t num_buckets;  /* b, 1 .. 4096 */
+    int32_t num_rounds;   /* R, 1 .. 8 */
+    int32_t kmeans_iters; /* >= 1 (k-means hashing only) */
+    uint64_t seed;
+    const float *projections; /* device; cross-polytope only, else NULL */
+} lcn_lsh_params;
+
+/* Size of a workspace that is certainly enough for everything except the
+ * sparse values, plus room for `nnz_guess` sparse entries (pass 0 to get a
+ * balanced-bucket guess).  The exact need is only known once the buckets have
+ * been built: if lcn_build returns LCN_ERR_ALLOC, call it again with a
+ * workspace of at least the *bytes_needed it reported.
+ * landmarks / lsh may be NULL for modes that do not use them. */
+lcn_status lcn_workspace_bytes(int64_t n, int64_t m, int32_t d, int32_t mode, const lcn_landmark_params *landmarks,
+                               const lcn_lsh_params *lsh, int64_t nnz_guess, size_t *bytes);
+
+/* Build the approximate kernel for one problem (Secs. 2-4).
+ *   X, Y       device, n x d and m x d, of type `dtype` (bf16 is widened to fp32 on load)
+ *   a, b       device, fp32 marginals of length n and m (positive)
+ *   lambda     entropic regularisation (> 0); K = exp(-c / lambda)
+ *   cost       lcn_cost; k-means always uses the Euclidean rule on the vectors as given
+ *   mode       lcn_mode; landmarks is required for NYSTROM/LCN, lsh for SPARSE/LCN
+ *   workspace  device, 256-byte aligned; everything the handle needs lives in it
+ *   bytes_needed  host, nullable; set on LCN_OK and on LCN_ERR_ALLOC
+ *   out        host; receives the handle (NULL on error)
+ * The scalings start at v = 1 (eq. 2).  Points must satisfy |x| < 2^10 and
+ * n + m <= 2^20 when k-means is used (its means are summed in 2^-32 fixed
+ * point so that they do not depend on summation order).
+ * Errors: INVALID_ARG, ALLOC, DEVICE, SINGULAR. */
+lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t d, int32_t dtype, const float *a,
+                     const float *b, float lambda, int32_t cost, int32_t mode, const lcn_landmark_params *landmarks,
+                     const lcn_lsh_params *lsh, void *workspace, size_t workspace_bytes, void *hip_stream,
+                     size_t *bytes_needed, lcn_handle *out);
+
+/* Run `iters` Sinkhorn iterations u = a ./ (K~ v), v = b ./ (K~^T u) (eq. 2),
+ * continuing from the current scalings: N then M iterations equal N + M.
+ * Returns after the work has finished.  NONPOSITIVE is reported if any sum
+ * was <= 0 (the affected scalings are NaN); WARN_NO_SUPPORT if the sparse
+ * kernel has empty rows/columns. */
+lcn_status sinkhorn_run(lcn_handle h, int32_t iters);
+
+/* Sinkhorn distance of the current plan P = diag(u) K~ diag(v):
+ *   d = <P, C> - lambda H(P) = lambda (sum_i r_i log u_i + sum_j c_j log v_j),
+ * r = P 1, c = P^T 1 (eq. 1; eq. 5 for the decomposed plan).  Entropy is
+ * included, so d may be negative.  d_host: host double. */
+lcn_status transport_cost(lcn_handle h, double *d_host);
+
+/* Marginals of the current plan: row_dev (n) = u .* (K~ v), col_dev (m) =
+ * v .* (K~^T u) as fp32 device vectors (either may be NULL), and the stopping
+ * quantity ||r - a||_1 + ||c - b||_1 of Thm. 3/4 (host double, nullable). */
+lcn_status plan_marginals(lcn_handle h, float *row_dev, float *col_dev, double *l1_residual_host);
+
+/* Natural logs of the scalings, fp32 device vectors of length n and m. */
+lcn_status lcn_get_scalings(lcn_handle h, float *log_u_dev, float *log_v_dev);
+/* Restart from given log v (log u is recomputed by the next iteration; it is
+ * stored so that queries see it).  Both device fp32. */
+lcn_status lcn_set_scalings(lcn_handle h, const float *log_u_dev, const float *log_v_dev);
+
+/* Structure queries (device outputs). */
+lcn_status lcn_get_landmarks(lcn_handle h, float *L_dev /* l x d */);
+lcn_status lcn_get_buckets(lcn_handle h, int32_t *bucket_dev /* R x (n + m): x_i at [r][i], y_j at [r][n + j] */);
+/* Canonical CSR of the sparse part (pairs sharing a bucket in any round, each
+ * once; columns ascending).  Call with colidx_dev == NULL to get *nnz_host and
+ * rowptr_dev (n + 1, int64) only.  val_dev (nullable) receives K^sp (sparse,
+ * dense modes) or K^sp - K^sp_Nys (lcn mode). */
+lcn_status lcn_get_csr(lcn_handle h, int64_t *nnz_host, int64_t *rowptr_dev, int32_t *colidx_dev, float *val_dev);
+/* Nystrom factors as stored: U (n x l) and W^T (m x l), fp32 device. */
+lcn_status lcn_get_factors(lcn_handle h, float *U_dev, float *Wt_dev);
+
+/* Sizes and counters: stored sparse entries (tiles, including pairs that a
+ * later round repeats and that are stored as zero), unique pairs, and the
+ * numeric-fault counters accumulated since the build. */
+typedef struct {
+    int64_t n, m;
+    int32_t d, l, rounds, buckets;
+    int64_t nnz_stored, nnz_unique;
+    int64_t nonpositive, empty_rows, empty_cols;
+    size_t workspace_used;
+} lcn_info;
+lcn_status lcn_get_info(lcn_handle h, lcn_info *info_host);
+
+/* Elapsed GPU time in milliseconds of the kernels of the last sinkhorn_run on
+ * this handle, measured with HIP events on the handle's stream, and the
+ * number of half-iteration launches it covered. */
+lcn_status lcn_last_run_timing(lcn_handle h, float *ms_host, int32_t *launches_host);
+
+void lcn_destroy(lcn_handle h); /* frees host memory only; the workspace is the caller's */
+const char *lcn_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCN_H */

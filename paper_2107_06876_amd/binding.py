@@ -1,0 +1,290 @@
+"""ctypes binding of include/lcn.h.  Same names as the C entry points;
+argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblcn_hip.so")
+
+COST_SQEUCLID, COST_EUCLID, COST_COSINE = 0, 1, 2
+MODE_DENSE, MODE_SPARSE, MODE_NYSTROM, MODE_LCN = 0, 1, 2, 3
+HASH_KMEANS, HASH_CROSSPOLYTOPE = 0, 1
+F32, BF16 = 0, 1
+
+OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_DEVICE, ERR_STATE, ERR_SINGULAR, ERR_NONPOSITIVE, WARN_NO_SUPPORT = range(8)
+
+
+class LandmarkParams(ctypes.Structure):
+    _fields_ = [("num_landmarks", ctypes.c_int32), ("kmeans_iters", ctypes.c_int32), ("seed", ctypes.c_uint64),
+                ("ridge", ctypes.c_double)]
+
+
+class LshParams(ctypes.Structure):
+    _fields_ = [("hash", ctypes.c_int32), ("num_buckets", ctypes.c_int32), ("num_rounds", ctypes.c_int32),
+                ("kmeans_iters", ctypes.c_int32), ("seed", ctypes.c_uint64), ("projections", ctypes.c_void_p)]
+
+
+class Info(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("m", ctypes.c_int64), ("d", ctypes.c_int32), ("l", ctypes.c_int32),
+                ("rounds", ctypes.c_int32), ("buckets", ctypes.c_int32), ("nnz_stored", ctypes.c_int64),
+                ("nnz_unique", ctypes.c_int64), ("nonpositive", ctypes.c_int64), ("empty_rows", ctypes.c_int64),
+                ("empty_cols", ctypes.c_int64), ("workspace_used", ctypes.c_size_t)]
+
+
+class LcnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, lcn_status_string(status), status))
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the HIP library; there is no fallback if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("HIP library %s has not been built: run `python -m paper_2107_06876_amd.build`"
+                               % _LIB_PATH)
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        lib.lcn_workspace_bytes.argtypes = [i64, i64, i32, i32, ctypes.POINTER(LandmarkParams),
+                                            ctypes.POINTER(LshParams), i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.lcn_build.argtypes = [vp, i64, vp, i64, i32, i32, vp, vp, ctypes.c_float, i32, i32,
+                                  ctypes.POINTER(LandmarkParams), ctypes.POINTER(LshParams), vp, ctypes.c_size_t, vp,
+                                  ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(vp)]
+        lib.sinkhorn_run.argtypes = [vp, i32]
+        lib.transport_cost.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+        lib.plan_marginals.argtypes = [vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
+        lib.lcn_get_scalings.argtypes = [vp, vp, vp]
+        lib.lcn_set_scalings.argtypes = [vp, vp, vp]
+        lib.lcn_get_landmarks.argtypes = [vp, vp]
+        lib.lcn_get_buckets.argtypes = [vp, vp]
+        lib.lcn_get_csr.argtypes = [vp, ctypes.POINTER(i64), vp, vp, vp]
+        lib.lcn_get_factors.argtypes = [vp, vp, vp]
+        lib.lcn_get_info.argtypes = [vp, ctypes.POINTER(Info)]
+        lib.lcn_last_run_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        lib.lcn_destroy.argtypes = [vp]
+        lib.lcn_destroy.restype = None
+        lib.lcn_status_string.argtypes = [i32]
+        lib.lcn_status_string.restype = ctypes.c_char_p
+        for name in ("lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
+                     "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
+                     "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing"):
+            getattr(lib, name).restype = i32
+        _lib = lib
+    return _lib
+
+
+def lcn_status_string(status: int) -> str:
+    return load_library().lcn_status_string(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dev(t: torch.Tensor, dtype):
+    assert t.is_cuda and t.is_contiguous() and t.dtype == dtype, "expected a contiguous %s device tensor" % dtype
+    return t
+
+
+class LcnHandle:
+    """Owns the opaque handle and keeps the workspace tensor alive."""
+
+    def __init__(self, raw, workspace, shape):
+        self.raw = raw
+        self.workspace = workspace
+        self.n, self.m, self.d, self.l, self.rounds = shape
+        self.device = workspace.device
+
+    def __del__(self):
+        try:
+            lcn_destroy(self)
+        except Exception:
+            pass
+
+
+def _params(landmarks, lsh, keep):
+    lm = None
+    if landmarks is not None:
+        lm = LandmarkParams(int(landmarks["num_landmarks"]), int(landmarks.get("kmeans_iters", 10)),
+                            int(landmarks.get("seed", 1)), float(landmarks.get("ridge", 0.0)))
+    ls = None
+    if lsh is not None:
+        proj = lsh.get("projections")
+        if proj is not None:
+            proj = _dev(proj, torch.float32)
+            keep.append(proj)
+        ls = LshParams(int(lsh.get("hash", HASH_KMEANS)), int(lsh["num_buckets"]), int(lsh["num_rounds"]),
+                       int(lsh.get("kmeans_iters", 10)), int(lsh.get("seed", 101)),
+                       None if proj is None else proj.data_ptr())
+    return lm, ls
+
+
+def lcn_workspace_bytes(n, m, d, mode, landmarks=None, lsh=None, nnz_guess=0) -> int:
+    lm, ls = _params(landmarks, lsh, [])
+    out = ctypes.c_size_t(0)
+    st = load_library().lcn_workspace_bytes(n, m, d, mode, None if lm is None else ctypes.byref(lm),
+                                            None if ls is None else ctypes.byref(ls), int(nnz_guess),
+                                            ctypes.byref(out))
+    if st != OK:
+        raise LcnError(st, "lcn_workspace_bytes")
+    return out.value
+
+
+def lcn_build(X, Y, a, b, lam, cost, mode, landmarks=None, lsh=None, workspace=None, stream=None) -> LcnHandle:
+    """landmarks: dict(num_landmarks, kmeans_iters, seed, ridge); lsh: dict(hash,
+    num_buckets, num_rounds, kmeans_iters, seed, projections).  X, Y: float32 or
+    bfloat16 device tensors.  If the workspace (a uint8 device tensor) is
+    missing or too small a new one of the size the library asks for is
+    allocated and the build is repeated."""
+    lib = load_library()
+    assert X.dtype in (torch.float32, torch.bfloat16) and Y.dtype == X.dtype
+    X, Y = _dev(X, X.dtype), _dev(Y, X.dtype)
+    a, b = _dev(a, torch.float32), _dev(b, torch.float32)
+    n, d = X.shape
+    m = Y.shape[0]
+    assert Y.shape[1] == d and a.numel() == n and b.numel() == m
+    keep = []
+    lm, ls = _params(landmarks, lsh, keep)
+    lmp = None if lm is None else ctypes.byref(lm)
+    lsp = None if ls is None else ctypes.byref(ls)
+    dtype = BF16 if X.dtype == torch.bfloat16 else F32
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+    if workspace is None:
+        workspace = torch.empty(lcn_workspace_bytes(n, m, d, mode, landmarks, lsh), dtype=torch.uint8,
+                                device=X.device)
+    for _ in range(2):
+        raw = ctypes.c_void_p()
+        need = ctypes.c_size_t(0)
+        st = lib.lcn_build(_ptr(X), n, _ptr(Y), m, d, dtype, _ptr(a), _ptr(b), float(lam), cost, mode, lmp, lsp,
+                           _ptr(workspace), workspace.numel(), ctypes.c_void_p(stream), ctypes.byref(need),
+                           ctypes.byref(raw))
+        if st == ERR_ALLOC and need.value > workspace.numel():
+            workspace = torch.empty(need.value, dtype=torch.uint8, device=X.device)
+            continue
+        break
+    if st != OK:
+        raise LcnError(st, "lcn_build")
+    h = LcnHandle(raw, workspace, (n, m, d, 0 if lm is None else lm.num_landmarks, 0 if ls is None else ls.num_rounds))
+    h._keep = keep
+    return h
+
+
+def sinkhorn_run(h: LcnHandle, iters: int, check: bool = True) -> int:
+    """Returns the status; raises on errors (a missing-support warning is returned, not raised)."""
+    st = load_library().sinkhorn_run(h.raw, int(iters))
+    if check and st not in (OK, WARN_NO_SUPPORT):
+        raise LcnError(st, "sinkhorn_run")
+    return st
+
+
+def transport_cost(h: LcnHandle) -> float:
+    out = ctypes.c_double(0.0)
+    st = load_library().transport_cost(h.raw, ctypes.byref(out))
+    if st != OK:
+        raise LcnError(st, "transport_cost")
+    return out.value
+
+
+def plan_marginals(h: LcnHandle):
+    """Returns (row marginals, column marginals, L1 residual)."""
+    r = torch.empty(h.n, dtype=torch.float32, device=h.device)
+    c = torch.empty(h.m, dtype=torch.float32, device=h.device)
+    res = ctypes.c_double(0.0)
+    st = load_library().plan_marginals(h.raw, _ptr(r), _ptr(c), ctypes.byref(res))
+    if st != OK:
+        raise LcnError(st, "plan_marginals")
+    return r, c, res.value
+
+
+def lcn_get_scalings(h: LcnHandle):
+    lu = torch.empty(h.n, dtype=torch.float32, device=h.device)
+    lv = torch.empty(h.m, dtype=torch.float32, device=h.device)
+    st = load_library().lcn_get_scalings(h.raw, _ptr(lu), _ptr(lv))
+    if st != OK:
+        raise LcnError(st, "lcn_get_scalings")
+    return lu, lv
+
+
+def lcn_set_scalings(h: LcnHandle, log_u, log_v):
+    st = load_library().lcn_set_scalings(h.raw, _ptr(_dev(log_u, torch.float32)), _ptr(_dev(log_v, torch.float32)))
+    if st != OK:
+        raise LcnError(st, "lcn_set_scalings")
+
+
+def lcn_get_landmarks(h: LcnHandle):
+    L = torch.empty((h.l, h.d), dtype=torch.float32, device=h.device)
+    st = load_library().lcn_get_landmarks(h.raw, _ptr(L))
+    if st != OK:
+        raise LcnError(st, "lcn_get_landmarks")
+    return L
+
+
+def lcn_get_buckets(h: LcnHandle):
+    info = lcn_get_info(h)
+    out = torch.empty((info.rounds, h.n + h.m), dtype=torch.int32, device=h.device)
+    st = load_library().lcn_get_buckets(h.raw, _ptr(out))
+    if st != OK:
+        raise LcnError(st, "lcn_get_buckets")
+    return out
+
+
+def lcn_get_csr(h: LcnHandle, values: bool = True):
+    """Returns (rowptr int64 (n+1), colidx int32 (nnz), values float32 (nnz) or None)."""
+    lib = load_library()
+    rowptr = torch.empty(h.n + 1, dtype=torch.int64, device=h.device)
+    nnz = ctypes.c_int64(0)
+    st = lib.lcn_get_csr(h.raw, ctypes.byref(nnz), _ptr(rowptr), None, None)
+    if st != OK:
+        raise LcnError(st, "lcn_get_csr")
+    colidx = torch.empty(max(nnz.value, 1), dtype=torch.int32, device=h.device)
+    val = torch.empty(max(nnz.value, 1), dtype=torch.float32, device=h.device) if values else None
+    st = lib.lcn_get_csr(h.raw, ctypes.byref(nnz), _ptr(rowptr), _ptr(colidx), _ptr(val))
+    if st != OK:
+        raise LcnError(st, "lcn_get_csr")
+    return rowptr, colidx[:nnz.value], None if val is None else val[:nnz.value]
+
+
+def lcn_get_factors(h: LcnHandle):
+    U = torch.empty((h.n, h.l), dtype=torch.float32, device=h.device)
+    Wt = torch.empty((h.m, h.l), dtype=torch.float32, device=h.device)
+    st = load_library().lcn_get_factors(h.raw, _ptr(U), _ptr(Wt))
+    if st != OK:
+        raise LcnError(st, "lcn_get_factors")
+    return U, Wt
+
+
+def lcn_get_info(h: LcnHandle) -> Info:
+    info = Info()
+    st = load_library().lcn_get_info(h.raw, ctypes.byref(info))
+    if st != OK:
+        raise LcnError(st, "lcn_get_info")
+    return info
+
+
+def lcn_last_run_timing(h: LcnHandle):
+    ms = ctypes.c_float(0.0)
+    launches = ctypes.c_int32(0)
+    st = load_library().lcn_last_run_timing(h.raw, ctypes.byref(ms), ctypes.byref(launches))
+    if st != OK:
+        raise LcnError(st, "lcn_last_run_timing")
+    return ms.value, launches.value
+
+
+def lcn_destroy(h: LcnHandle):
+    if getattr(h, "raw", None) is not None and h.raw.value:
+        load_library().lcn_destroy(h.raw)
+        h.raw = ctypes.c_void_p()

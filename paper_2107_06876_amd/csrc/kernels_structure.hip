@@ -1,0 +1,593 @@
+// Structure build: input conversion, exact-rule bucket assignment (k-means
+// and cross-polytope hashing), the k-means centroid update, the bucket sort
+// into blocks, and the CSR export.
+//
+// This file is compiled with -ffp-contract=off: the bucket of a point is
+// decided by fp64 arithmetic evaluated in a fixed order with separate
+// multiplies and adds, so that it is a function of the inputs alone.
+#include "lcn_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace lcn {
+
+// ------------------------------------------------------------- conversion --
+
+__global__ void convert_kernel(const void *X, long long nx_elems, const void *Y, long long total, int dtype, float *Z,
+                               unsigned *range_flag)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    long long stride = (long long)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (; i < total; i += stride) {
+        const void *src = i < nx_elems ? X : Y;
+        long long j = i < nx_elems ? i : i - nx_elems;
+        float v;
+        if (dtype == LCN_BF16) {
+            unsigned bits = ((const unsigned short *)src)[j];
+            v = __uint_as_float(bits << 16);
+        } else {
+            v = ((const float *)src)[j];
+        }
+        Z[i] = v;
+        bad |= !(fabsf(v) < 1024.0f);
+    }
+    if (bad) atomicOr(range_flag, 1u);
+}
+
+hipError_t launch_convert(const void *X, long long n, const void *Y, long long m, int d, int dtype, float *Z,
+                          unsigned *range_flag, hipStream_t s)
+{
+    long long total = (n + m) * d;
+    int grid = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(convert_kernel, dim3(grid), dim3(256), 0, s, X, n * d, Y, total, dtype, Z, range_flag);
+    return hipGetLastError();
+}
+
+__global__ void gather_rows_kernel(const float *Z, int d, const long long *idx, int k, float *out)
+{
+    int c = blockIdx.x;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) out[(long long)c * d + j] = Z[idx[c] * d + j];
+}
+
+hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k, float *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(k), dim3(128), 0, s, Z, d, idx, k, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------- exact-rule assignment --
+//
+// A block takes 64 points and walks over all candidates (centroids, or
+// projection columns) in tiles of 64; each thread keeps a 4 x 4 patch of fp64
+// accumulators.  Every accumulator adds its terms in ascending dimension
+// order, multiply and add separately, which is the rule the bucket of a point
+// is defined by.  KIND 0: squared distance, arg-min (k-means).  KIND 1: dot
+// product with the columns of a d x h matrix, arg-max over [g, -g]
+// (cross-polytope hashing).
+
+constexpr int TILE = 64;
+constexpr int KCH = 32;
+constexpr int LDT = TILE + 4;
+
+template <int KIND>
+__global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ Z, long long N, int d,
+                                                     const float *__restrict__ C, int k, int32_t *__restrict__ out)
+{
+    __shared__ float Ps[KCH][LDT];
+    __shared__ float Cs[KCH][LDT];
+    __shared__ double red_v[TILE][17];
+    __shared__ int red_i[TILE][17];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const long long p0 = (long long)blockIdx.x * TILE;
+
+    double bestv[4];
+    int besti[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        bestv[i] = 0.0;
+        besti[i] = -1;
+    }
+
+    for (int c0 = 0; c0 < k; c0 += TILE) {
+        double acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+
+        for (int k0 = 0; k0 < d; k0 += KCH) {
+            __syncthreads();
+            // stage 64 points x 32 dims and 64 candidates x 32 dims, zero padded
+            {
+                const int kk = tid & 31;
+                const int r0 = tid >> 5;
+#pragma unroll
+                for (int pass = 0; pass < 8; ++pass) {
+                    int r = r0 + pass * 8;
+                    long long p = p0 + r;
+                    float v = 0.f;
+                    if (p < N && k0 + kk < d) v = Z[p * d + k0 + kk];
+                    Ps[kk][r] = v;
+                }
+                if (KIND == 0) {
+#pragma unroll
+                    for (int pass = 0; pass < 8; ++pass) {
+                        int r = r0 + pass * 8;
+                        int c = c0 + r;
+                        float v = 0.f;
+                        if (c < k && k0 + kk < d) v = C[(long long)c * d + k0 + kk];
+                        Cs[kk][r] = v;
+                    }
+                } else {
+                    const int cc = tid & 63;
+                    const int kr = tid >> 6;
+#pragma unroll
+                    for (int pass = 0; pass < 8; ++pass) {
+                        int kq = kr + pass * 4;
+                        float v = 0.f;
+                        if (c0 + cc < k && k0 + kq < d) v = C[(long long)(k0 + kq) * k + c0 + cc];
+                        Cs[kq][cc] = v;
+                    }
+                }
+            }
+            __syncthreads();
+#pragma unroll 4
+            for (int kk = 0; kk < KCH; ++kk) {
+                const float4 pz = *(const float4 *)&Ps[kk][ty * 4];
+                const float4 cz = *(const float4 *)&Cs[kk][tx * 4];
+                const double pv[4] = {(double)pz.x, (double)pz.y, (double)pz.z, (double)pz.w};
+                const double cv[4] = {(double)cz.x, (double)cz.y, (double)cz.z, (double)cz.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (KIND == 0) {
+                            double t = pv[i] - cv[j];
+                            double t2 = t * t;
+                            acc[i][j] = acc[i][j] + t2;
+                        } else {
+                            double t = pv[i] * cv[j];
+                            acc[i][j] = acc[i][j] + t;
+                        }
+                    }
+            }
+        }
+        // fold this tile's candidates into the running best (lowest index wins ties)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int c = c0 + tx * 4 + j;
+            if (c >= k) continue;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (KIND == 0) {
+                    double D = acc[i][j];
+                    if (besti[i] < 0 || D < bestv[i] || (D == bestv[i] && c < besti[i])) {
+                        bestv[i] = D;
+                        besti[i] = c;
+                    }
+                } else {
+                    double g = acc[i][j];
+                    // candidate c has value g, candidate k + c has value -g
+                    if (besti[i] < 0 || g > bestv[i] || (g == bestv[i] && c < besti[i])) {
+                        bestv[i] = g;
+                        besti[i] = c;
+                    }
+                    double ng = -g;
+                    if (ng > bestv[i] || (ng == bestv[i] && k + c < besti[i])) {
+                        bestv[i] = ng;
+                        besti[i] = k + c;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        red_v[ty * 4 + i][tx] = bestv[i];
+        red_i[ty * 4 + i][tx] = besti[i];
+    }
+    __syncthreads();
+    if (tid < TILE) {
+        double bv = 0.0;
+        int bi = -1;
+        for (int t = 0; t < 16; ++t) {
+            double v = red_v[tid][t];
+            int ix = red_i[tid][t];
+            if (ix < 0) continue;
+            bool better;
+            if (KIND == 0)
+                better = bi < 0 || v < bv || (v == bv && ix < bi);
+            else
+                better = bi < 0 || v > bv || (v == bv && ix < bi);
+            if (better) {
+                bv = v;
+                bi = ix;
+            }
+        }
+        if (p0 + tid < N) out[p0 + tid] = bi;
+    }
+}
+
+hipError_t launch_assign_kmeans(const float *Z, long long N, int d, const float *cent, int k, int32_t *out,
+                                hipStream_t s)
+{
+    int grid = (int)((N + TILE - 1) / TILE);
+    hipLaunchKernelGGL(assign_kernel<0>, dim3(grid), dim3(256), 0, s, Z, N, d, cent, k, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
+                                       hipStream_t s)
+{
+    int grid = (int)((N + TILE - 1) / TILE);
+    hipLaunchKernelGGL(assign_kernel<1>, dim3(grid), dim3(256), 0, s, Z, N, d, Rm, b / 2, out);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------- k-means update --
+//
+// Member sums in 2^-32 fixed point: integer addition is associative, so the
+// atomics below give the same sums in any order.
+
+__global__ void kmeans_accumulate_kernel(const float *__restrict__ Z, long long N, int d,
+                                         const int32_t *__restrict__ assign, long long *sums, long long *counts)
+{
+    long long total = N * d;
+    long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    long long stride = (long long)gridDim.x * blockDim.x;
+    for (; e < total; e += stride) {
+        long long p = e / d;
+        int j = (int)(e - p * d);
+        int c = assign[p];
+        long long q = __double2ll_rn((double)Z[e] * 4294967296.0);
+        atomicAdd((unsigned long long *)&sums[(long long)c * d + j], (unsigned long long)q);
+        if (j == 0) atomicAdd((unsigned long long *)&counts[c], 1ull);
+    }
+}
+
+__global__ void kmeans_finalize_kernel(const long long *sums, const long long *counts, int k, int d, float *cent)
+{
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= k * d) return;
+    int c = e / d;
+    long long cnt = counts[c];
+    if (cnt == 0) return;  // an empty cluster keeps its centroid
+    double mean = ((double)sums[e] * (1.0 / 4294967296.0)) / (double)cnt;
+    cent[e] = (float)mean;
+}
+
+hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *sums,
+                                long long *counts, float *cent, hipStream_t s)
+{
+    hipError_t e = hipMemsetAsync(sums, 0, sizeof(long long) * (size_t)k * d, s);
+    if (e != hipSuccess) return e;
+    e = hipMemsetAsync(counts, 0, sizeof(long long) * (size_t)k, s);
+    if (e != hipSuccess) return e;
+    long long total = N * d;
+    int grid = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
+    hipLaunchKernelGGL(kmeans_accumulate_kernel, dim3(grid), dim3(256), 0, s, Z, N, d, assign, sums, counts);
+    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((k * d + 255) / 256), dim3(256), 0, s, sums, counts, k, d, cent);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------ bucket sort --
+//
+// Stable counting sort of the point indices of each side (X, Y) by bucket,
+// per hash round.  Chunks of CH consecutive indices are histogrammed, the
+// histograms are prefixed over chunks and buckets, and each chunk is then
+// scattered by one wavefront that ranks equal keys in index order.
+
+constexpr int CH = 1024;
+
+int sort_chunks(long long n, long long m)
+{
+    long long mx = n > m ? n : m;
+    return (int)((mx + CH - 1) / CH);
+}
+
+__device__ inline long long side_count(const SortBuffers &B, int side) { return side == 0 ? B.n : B.m; }
+
+// grid: (chunks, R, 2)
+__global__ __launch_bounds__(256) void sort_hist_kernel(SortBuffers B)
+{
+    extern __shared__ int hist[];
+    const int chunk = blockIdx.x, r = blockIdx.y, side = blockIdx.z;
+    const long long cnt = side_count(B, side);
+    for (int t = threadIdx.x; t < B.b; t += blockDim.x) hist[t] = 0;
+    __syncthreads();
+    const long long base = (long long)chunk * CH;
+    const int32_t *bk = B.bucket + (long long)r * (B.n + B.m) + (side ? B.n : 0);
+    for (int t = threadIdx.x; t < CH; t += blockDim.x) {
+        long long i = base + t;
+        if (i < cnt) atomicAdd(&hist[bk[i]], 1);
+    }
+    __syncthreads();
+    int *dst = B.hist + (((long long)side * B.R + r) * B.chunks + chunk) * B.b;
+    for (int t = threadIdx.x; t < B.b; t += blockDim.x) dst[t] = hist[t];
+}
+
+// one thread per (side, round, bucket): exclusive prefix over chunks, bucket totals
+__global__ void sort_chunk_prefix_kernel(SortBuffers B)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= 2 * B.R * B.b) return;
+    int beta = t % B.b;
+    int sr = t / B.b;  // side * R + r
+    int *h = B.hist + (long long)sr * B.chunks * B.b + beta;
+    int run = 0;
+    for (int c = 0; c < B.chunks; ++c) {
+        int v = h[(long long)c * B.b];
+        h[(long long)c * B.b] = run;
+        run += v;
+    }
+    B.totals[t] = run;
+}
+
+// single block: bucket offsets per (side, round), tile offsets over all blocks
+__global__ __launch_bounds__(1024) void sort_offsets_kernel(SortBuffers B)
+{
+    __shared__ long long part[1024];
+    __shared__ long long part2[1024];
+    const int tid = threadIdx.x;
+    // per (side, round): exclusive scan of totals over buckets; 2R <= 16 sequences
+    for (int sr = 0; sr < 2 * B.R; ++sr) {
+        const int *tot = B.totals + sr * B.b;
+        int *off = B.off + sr * (B.b + 1);
+        int seg = (B.b + 1023) / 1024;
+        int lo = tid * seg, hi = lo + seg < B.b ? lo + seg : B.b;
+        long long s = 0;
+        for (int i = lo; i < hi; ++i) s += tot[i];
+        part[tid] = s;
+        __syncthreads();
+        if (tid == 0) {
+            long long run = 0;
+            for (int i = 0; i < 1024; ++i) {
+                long long v = part[i];
+                part[i] = run;
+                run += v;
+            }
+            off[B.b] = (int)run;
+        }
+        __syncthreads();
+        long long run = part[tid];
+        for (int i = lo; i < hi; ++i) {
+            off[i] = (int)run;
+            run += tot[i];
+        }
+        __syncthreads();
+    }
+    // blocks in (round, bucket) order: value offsets (nx * ny) and 64 x 64 build tiles
+    const int nb = B.R * B.b;
+    int seg = (nb + 1023) / 1024;
+    int lo = tid * seg, hi = lo + seg < nb ? lo + seg : nb;
+    long long s = 0, s2 = 0;
+    for (int i = lo; i < hi; ++i) {
+        long long nx = B.totals[i];
+        long long ny = B.totals[B.R * B.b + i];
+        s += nx * ny;
+        s2 += ((nx + 63) / 64) * ((ny + 63) / 64);
+    }
+    part[tid] = s;
+    part2[tid] = s2;
+    __syncthreads();
+    if (tid == 0) {
+        long long run = 0, run2 = 0;
+        for (int i = 0; i < 1024; ++i) {
+            long long v = part[i], v2 = part2[i];
+            part[i] = run;
+            part2[i] = run2;
+            run += v;
+            run2 += v2;
+        }
+        B.val_off[nb] = run;
+        B.tile_off[nb] = (int)run2;
+        B.totals_out[0] = run;
+        B.totals_out[1] = run2;
+    }
+    __syncthreads();
+    long long run = part[tid], run2 = part2[tid];
+    for (int i = lo; i < hi; ++i) {
+        long long nx = B.totals[i];
+        long long ny = B.totals[B.R * B.b + i];
+        B.val_off[i] = run;
+        B.tile_off[i] = (int)run2;
+        run += nx * ny;
+        run2 += ((nx + 63) / 64) * ((ny + 63) / 64);
+    }
+}
+
+// grid: (chunks, R, 2), one wavefront per chunk
+__global__ __launch_bounds__(64) void sort_scatter_kernel(SortBuffers B)
+{
+    extern __shared__ int running[];
+    const int chunk = blockIdx.x, r = blockIdx.y, side = blockIdx.z;
+    const long long cnt = side_count(B, side);
+    const long long base = (long long)chunk * CH;
+    if (base >= cnt) return;
+    const int lane = threadIdx.x;
+    const int sr = side * B.R + r;
+    const int *pre = B.hist + ((long long)sr * B.chunks + chunk) * B.b;
+    const int *off = B.off + sr * (B.b + 1);
+    for (int t = lane; t < B.b; t += 64) running[t] = off[t] + pre[t];
+    __syncthreads();
+    const int32_t *bk = B.bucket + (long long)r * (B.n + B.m) + (side ? B.n : 0);
+    int *perm = B.perm + (side ? (long long)B.R * B.n + (long long)r * B.m : (long long)r * B.n);
+    int *pos = B.pos + (side ? (long long)B.R * B.n + (long long)r * B.m : (long long)r * B.n);
+    for (int step = 0; step < CH / 64; ++step) {
+        long long i = base + step * 64 + lane;
+        bool valid = i < cnt;
+        int key = valid ? bk[i] : -1;
+        int rank = 0, group = 0;
+        // rank of this lane among the lanes with the same key (lower lanes first)
+        bool pending = valid;
+        while (true) {
+            unsigned long long todo = __ballot(pending);
+            if (todo == 0ull) break;
+            int leader = __ffsll((long long)todo) - 1;
+            int k0 = __shfl(key, leader, 64);
+            unsigned long long same = __ballot(pending && key == k0);
+            if (pending && key == k0) {
+                rank = __popcll(same & ((1ull << lane) - 1ull));
+                group = __popcll(same);
+                pending = false;
+            }
+        }
+        int dst = 0;
+        if (valid) dst = running[key] + rank;
+        __syncthreads();
+        if (valid && rank == group - 1) running[key] += group;  // one lane per key
+        __syncthreads();
+        if (valid) {
+            perm[dst] = (int)i;
+            pos[i] = dst;
+        }
+    }
+}
+
+// per (round, row): where the row's values and its slice of the input vector start
+__global__ void rowinfo_kernel(SortBuffers B)
+{
+    const int r = blockIdx.y, side = blockIdx.z;
+    const long long cnt = side_count(B, side);
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    const long long other = side ? B.n : B.m;
+    const int32_t *bk = B.bucket + (long long)r * (B.n + B.m) + (side ? B.n : 0);
+    const int beta = bk[i];
+    const int *off_me = B.off + (side * B.R + r) * (B.b + 1);
+    const int *off_ot = B.off + ((1 - side) * B.R + r) * (B.b + 1);
+    const int *pos = B.pos + (side ? (long long)B.R * B.n + (long long)r * B.m : (long long)r * B.n);
+    const int len = off_ot[beta + 1] - off_ot[beta];
+    const int local = pos[i] - off_me[beta];
+    RowInfo ri;
+    ri.start = B.val_off[r * B.b + beta] + (long long)local * len;
+    ri.vstart = (int)((long long)r * other + off_ot[beta]);
+    ri.len = len;
+    (side ? B.rinfo_y : B.rinfo_x)[(long long)r * cnt + i] = ri;
+}
+
+hipError_t launch_bucket_sort(const SortBuffers &B, hipStream_t s)
+{
+    dim3 grid(B.chunks, B.R, 2);
+    size_t lds = sizeof(int) * (size_t)B.b;
+    hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(256), lds, s, B);
+    int t = 2 * B.R * B.b;
+    hipLaunchKernelGGL(sort_chunk_prefix_kernel, dim3((t + 127) / 128), dim3(128), 0, s, B);
+    hipLaunchKernelGGL(sort_offsets_kernel, dim3(1), dim3(1024), 0, s, B);
+    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(64), lds, s, B);
+    long long mx = B.n > B.m ? B.n : B.m;
+    hipLaunchKernelGGL(rowinfo_kernel, dim3((unsigned)((mx + 255) / 256), B.R, 2), dim3(256), 0, s, B);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------- CSR export --
+//
+// Row i of the pattern is the union over rounds of the Y members of the
+// bucket x_i fell into; a pair that an earlier round already holds is
+// skipped.  Members of a bucket are in ascending index order (stable sort),
+// so the union is an R-way merge of ascending lists.
+
+__device__ inline bool owned_by_earlier_round(const int32_t *bucket, long long N, long long n, int r, long long i,
+                                              int j)
+{
+    for (int q = 0; q < r; ++q)
+        if (bucket[(long long)q * N + i] == bucket[(long long)q * N + n + j]) return true;
+    return false;
+}
+
+template <bool FILL>
+__global__ void csr_kernel(SortBuffers B, const float *tiles, long long *rowcount, const long long *rowptr,
+                           int32_t *colidx, float *val)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B.n) return;
+    const long long N = B.n + B.m;
+    int head[8];
+    for (int r = 0; r < B.R; ++r) head[r] = 0;
+    long long outp = FILL ? rowptr[i] : 0;
+    long long cnt = 0;
+    while (true) {
+        int bestj = 0x7fffffff, bestr = -1;
+        for (int r = 0; r < B.R; ++r) {
+            const RowInfo ri = B.rinfo_x[(long long)r * B.n + i];
+            const int *yperm = B.perm + (long long)B.R * B.n + (long long)r * B.m;
+            const int seg0 = ri.vstart - (int)((long long)r * B.m);
+            // skip entries an earlier round owns
+            while (head[r] < ri.len &&
+                   owned_by_earlier_round(B.bucket, N, B.n, r, i, yperm[seg0 + head[r]]))
+                ++head[r];
+            if (head[r] < ri.len) {
+                int j = yperm[seg0 + head[r]];
+                if (j < bestj) {
+                    bestj = j;
+                    bestr = r;
+                }
+            }
+        }
+        if (bestr < 0) break;
+        if (FILL) {
+            const RowInfo ri = B.rinfo_x[(long long)bestr * B.n + i];
+            colidx[outp] = bestj;
+            if (val) val[outp] = tiles[ri.start + head[bestr]];
+            ++outp;
+        }
+        ++cnt;
+        ++head[bestr];
+    }
+    if (!FILL) rowcount[i] = cnt;
+}
+
+hipError_t launch_csr_count(const Handle &h, long long *rowcount, hipStream_t s)
+{
+    hipLaunchKernelGGL(csr_kernel<false>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.tiles,
+                       rowcount, (const long long *)nullptr, (int32_t *)nullptr, (float *)nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_csr_fill(const Handle &h, const long long *rowptr, int32_t *colidx, float *val, hipStream_t s)
+{
+    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.tiles,
+                       (long long *)nullptr, rowptr, colidx, val);
+    return hipGetLastError();
+}
+
+// in-place exclusive scan of n int64 values by one block; data[n] receives the total
+__global__ __launch_bounds__(1024) void scan_i64_kernel(long long *data, long long n)
+{
+    __shared__ long long part[1024];
+    const int tid = threadIdx.x;
+    long long seg = (n + 1023) / 1024;
+    long long lo = tid * seg, hi = lo + seg < n ? lo + seg : n;
+    long long s = 0;
+    for (long long i = lo; i < hi; ++i) s += data[i];
+    part[tid] = s;
+    __syncthreads();
+    if (tid == 0) {
+        long long run = 0;
+        for (int i = 0; i < 1024; ++i) {
+            long long v = part[i];
+            part[i] = run;
+            run += v;
+        }
+        data[n] = run;
+    }
+    __syncthreads();
+    long long run = part[tid];
+    for (long long i = lo; i < hi; ++i) {
+        long long v = data[i];
+        data[i] = run;
+        run += v;
+    }
+}
+
+hipError_t launch_scan_i64(long long *data, long long n, hipStream_t s)
+{
+    hipLaunchKernelGGL(scan_i64_kernel, dim3(1), dim3(1024), 0, s, data, n);
+    return hipGetLastError();
+}
+
+}  // namespace lcn

@@ -1,0 +1,584 @@
+// Host side of the C ABI declared in include/lcn.h: argument checks, the
+// workspace layout, and the order in which the build and iteration kernels are
+// enqueued.  No arithmetic of the method happens on the host except the choice
+// of the k-means start indices (integer only).
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+#include "lcn_internal.h"
+
+using namespace lcn;
+
+namespace {
+
+// ---------------------------------------------------------------- helpers --
+
+struct Bump {
+    char *base;
+    size_t cap, used;
+    bool dry;
+    template <class T>
+    T *take(size_t count)
+    {
+        size_t bytes = (count * sizeof(T) + 255) & ~(size_t)255;
+        size_t at = used;
+        used += bytes;
+        if (dry || used > cap) return nullptr;
+        return (T *)(base + at);
+    }
+};
+
+uint64_t splitmix64(uint64_t &state)
+{
+    uint64_t z = (state += 0x9E3779B97F4A7C15ULL);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+// The first k slots of a Fisher-Yates shuffle of 0..N-1 driven by splitmix64,
+// step t swapping slot t with slot t + next() mod (N - t); only touched slots
+// are stored.
+std::vector<long long> seeded_indices(uint64_t seed, long long N, int k)
+{
+    std::unordered_map<long long, long long> moved;
+    auto at = [&](long long i) {
+        auto it = moved.find(i);
+        return it == moved.end() ? i : it->second;
+    };
+    std::vector<long long> idx((size_t)k);
+    uint64_t s = seed;
+    for (int t = 0; t < k; ++t) {
+        long long j = t + (long long)(splitmix64(s) % (uint64_t)(N - t));
+        long long vt = at(t), vj = at(j);
+        moved[t] = vj;
+        moved[j] = vt;
+        idx[(size_t)t] = vj;
+    }
+    return idx;
+}
+
+bool uses_landmarks(int mode) { return mode == LCN_MODE_NYSTROM || mode == LCN_MODE_LCN; }
+bool uses_lsh(int mode) { return mode == LCN_MODE_SPARSE || mode == LCN_MODE_LCN; }
+
+struct Scratch {  // build-only buffers
+    long long *idx;
+    float *cent;
+    long long *sums, *counts;
+    int32_t *assign;
+    double *Vt64, *A64, *Lt, *Li, *Ainv, *ln;
+    int *fail_flag;
+    long long *totals;
+};
+
+// Lays out everything except the sparse values.  With bump.dry only sizes are
+// computed.
+void layout(Handle &h, Bump &bump, Scratch &sc)
+{
+    const long long N = h.n + h.m;
+    const int kmax = h.l > h.b ? h.l : h.b;
+    h.Z = bump.take<float>((size_t)N * h.d);
+    h.zn = bump.take<double>((size_t)N);
+    h.a = bump.take<float>((size_t)h.n);
+    h.b_marg = bump.take<float>((size_t)h.m);
+    h.counters = bump.take<unsigned long long>(8);
+    h.done_counter = bump.take<unsigned>(4);
+    h.query_out = bump.take<double>(4);
+    sc.fail_flag = bump.take<int>(4);
+    sc.totals = bump.take<long long>(4);
+    h.L = bump.take<float>((size_t)(h.l > 0 ? h.l : 1) * h.d);
+    sc.idx = bump.take<long long>((size_t)kmax);
+    sc.cent = bump.take<float>((size_t)kmax * h.d);
+    sc.sums = bump.take<long long>((size_t)kmax * h.d);
+    sc.counts = bump.take<long long>((size_t)kmax);
+    sc.assign = bump.take<int32_t>((size_t)N);
+    h.bucket = bump.take<int32_t>((size_t)(h.R > 0 ? h.R : 1) * N);
+
+    SortBuffers &B = h.sort;
+    B.R = h.R;
+    B.b = h.b;
+    B.n = h.n;
+    B.m = h.m;
+    B.bucket = h.bucket;
+    B.chunks = sort_chunks(h.n, h.m);
+    const size_t Rb = (size_t)(h.R > 0 ? h.R : 1) * h.b;
+    B.hist = bump.take<int>(2 * Rb * B.chunks);
+    B.totals = bump.take<int>(2 * Rb);
+    B.off = bump.take<int>(2 * (size_t)(h.R > 0 ? h.R : 1) * (h.b + 1));
+    B.perm = bump.take<int>((size_t)(h.R > 0 ? h.R : 1) * N);
+    B.pos = bump.take<int>((size_t)(h.R > 0 ? h.R : 1) * N);
+    B.val_off = bump.take<long long>(Rb + 1);
+    B.tile_off = bump.take<int>(Rb + 1);
+    B.totals_out = sc.totals;
+    B.rinfo_x = bump.take<RowInfo>((size_t)(h.R > 0 ? h.R : 1) * h.n);
+    B.rinfo_y = bump.take<RowInfo>((size_t)(h.R > 0 ? h.R : 1) * h.m);
+
+    const size_t lp1 = h.lp > 0 ? h.lp : 1;
+    h.U = bump.take<float>((size_t)h.n * lp1);
+    h.Wt = bump.take<float>((size_t)h.m * lp1);
+    const size_t l1 = h.l > 0 ? h.l : 1;
+    sc.Vt64 = bump.take<double>((size_t)h.m * l1);
+    sc.A64 = bump.take<double>(l1 * l1);
+    sc.Lt = bump.take<double>(l1 * l1);
+    sc.Li = bump.take<double>(l1 * l1);
+    sc.Ainv = bump.take<double>(l1 * l1);
+    sc.ln = bump.take<double>(l1);
+
+    h.log_u = bump.take<float>((size_t)h.n);
+    h.log_v = bump.take<float>((size_t)h.m);
+    h.lin_u = bump.take<double>((size_t)h.n);
+    h.lin_v = bump.take<double>((size_t)h.m);
+    h.perm_u = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.n);
+    h.perm_v = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.m);
+    h.acc_y = bump.take<double>(lp1);
+    h.acc_z = bump.take<double>(lp1);
+    h.grid = pass_grid(h);
+    h.partial = bump.take<double>((size_t)h.grid * (h.lp + 2));
+}
+
+lcn_status check_params(long long n, long long m, int d, int dtype, float lambda, int cost, int mode,
+                        const lcn_landmark_params *lm, const lcn_lsh_params *lsh)
+{
+    if (n < 1 || m < 1 || d < 1) return LCN_ERR_INVALID_ARG;
+    if (n > (1ll << 30) || m > (1ll << 30) || d > 65536) return LCN_ERR_INVALID_ARG;
+    if (dtype != LCN_F32 && dtype != LCN_BF16) return LCN_ERR_INVALID_ARG;
+    if (!(lambda > 0.f) || !(lambda < INFINITY)) return LCN_ERR_INVALID_ARG;
+    if (cost < LCN_COST_SQEUCLID || cost > LCN_COST_COSINE) return LCN_ERR_INVALID_ARG;
+    if (mode < LCN_MODE_DENSE || mode > LCN_MODE_LCN) return LCN_ERR_INVALID_ARG;
+    bool kmeans = false;
+    if (uses_landmarks(mode)) {
+        if (!lm) return LCN_ERR_INVALID_ARG;
+        if (lm->num_landmarks < 1 || lm->num_landmarks > 512 || lm->num_landmarks > n + m) return LCN_ERR_INVALID_ARG;
+        if (lm->kmeans_iters < 1) return LCN_ERR_INVALID_ARG;
+        if (!(lm->ridge >= 0.0)) return LCN_ERR_INVALID_ARG;
+        kmeans = true;
+    }
+    if (uses_lsh(mode)) {
+        if (!lsh) return LCN_ERR_INVALID_ARG;
+        if (lsh->num_buckets < 1 || lsh->num_buckets > 4096) return LCN_ERR_INVALID_ARG;
+        if (lsh->num_rounds < 1 || lsh->num_rounds > 8) return LCN_ERR_INVALID_ARG;
+        if (lsh->hash == LCN_HASH_KMEANS) {
+            if (lsh->kmeans_iters < 1 || lsh->num_buckets > n + m) return LCN_ERR_INVALID_ARG;
+            kmeans = true;
+        } else if (lsh->hash == LCN_HASH_CROSSPOLYTOPE) {
+            if ((lsh->num_buckets & 1) || !lsh->projections) return LCN_ERR_INVALID_ARG;
+        } else {
+            return LCN_ERR_INVALID_ARG;
+        }
+    }
+    if (kmeans && n + m > (1ll << 20)) return LCN_ERR_INVALID_ARG;
+    return LCN_OK;
+}
+
+void fill_shape(Handle &h, long long n, long long m, int d, int mode, const lcn_landmark_params *lm,
+                const lcn_lsh_params *lsh)
+{
+    h.n = n;
+    h.m = m;
+    h.d = d;
+    h.mode = mode;
+    h.l = uses_landmarks(mode) ? lm->num_landmarks : 0;
+    h.lp = (h.l + 63) / 64 * 64;
+    if (uses_lsh(mode)) {
+        h.R = lsh->num_rounds;
+        h.b = lsh->num_buckets;
+        h.hash = lsh->hash;
+    } else if (mode == LCN_MODE_DENSE) {  // the dense kernel is the single-bucket sparse kernel
+        h.R = 1;
+        h.b = 1;
+        h.hash = -1;
+    } else {
+        h.R = 0;
+        h.b = 1;
+        h.hash = -1;
+    }
+}
+
+#define HIPCHK(expr)                         \
+    do {                                     \
+        hipError_t e_ = (expr);              \
+        if (e_ != hipSuccess) {              \
+            (void)hipGetLastError();         \
+            return LCN_ERR_DEVICE;           \
+        }                                    \
+    } while (0)
+
+lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float *cent, int32_t *assign)
+{
+    const long long N = h.n + h.m;
+    std::vector<long long> idx = seeded_indices(seed, N, k);
+    HIPCHK(hipMemcpyAsync(sc.idx, idx.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
+    HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
+    for (int it = 0; it < T; ++it) {
+        HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, h.stream));
+        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.sums, sc.counts, cent, h.stream));
+    }
+    return LCN_OK;
+}
+
+lcn_status status_from_counters(Handle &h)
+{
+    unsigned long long c[3];
+    HIPCHK(hipMemcpyAsync(c, h.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    if (c[0]) return LCN_ERR_NONPOSITIVE;
+    if (c[1] | c[2]) return LCN_WARN_NO_SUPPORT;
+    return LCN_OK;
+}
+
+bool valid(lcn_handle hh) { return hh && ((Handle *)hh)->magic == HANDLE_MAGIC; }
+
+}  // namespace
+
+extern "C" {
+
+lcn_status lcn_workspace_bytes(int64_t n, int64_t m, int32_t d, int32_t mode, const lcn_landmark_params *lm,
+                               const lcn_lsh_params *lsh, int64_t nnz_guess, size_t *bytes)
+{
+    if (!bytes) return LCN_ERR_INVALID_ARG;
+    lcn_status st = check_params(n, m, d, LCN_F32, 1.f, LCN_COST_SQEUCLID, mode, lm, lsh);
+    if (st != LCN_OK) return st;
+    Handle h{};
+    fill_shape(h, n, m, d, mode, lm, lsh);
+    Bump bump{nullptr, 0, 0, true};
+    Scratch sc{};
+    layout(h, bump, sc);
+    long long nnz = nnz_guess;
+    if (nnz <= 0) {
+        if (mode == LCN_MODE_DENSE)
+            nnz = n * m;
+        else if (h.R > 0)
+            nnz = (long long)(1.5 * (double)h.R * (double)n * (double)m / (double)h.b) + 4096;
+        else
+            nnz = 0;
+    }
+    bump.take<float>((size_t)nnz);
+    bump.take<float>((size_t)nnz);
+    *bytes = bump.used + 256;
+    return LCN_OK;
+}
+
+lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t d, int32_t dtype, const float *a,
+                     const float *b, float lambda, int32_t cost, int32_t mode, const lcn_landmark_params *lm,
+                     const lcn_lsh_params *lsh, void *workspace, size_t workspace_bytes, void *hip_stream,
+                     size_t *bytes_needed, lcn_handle *out)
+{
+    if (!out) return LCN_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!X || !Y || !a || !b || !workspace || ((uintptr_t)workspace & 255)) return LCN_ERR_INVALID_ARG;
+    lcn_status st = check_params(n, m, d, dtype, lambda, cost, mode, lm, lsh);
+    if (st != LCN_OK) return st;
+
+    Handle *hp = new (std::nothrow) Handle{};
+    if (!hp) return LCN_ERR_ALLOC;
+    Handle &h = *hp;
+    struct Guard {
+        Handle *p;
+        ~Guard()
+        {
+            if (p) {
+                if (p->ev0) (void)hipEventDestroy(p->ev0);
+                if (p->ev1) (void)hipEventDestroy(p->ev1);
+                delete p;
+            }
+        }
+    } guard{hp};
+
+    fill_shape(h, n, m, d, mode, lm, lsh);
+    h.cost = cost;
+    h.lambda = (double)lambda;
+    h.ridge = uses_landmarks(mode) ? lm->ridge : 0.0;
+    h.stream = (hipStream_t)hip_stream;
+    h.ws = (char *)workspace;
+    h.ws_bytes = workspace_bytes;
+    const long long N = n + m;
+
+    Bump bump{h.ws, workspace_bytes, 0, false};
+    Scratch sc{};
+    layout(h, bump, sc);
+    if (bump.used > workspace_bytes) {
+        if (bytes_needed) lcn_workspace_bytes(n, m, d, mode, lm, lsh, 0, bytes_needed);
+        return LCN_ERR_ALLOC;
+    }
+
+    HIPCHK(hipEventCreate(&h.ev0));
+    HIPCHK(hipEventCreate(&h.ev1));
+    HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
+    HIPCHK(hipMemsetAsync(h.done_counter, 0, 4 * sizeof(unsigned), h.stream));
+    HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
+    HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
+    HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
+    HIPCHK(hipMemcpyAsync(h.b_marg, b, sizeof(float) * (size_t)m, hipMemcpyDeviceToDevice, h.stream));
+    HIPCHK(launch_convert(X, n, Y, m, d, dtype, h.Z, (unsigned *)(h.counters + 4), h.stream));
+    if (cost == LCN_COST_COSINE) HIPCHK(launch_sqnorms(h.Z, N, d, h.zn, h.stream));
+
+    // landmarks: centroids of k-means on X u Y (Sec. 4)
+    if (h.l > 0) {
+        st = run_kmeans(h, sc, h.l, lm->kmeans_iters, lm->seed, h.L, sc.assign);
+        if (st != LCN_OK) return st;
+    }
+    // hash rounds (Sec. 3)
+    if (uses_lsh(mode)) {
+        for (int r = 0; r < h.R; ++r) {
+            int32_t *dst = h.bucket + (long long)r * N;
+            if (h.hash == LCN_HASH_KMEANS) {
+                st = run_kmeans(h, sc, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, sc.cent, dst);
+                if (st != LCN_OK) return st;
+            } else {
+                const float *Rm = lsh->projections + (long long)r * d * (h.b / 2);
+                HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, h.b, dst, h.stream));
+            }
+        }
+    } else if (mode == LCN_MODE_DENSE) {
+        HIPCHK(hipMemsetAsync(h.bucket, 0, sizeof(int32_t) * (size_t)N, h.stream));
+    }
+    long long totals[2] = {0, 0};
+    unsigned long long range_flag = 0;
+    if (h.R > 0) {
+        HIPCHK(launch_bucket_sort(h.sort, h.stream));
+        HIPCHK(hipMemcpyAsync(totals, sc.totals, sizeof(totals), hipMemcpyDeviceToHost, h.stream));
+    }
+    HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
+    h.nnz_stored = totals[0];
+    h.ntiles = (int)totals[1];
+
+    h.tiles = bump.take<float>((size_t)h.nnz_stored);
+    h.tilesT = bump.take<float>((size_t)h.nnz_stored);
+    h.ws_used = bump.used;
+    if (bytes_needed) *bytes_needed = bump.used + 256;
+    if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;
+
+    // Nystrom factors (Sec. 4; App. "Implementational details")
+    if (h.l > 0) {
+        const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
+        const bool cosn = cost == LCN_COST_COSINE;
+        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, h.stream));
+        HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, h.stream));
+        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, h.stream));
+        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
+                                    h.U, nullptr, h.lp, h.stream));
+        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, h.stream));
+        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, h.stream));
+        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.fail_flag, h.stream));
+        // W^T = V^T A^{-1} (A^{-1} is symmetric)
+        HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, h.stream));
+    }
+    // sparse values per bucket block (Sec. 3 / Sec. 4)
+    if (h.R > 0) HIPCHK(launch_correction(h, h.ntiles, h.stream));
+
+    // scalings start at 1 (eq. 2)
+    HIPCHK(hipMemsetAsync(h.log_u, 0, sizeof(float) * (size_t)n, h.stream));
+    HIPCHK(hipMemsetAsync(h.log_v, 0, sizeof(float) * (size_t)m, h.stream));
+    HIPCHK(launch_pass(h, 0, PASS_INIT, nullptr, h.stream));
+    HIPCHK(launch_pass(h, 1, PASS_INIT, nullptr, h.stream));
+
+    int fail = 0;
+    unsigned long long uniq = 0;
+    HIPCHK(hipMemcpyAsync(&fail, sc.fail_flag, sizeof(int), hipMemcpyDeviceToHost, h.stream));
+    HIPCHK(hipMemcpyAsync(&uniq, h.counters + 3, sizeof(uniq), hipMemcpyDeviceToHost, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    if (fail) return LCN_ERR_SINGULAR;
+    h.nnz_unique = (long long)uniq;
+
+    h.magic = HANDLE_MAGIC;
+    guard.p = nullptr;
+    *out = (lcn_handle)hp;
+    return LCN_OK;
+}
+
+lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    if (iters < 0) return LCN_ERR_INVALID_ARG;
+    Handle &h = *(Handle *)hh;
+    HIPCHK(hipEventRecord(h.ev0, h.stream));
+    for (int it = 0; it < iters; ++it) {
+        HIPCHK(launch_pass(h, 0, PASS_UPDATE, nullptr, h.stream));
+        HIPCHK(launch_pass(h, 1, PASS_UPDATE, nullptr, h.stream));
+    }
+    HIPCHK(hipEventRecord(h.ev1, h.stream));
+    lcn_status st = status_from_counters(h);
+    if (st == LCN_ERR_DEVICE) return st;
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, h.ev0, h.ev1));
+    h.last_ms = ms;
+    h.last_launches = 2 * iters;
+    return st;
+}
+
+static lcn_status query(Handle &h, float *row_dev, float *col_dev, double q[4])
+{
+    HIPCHK(launch_pass(h, 0, PASS_QUERY, row_dev, h.stream));
+    HIPCHK(launch_pass(h, 1, PASS_QUERY, col_dev, h.stream));
+    HIPCHK(hipMemcpyAsync(q, h.query_out, 4 * sizeof(double), hipMemcpyDeviceToHost, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status transport_cost(lcn_handle hh, double *d_host)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    if (!d_host) return LCN_ERR_INVALID_ARG;
+    Handle &h = *(Handle *)hh;
+    double q[4];
+    lcn_status st = query(h, nullptr, nullptr, q);
+    if (st != LCN_OK) return st;
+    *d_host = h.lambda * (q[0] + q[2]);
+    return LCN_OK;
+}
+
+lcn_status plan_marginals(lcn_handle hh, float *row_dev, float *col_dev, double *l1_residual_host)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    double q[4];
+    lcn_status st = query(h, row_dev, col_dev, q);
+    if (st != LCN_OK) return st;
+    if (l1_residual_host) *l1_residual_host = q[1] + q[3];
+    return LCN_OK;
+}
+
+lcn_status lcn_get_scalings(lcn_handle hh, float *log_u_dev, float *log_v_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if (log_u_dev)
+        HIPCHK(hipMemcpyAsync(log_u_dev, h.log_u, sizeof(float) * (size_t)h.n, hipMemcpyDeviceToDevice, h.stream));
+    if (log_v_dev)
+        HIPCHK(hipMemcpyAsync(log_v_dev, h.log_v, sizeof(float) * (size_t)h.m, hipMemcpyDeviceToDevice, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status lcn_set_scalings(lcn_handle hh, const float *log_u_dev, const float *log_v_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    if (!log_u_dev || !log_v_dev) return LCN_ERR_INVALID_ARG;
+    Handle &h = *(Handle *)hh;
+    HIPCHK(hipMemcpyAsync(h.log_u, log_u_dev, sizeof(float) * (size_t)h.n, hipMemcpyDeviceToDevice, h.stream));
+    HIPCHK(hipMemcpyAsync(h.log_v, log_v_dev, sizeof(float) * (size_t)h.m, hipMemcpyDeviceToDevice, h.stream));
+    HIPCHK(launch_pass(h, 0, PASS_INIT, nullptr, h.stream));
+    HIPCHK(launch_pass(h, 1, PASS_INIT, nullptr, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status lcn_get_landmarks(lcn_handle hh, float *L_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if (h.l == 0) return LCN_ERR_STATE;
+    if (!L_dev) return LCN_ERR_INVALID_ARG;
+    HIPCHK(hipMemcpyAsync(L_dev, h.L, sizeof(float) * (size_t)h.l * h.d, hipMemcpyDeviceToDevice, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status lcn_get_buckets(lcn_handle hh, int32_t *bucket_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if (h.R == 0) return LCN_ERR_STATE;
+    if (!bucket_dev) return LCN_ERR_INVALID_ARG;
+    HIPCHK(hipMemcpyAsync(bucket_dev, h.bucket, sizeof(int32_t) * (size_t)h.R * (h.n + h.m), hipMemcpyDeviceToDevice,
+                          h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status lcn_get_csr(lcn_handle hh, int64_t *nnz_host, int64_t *rowptr_dev, int32_t *colidx_dev, float *val_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if (h.R == 0) return LCN_ERR_STATE;
+    if (!rowptr_dev) return LCN_ERR_INVALID_ARG;
+    HIPCHK(launch_csr_count(h, (long long *)rowptr_dev, h.stream));
+    HIPCHK(launch_scan_i64((long long *)rowptr_dev, h.n, h.stream));
+    long long total = 0;
+    HIPCHK(hipMemcpyAsync(&total, rowptr_dev + h.n, sizeof(long long), hipMemcpyDeviceToHost, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    if (nnz_host) *nnz_host = total;
+    if (colidx_dev) {
+        HIPCHK(launch_csr_fill(h, (const long long *)rowptr_dev, colidx_dev, val_dev, h.stream));
+        HIPCHK(hipStreamSynchronize(h.stream));
+    }
+    return LCN_OK;
+}
+
+lcn_status lcn_get_factors(lcn_handle hh, float *U_dev, float *Wt_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if (h.l == 0) return LCN_ERR_STATE;
+    const size_t w = sizeof(float) * (size_t)h.l, pitch = sizeof(float) * (size_t)h.lp;
+    if (U_dev) HIPCHK(hipMemcpy2DAsync(U_dev, w, h.U, pitch, w, (size_t)h.n, hipMemcpyDeviceToDevice, h.stream));
+    if (Wt_dev) HIPCHK(hipMemcpy2DAsync(Wt_dev, w, h.Wt, pitch, w, (size_t)h.m, hipMemcpyDeviceToDevice, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status lcn_get_info(lcn_handle hh, lcn_info *info)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    if (!info) return LCN_ERR_INVALID_ARG;
+    Handle &h = *(Handle *)hh;
+    unsigned long long c[3];
+    HIPCHK(hipMemcpyAsync(c, h.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    info->n = h.n;
+    info->m = h.m;
+    info->d = h.d;
+    info->l = h.l;
+    info->rounds = h.R;
+    info->buckets = h.b;
+    info->nnz_stored = h.nnz_stored;
+    info->nnz_unique = h.nnz_unique;
+    info->nonpositive = (int64_t)c[0];
+    info->empty_rows = (int64_t)c[1];
+    info->empty_cols = (int64_t)c[2];
+    info->workspace_used = h.ws_used;
+    return LCN_OK;
+}
+
+lcn_status lcn_last_run_timing(lcn_handle hh, float *ms_host, int32_t *launches_host)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if (ms_host) *ms_host = h.last_ms;
+    if (launches_host) *launches_host = h.last_launches;
+    return LCN_OK;
+}
+
+void lcn_destroy(lcn_handle hh)
+{
+    if (!valid(hh)) return;
+    Handle *h = (Handle *)hh;
+    (void)hipStreamSynchronize(h->stream);
+    (void)hipEventDestroy(h->ev0);
+    (void)hipEventDestroy(h->ev1);
+    h->magic = 0;
+    delete h;
+}
+
+const char *lcn_status_string(int32_t status)
+{
+    switch (status) {
+        case LCN_OK: return "ok";
+        case LCN_ERR_INVALID_ARG: return "invalid argument";
+        case LCN_ERR_ALLOC: return "workspace too small";
+        case LCN_ERR_DEVICE: return "HIP error";
+        case LCN_ERR_STATE: return "bad handle or call not available in this mode";
+        case LCN_ERR_SINGULAR: return "landmark kernel matrix is not positive definite";
+        case LCN_ERR_NONPOSITIVE: return "non-positive kernel-vector product";
+        case LCN_WARN_NO_SUPPORT: return "sparse kernel has rows or columns without entries";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,138 @@
+// Internal declarations shared by the HIP translation units of the LCN-Sinkhorn
+// library.  Nothing here is part of the public ABI (see include/lcn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lcn.h"
+
+namespace lcn {
+
+// One row (or column) of the sparse part in one hash round: its values are
+// `len` consecutive floats starting at `start` in the tile array, and they
+// multiply `len` consecutive entries of the permuted input vector starting at
+// `vstart`.
+struct RowInfo {
+    long long start;
+    int vstart;
+    int len;
+};
+
+// Everything the half-iteration kernel needs for one side (rows of U with the
+// row-major tiles, or rows of W^T with the transposed tiles).
+struct PassSide {
+    long long rows;         // n or m
+    const float *F;         // rows x lp factor (U or W^T), zero padded to lp
+    const float *tiles;     // sparse values laid out so that this side's rows are contiguous
+    const RowInfo *rinfo;   // [R][rows]
+    const int *pos;         // [R][rows] position of the row in its round's bucket order
+    const float *marg;      // a or b
+    float *log_out;         // log u or log v (fp32 state that is reported)
+    double *lin_out;        // u or v, linear, by original index
+    double *perm_out;       // [R][rows] u or v in bucket order of each round
+    const double *perm_in;  // [R][other] the other side's scaling in bucket order
+    const double *acc_in;   // lp: y = W v (for rows of U) or z = U^T u (for rows of W^T)
+    double *acc_out;        // lp: accumulated F^T out
+    float *marg_out;        // query mode: plan marginal of each row (nullable)
+};
+
+enum PassMode { PASS_UPDATE = 0, PASS_QUERY = 1, PASS_INIT = 2 };
+
+struct Handle;
+
+// ---- structure build (kernels_structure.hip) -------------------------------
+hipError_t launch_convert(const void *X, long long n, const void *Y, long long m, int d, int dtype, float *Z,
+                          unsigned *range_flag, hipStream_t s);
+hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k, float *out, hipStream_t s);
+hipError_t launch_assign_kmeans(const float *Z, long long N, int d, const float *cent, int k, int32_t *out,
+                                hipStream_t s);
+hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
+                                       hipStream_t s);
+hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *sums,
+                                long long *counts, float *cent, hipStream_t s);
+
+struct SortBuffers {
+    int R, b;
+    long long n, m;
+    const int32_t *bucket;  // [R][n+m]
+    int *hist;              // scratch [2][R][chunks][b]
+    int chunks;             // max over sides
+    int *totals;            // [2][R][b]
+    int *off;               // [2][R][b+1]  (x side then y side)
+    int *perm;              // x: [R][n] then y: [R][m]
+    int *pos;               // x: [R][n] then y: [R][m]
+    long long *val_off;     // [R*b + 1] start of each block's tile in the value array
+    int *tile_off;          // [R*b + 1] start of each block in the list of 64x64 build tiles
+    long long *totals_out;  // [2]: nnz_stored, build tiles
+    RowInfo *rinfo_x;       // [R][n]
+    RowInfo *rinfo_y;       // [R][m]
+};
+hipError_t launch_bucket_sort(const SortBuffers &B, hipStream_t s);
+int sort_chunks(long long n, long long m);
+
+hipError_t launch_csr_count(const Handle &h, long long *rowcount, hipStream_t s);
+hipError_t launch_scan_i64(long long *data, long long n, hipStream_t s);  // in-place exclusive scan, data[n] = total
+hipError_t launch_csr_fill(const Handle &h, const long long *rowptr, int32_t *colidx, float *val, hipStream_t s);
+
+// ---- factor build (kernels_factors.hip) ------------------------------------
+hipError_t launch_sqnorms(const float *P, long long rows, int d, double *out, hipStream_t s);
+// out[i][k] = exp(-c(P_i, Q_k) / lambda); P: rows x d, Q: cols x d.  Writes fp32 (ld = ldo) and/or fp64.
+hipError_t launch_kernel_matrix(const float *P, long long rows, const float *Q, int cols, int d, int cost,
+                                double lambda, const double *pn, const double *qn, float *out32, double *out64,
+                                int ldo, hipStream_t s);
+hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lt, double *Lit, double *Ainv, int *fail_flag,
+                              hipStream_t s);
+// C (M x N, fp32, ld ldc) = A (M x K, fp64) * B (K x N, fp64)
+hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N, int K, float *C32, int ldc,
+                           hipStream_t s);
+hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s);
+
+// ---- iteration (kernels_iter.hip) ------------------------------------------
+hipError_t launch_pass(const Handle &h, int side, int mode, float *marg_out, hipStream_t s);
+int pass_grid(const Handle &h);
+
+struct Handle {
+    uint32_t magic;
+    long long n, m;
+    int d, l, lp, R, b;
+    int mode, cost, hash;
+    double lambda, ridge;
+    hipStream_t stream;
+    char *ws;
+    size_t ws_bytes, ws_used;
+
+    // inputs (copies)
+    float *Z;          // (n+m) x d fp32
+    double *zn;        // squared norms of the rows of Z (cosine cost)
+    float *a, *b_marg; // marginals
+    // structure
+    float *L;          // l x d landmarks
+    int32_t *bucket;   // [R][n+m]
+    SortBuffers sort;
+    long long nnz_stored, nnz_unique;
+    int ntiles;
+    // factors
+    float *U;          // n x lp
+    float *Wt;         // m x lp
+    float *tiles;      // row-major tiles (rows of X contiguous)
+    float *tilesT;     // transposed tiles (rows of Y contiguous)
+    // state
+    float *log_u, *log_v;
+    double *lin_u, *lin_v;
+    double *perm_u, *perm_v;   // [R][n], [R][m]
+    double *acc_y, *acc_z;     // lp each: y = W v, z = U^T u
+    double *partial;           // [grid][lp + 2]
+    double *query_out;         // [2 sides][2]: sum r log u, sum |r - a|
+    unsigned *done_counter;
+    unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag
+    int grid;
+
+    hipEvent_t ev0, ev1;
+    float last_ms;
+    int last_launches;
+};
+
+constexpr uint32_t HANDLE_MAGIC = 0x4C434E31u;  // "LCN1"
+
+}  // namespace lcn
