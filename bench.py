@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the LCN-Sinkhorn hot path on one MI355X.
+
+One step = one pass of the whole path on one synthetic problem already in HBM:
+lcn_build (landmarks, LSH buckets, bucket sort, Nystrom factors, sparse
+correction) + sinkhorn_run(iters) + transport_cost.  The headline value is
+Sinkhorn iterations per second inside sinkhorn_run (HIP events on the
+library's stream); build time and the whole step are reported beside it.
+
+Prints ONE JSON line.  See DESIGN.md ("Measurement") for the definitions of
+the roofline figures.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def make_problem(config: int):
+    import workloads
+    if config == 1:
+        return workloads.config1(), "C1 n=m=1024 d=16 sq-Euclid l=64 b=16x1 it=50"
+    if config == 2:
+        return workloads.config2(), "C2 n=m=10000 d=64 sq-Euclid l=128 b=64x2 it=100"
+    if config == 3:
+        return workloads.config3(), "C3 n=m=20000 d=300 cosine lambda=0.05 l=256 b=128x3 it=200"
+    if config == 5:
+        return workloads.config5(), "C5 n=m=200000 d=300 bf16-in cosine lambda=0.05 l=512 b=1024x3 it=200"
+    raise SystemExit("unknown --config %d" % config)
+
+
+def cpu_baseline(p, sample_iters: int):
+    """The oracle as it stands on the host cores: full build of the same
+    problem, then a few iterations."""
+    import oracle
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or os.cpu_count()
+    t0 = time.perf_counter()
+    B = oracle.build_problem(p.X, p.Y, p.cost, p.lam, "lcn", p.num_landmarks, p.landmark_seed, p.kmeans_iters,
+                             p.ridge, 0, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections)
+    t1 = time.perf_counter()
+    st = oracle.sinkhorn(B.op, p.a, p.b, sample_iters)
+    t2 = time.perf_counter()
+    _, _, dist, resid = oracle.marginals(B.op, p.a, p.b, p.lam, st)
+    return {
+        "value": sample_iters / (t2 - t1), "unit": "iterations/s", "cores": threads, "kind": "oracle",
+        "sample": "full oracle build of the same problem (%.1f s) then %d Sinkhorn iterations (%.2f s)"
+                  % (t1 - t0, sample_iters, t2 - t1),
+        "build_ms": 1e3 * (t1 - t0),
+    }, (st, dist, resid)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-iters", type=int, default=5)
+    ap.add_argument("--mode", default="lcn", choices=["lcn", "sparse", "nystrom", "dense"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+                         "--gpus %d is not supported" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import paper_2107_06876_amd as lcn
+    import workloads
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    p, wl = make_problem(args.config)
+    dev = "cuda:0"
+    dt = torch.bfloat16 if p.bf16_inputs else torch.float32
+    X = torch.from_numpy(p.X).to(dev).to(dt)
+    Y = torch.from_numpy(p.Y).to(dev).to(dt)
+    a = torch.from_numpy(p.a).to(dev)
+    b = torch.from_numpy(p.b).to(dev)
+    mode = {"lcn": lcn.MODE_LCN, "sparse": lcn.MODE_SPARSE, "nystrom": lcn.MODE_NYSTROM, "dense": lcn.MODE_DENSE}[args.mode]
+    lm = dict(num_landmarks=p.num_landmarks, kmeans_iters=p.kmeans_iters, seed=p.landmark_seed, ridge=p.ridge)
+    lsh = dict(hash=lcn.HASH_KMEANS, num_buckets=p.num_buckets, num_rounds=p.num_rounds,
+               kmeans_iters=p.kmeans_iters, seed=p.lsh_seed)
+    lm = lm if args.mode in ("lcn", "nystrom") else None
+    lsh = lsh if args.mode in ("lcn", "sparse") else None
+
+    # first build sizes the workspace; every later build reuses it (no allocation in the timed region)
+    h = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh)
+    ws = h.workspace
+    info = lcn.lcn_get_info(h)
+    nnz_stored, nnz_unique, l = info.nnz_stored, info.nnz_unique, info.l
+    lcn.lcn_destroy(h)
+
+    def step():
+        t0 = time.perf_counter()
+        hh = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh, workspace=ws)
+        t1 = time.perf_counter()          # lcn_build returns after its work has finished
+        lcn.sinkhorn_run(hh, p.iters)
+        ms, launches = lcn.lcn_last_run_timing(hh)
+        d = lcn.transport_cost(hh)
+        return hh, 1e3 * (t1 - t0), ms, launches, d
+
+    for _ in range(args.warmup):
+        hh, *_ = step()
+        lcn.lcn_destroy(hh)
+    torch.cuda.synchronize()
+    build_ms, run_ms, n_launch = [], [], 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        hh, bms, ms, launches, dist = step()
+        build_ms.append(bms)
+        run_ms.append(ms)
+        n_launch = launches
+        lcn.lcn_destroy(hh)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+    run_mean = float(np.mean(run_ms))
+    its_per_s = p.iters / (run_mean * 1e-3)
+
+    # roofline of the half-iteration kernel: algorithmic bytes per launch = half of
+    # 4 (n l + l m) + 2 * 4 * nnz  (each factor entry once, each sparse value twice per iteration)
+    bytes_iter = 4.0 * (p.n * l + l * p.m) + 8.0 * nnz_unique
+    bytes_launch = bytes_iter / 2.0
+    launch_us = run_mean * 1e3 / max(n_launch, 1)
+    achieved = bytes_launch / (launch_us * 1e-6) / 1e9
+    out = {
+        "metric": "LCN-Sinkhorn iterations/s (n=20k,d=300); build ms; % HBM peak; cost rel.err",
+        "value": its_per_s, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 storage, f64 accumulate", "data": "synthetic",
+        "config": {"workload": wl, "mode": args.mode, "iters": p.iters, "nnz_unique": nnz_unique,
+                   "nnz_stored": nnz_stored},
+        "build_ms": float(np.mean(build_ms)), "sinkhorn_ms": run_mean, "distance": dist,
+        "roofline": {"bound": "hbm", "kernel": "pass_kernel (one half-iteration)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": bytes_launch, "launch_us": launch_us},
+    }
+    if not args.no_cpu_baseline:
+        base, (st, dist_o, resid_o) = cpu_baseline(p, args.cpu_iters)
+        out["cpu_baseline"] = base
+        # parity of a short GPU run against the same oracle run (outside the timed region)
+        hh = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh, workspace=ws)
+        lcn.sinkhorn_run(hh, args.cpu_iters)
+        lu, lv = lcn.lcn_get_scalings(hh)
+        d5 = lcn.transport_cost(hh)
+        out["parity_vs_oracle"] = {
+            "iters": args.cpu_iters,
+            "max_abs_log_u": float(np.max(np.abs(lu.cpu().numpy() - st.log_u))),
+            "max_abs_log_v": float(np.max(np.abs(lv.cpu().numpy() - st.log_v))),
+            "cost_rel": abs(d5 - dist_o) / abs(dist_o)}
+        lcn.lcn_destroy(hh)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -45,12 +45,12 @@ __device__ inline double fast_rcp(double x)
 
 template <int T, int MODE>
 __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, int lp, double *partial,
-                                                            unsigned *done_counter, unsigned long long *counters,
-                                                            int empty_slot, double *query_out)
+                                                            double *zero_buf, int use_atomics,
+                                                            unsigned long long *counters, int empty_slot,
+                                                            double *query_out)
 {
     constexpr int TT = T > 0 ? T : 1;
     extern __shared__ double zsh[];  // [PASS_WAVES / 2][lp + 2]
-    __shared__ unsigned ticket_sh;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long long nwaves = (long long)gridDim.x * PASS_WAVES;
     const long long gw = (long long)blockIdx.x * PASS_WAVES + wave;
@@ -64,6 +64,9 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     }
     double q0 = 0.0, q1 = 0.0;
     unsigned long long nonpos = 0, empty = 0;
+    // the accumulator that the launch after this one adds into is cleared here
+    if (zero_buf && blockIdx.x == 0)
+        for (int k = threadIdx.x; k < lp; k += PASS_THREADS) zero_buf[k] = 0.0;
 
     for (long long row = gw; row < S.rows; row += nwaves) {
         float f[TT];
@@ -153,29 +156,46 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
         double s = 0.0;
 #pragma unroll
         for (int w = 0; w < HALF; ++w) s += zsh[w * stride + k];
-        partial[(long long)blockIdx.x * stride + k] = s;
+        if (use_atomics) {
+            if (k < lp) {
+                if (MODE != PASS_QUERY) unsafeAtomicAdd(&S.acc_out[k], s);
+            } else if (MODE == PASS_QUERY) {
+                unsafeAtomicAdd(&query_out[k - lp], s);
+            }
+        } else {
+            partial[(long long)blockIdx.x * stride + k] = s;
+        }
     }
     if (lane == 0 && (nonpos | empty)) {
         if (nonpos) atomicAdd(&counters[0], nonpos);
         if (empty) atomicAdd(&counters[empty_slot], empty);
     }
-    // the last workgroup to arrive adds the partials in workgroup order
-    __threadfence();
+}
+
+// Adds the per-workgroup partial sums of a sweep in workgroup order (so the
+// result does not depend on timing).  One workgroup per 64 entries.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const double *__restrict__ partial, int groups,
+                                                              int stride, int lp, double *acc_out, double *query_out,
+                                                              int is_query)
+{
+    __shared__ double sh[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = blockIdx.x * 64 + lane;
+    double s = 0.0;
+    if (k < stride) {
+#pragma unroll 8
+        for (int g = wave; g < groups; g += 4) s += partial[(long long)g * stride + k];
+    }
+    sh[wave][lane] = s;
     __syncthreads();
-    if (threadIdx.x == 0) ticket_sh = atomicAdd(done_counter, 1u);
-    __syncthreads();
-    if (ticket_sh != gridDim.x - 1) return;
-    __threadfence();
-    for (int k = threadIdx.x; k < stride; k += PASS_THREADS) {
-        double s = 0.0;
-        for (unsigned g = 0; g < gridDim.x; ++g) s += partial[(long long)g * stride + k];
+    if (wave == 0 && k < stride) {
+        s = (sh[0][lane] + sh[1][lane]) + (sh[2][lane] + sh[3][lane]);
         if (k < lp) {
-            if (MODE != PASS_QUERY) S.acc_out[k] = s;
-        } else if (MODE == PASS_QUERY) {
+            if (!is_query) acc_out[k] = s;
+        } else if (is_query) {
             query_out[k - lp] = s;
         }
     }
-    if (threadIdx.x == 0) *done_counter = 0u;
 }
 
 int pass_grid(const Handle &h)
@@ -186,7 +206,8 @@ int pass_grid(const Handle &h)
 }
 
 template <int T>
-static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, hipStream_t s)
+static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, double *zero_buf,
+                                hipStream_t s)
 {
     long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
     int grid = (int)(g < h.grid ? g : h.grid);
@@ -195,18 +216,25 @@ static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, in
     int empty_slot = 1 + side;
     if (mode == PASS_UPDATE)
         hipLaunchKernelGGL((pass_kernel<T, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, h.done_counter, h.counters, empty_slot, qout);
+                           h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
     else if (mode == PASS_QUERY)
         hipLaunchKernelGGL((pass_kernel<T, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, h.done_counter, h.counters, empty_slot, qout);
+                           h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
     else
         hipLaunchKernelGGL((pass_kernel<T, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, h.done_counter, h.counters, empty_slot, qout);
+                           h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
+    if (!h.use_atomics) {
+        const int stride = h.lp + 2;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(256), 0, s, h.partial, grid, stride,
+                           h.lp, S.acc_out, qout, mode == PASS_QUERY ? 1 : 0);
+    }
     return hipGetLastError();
 }
 
-// side 0: rows of X (updates u, consumes y, produces z); side 1: rows of Y
-hipError_t launch_pass(const Handle &h, int side, int mode, float *marg_out, hipStream_t s)
+// side 0: rows of X (updates u, consumes y = W v, produces z = U^T u); side 1: rows of Y.
+// acc_in / acc_out / acc_zero index the three rotating accumulator buffers (-1: none).
+hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, int acc_zero, float *marg_out,
+                       hipStream_t s)
 {
     PassSide S;
     if (side == 0) {
@@ -220,8 +248,6 @@ hipError_t launch_pass(const Handle &h, int side, int mode, float *marg_out, hip
         S.lin_out = h.lin_u;
         S.perm_out = h.perm_u;
         S.perm_in = h.perm_v;
-        S.acc_in = h.acc_y;
-        S.acc_out = h.acc_z;
     } else {
         S.rows = h.m;
         S.F = h.Wt;
@@ -233,20 +259,21 @@ hipError_t launch_pass(const Handle &h, int side, int mode, float *marg_out, hip
         S.lin_out = h.lin_v;
         S.perm_out = h.perm_v;
         S.perm_in = h.perm_u;
-        S.acc_in = h.acc_z;
-        S.acc_out = h.acc_y;
     }
+    S.acc_in = acc_in >= 0 ? h.acc[acc_in] : nullptr;
+    S.acc_out = acc_out >= 0 ? h.acc[acc_out] : nullptr;
     S.marg_out = marg_out;
+    double *zb = (acc_zero >= 0 && h.use_atomics) ? h.acc[acc_zero] : nullptr;
     switch (h.lp / 64) {
-        case 0: return launch_pass_t<0>(S, h, side, mode, s);
-        case 1: return launch_pass_t<1>(S, h, side, mode, s);
-        case 2: return launch_pass_t<2>(S, h, side, mode, s);
-        case 3: return launch_pass_t<3>(S, h, side, mode, s);
-        case 4: return launch_pass_t<4>(S, h, side, mode, s);
-        case 5: return launch_pass_t<5>(S, h, side, mode, s);
-        case 6: return launch_pass_t<6>(S, h, side, mode, s);
-        case 7: return launch_pass_t<7>(S, h, side, mode, s);
-        case 8: return launch_pass_t<8>(S, h, side, mode, s);
+        case 0: return launch_pass_t<0>(S, h, side, mode, zb, s);
+        case 1: return launch_pass_t<1>(S, h, side, mode, zb, s);
+        case 2: return launch_pass_t<2>(S, h, side, mode, zb, s);
+        case 3: return launch_pass_t<3>(S, h, side, mode, zb, s);
+        case 4: return launch_pass_t<4>(S, h, side, mode, zb, s);
+        case 5: return launch_pass_t<5>(S, h, side, mode, zb, s);
+        case 6: return launch_pass_t<6>(S, h, side, mode, zb, s);
+        case 7: return launch_pass_t<7>(S, h, side, mode, zb, s);
+        case 8: return launch_pass_t<8>(S, h, side, mode, zb, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -2,6 +2,7 @@
 // workspace layout, and the order in which the build and iteration kernels are
 // enqueued.  No arithmetic of the method happens on the host except the choice
 // of the k-means start indices (integer only).
+#include <cstdlib>
 #include <new>
 #include <unordered_map>
 #include <vector>
@@ -83,7 +84,6 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.a = bump.take<float>((size_t)h.n);
     h.b_marg = bump.take<float>((size_t)h.m);
     h.counters = bump.take<unsigned long long>(8);
-    h.done_counter = bump.take<unsigned>(4);
     h.query_out = bump.take<double>(4);
     sc.fail_flag = bump.take<int>(4);
     sc.totals = bump.take<long long>(4);
@@ -131,8 +131,7 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.lin_v = bump.take<double>((size_t)h.m);
     h.perm_u = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.n);
     h.perm_v = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.m);
-    h.acc_y = bump.take<double>(lp1);
-    h.acc_z = bump.take<double>(lp1);
+    for (int i = 0; i < 3; ++i) h.acc[i] = bump.take<double>(lp1);
     h.grid = pass_grid(h);
     h.partial = bump.take<double>((size_t)h.grid * (h.lp + 2));
 }
@@ -228,6 +227,18 @@ lcn_status status_from_counters(Handle &h)
     return LCN_OK;
 }
 
+// From the stored log scalings: linear copies, bucket-ordered copies, and the
+// accumulators z = U^T u (buffer 2) and y = W v (buffer 0); phase 0.
+lcn_status init_state(Handle &h)
+{
+    const size_t lp1 = h.lp > 0 ? h.lp : 1;
+    for (int i = 0; i < 3; ++i) HIPCHK(hipMemsetAsync(h.acc[i], 0, sizeof(double) * lp1, h.stream));
+    HIPCHK(launch_pass(h, 0, PASS_INIT, -1, 2, -1, nullptr, h.stream));
+    HIPCHK(launch_pass(h, 1, PASS_INIT, -1, 0, -1, nullptr, h.stream));
+    h.phase = 0;
+    return LCN_OK;
+}
+
 bool valid(lcn_handle hh) { return hh && ((Handle *)hh)->magic == HANDLE_MAGIC; }
 
 }  // namespace
@@ -306,7 +317,6 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     HIPCHK(hipEventCreate(&h.ev0));
     HIPCHK(hipEventCreate(&h.ev1));
     HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
-    HIPCHK(hipMemsetAsync(h.done_counter, 0, 4 * sizeof(unsigned), h.stream));
     HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
     HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
     HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
@@ -375,8 +385,12 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     // scalings start at 1 (eq. 2)
     HIPCHK(hipMemsetAsync(h.log_u, 0, sizeof(float) * (size_t)n, h.stream));
     HIPCHK(hipMemsetAsync(h.log_v, 0, sizeof(float) * (size_t)m, h.stream));
-    HIPCHK(launch_pass(h, 0, PASS_INIT, nullptr, h.stream));
-    HIPCHK(launch_pass(h, 1, PASS_INIT, nullptr, h.stream));
+    {
+        const char *env = getenv("LCN_ACC_ATOMICS");
+        h.use_atomics = env ? atoi(env) : 0;
+    }
+    st = init_state(h);
+    if (st != LCN_OK) return st;
 
     int fail = 0;
     unsigned long long uniq = 0;
@@ -398,9 +412,10 @@ lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
     if (iters < 0) return LCN_ERR_INVALID_ARG;
     Handle &h = *(Handle *)hh;
     HIPCHK(hipEventRecord(h.ev0, h.stream));
-    for (int it = 0; it < iters; ++it) {
-        HIPCHK(launch_pass(h, 0, PASS_UPDATE, nullptr, h.stream));
-        HIPCHK(launch_pass(h, 1, PASS_UPDATE, nullptr, h.stream));
+    for (int it = 0; it < 2 * iters; ++it) {
+        const int t = h.phase;
+        HIPCHK(launch_pass(h, it & 1, PASS_UPDATE, t % 3, (t + 1) % 3, (t + 2) % 3, nullptr, h.stream));
+        h.phase = t + 1;
     }
     HIPCHK(hipEventRecord(h.ev1, h.stream));
     lcn_status st = status_from_counters(h);
@@ -414,8 +429,11 @@ lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
 
 static lcn_status query(Handle &h, float *row_dev, float *col_dev, double q[4])
 {
-    HIPCHK(launch_pass(h, 0, PASS_QUERY, row_dev, h.stream));
-    HIPCHK(launch_pass(h, 1, PASS_QUERY, col_dev, h.stream));
+    // y = W v is the input of the next sweep (buffer phase % 3); z = U^T u was the
+    // input of the last sweep over Y (buffer (phase + 2) % 3)
+    HIPCHK(hipMemsetAsync(h.query_out, 0, 4 * sizeof(double), h.stream));
+    HIPCHK(launch_pass(h, 0, PASS_QUERY, h.phase % 3, -1, -1, row_dev, h.stream));
+    HIPCHK(launch_pass(h, 1, PASS_QUERY, (h.phase + 2) % 3, -1, -1, col_dev, h.stream));
     HIPCHK(hipMemcpyAsync(q, h.query_out, 4 * sizeof(double), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
     return LCN_OK;
@@ -463,8 +481,8 @@ lcn_status lcn_set_scalings(lcn_handle hh, const float *log_u_dev, const float *
     Handle &h = *(Handle *)hh;
     HIPCHK(hipMemcpyAsync(h.log_u, log_u_dev, sizeof(float) * (size_t)h.n, hipMemcpyDeviceToDevice, h.stream));
     HIPCHK(hipMemcpyAsync(h.log_v, log_v_dev, sizeof(float) * (size_t)h.m, hipMemcpyDeviceToDevice, h.stream));
-    HIPCHK(launch_pass(h, 0, PASS_INIT, nullptr, h.stream));
-    HIPCHK(launch_pass(h, 1, PASS_INIT, nullptr, h.stream));
+    lcn_status st = init_state(h);
+    if (st != LCN_OK) return st;
     HIPCHK(hipStreamSynchronize(h.stream));
     return LCN_OK;
 }

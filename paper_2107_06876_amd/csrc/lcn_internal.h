@@ -89,7 +89,8 @@ hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N,
 hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s);
 
 // ---- iteration (kernels_iter.hip) ------------------------------------------
-hipError_t launch_pass(const Handle &h, int side, int mode, float *marg_out, hipStream_t s);
+hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, int acc_zero, float *marg_out,
+                       hipStream_t s);
 int pass_grid(const Handle &h);
 
 struct Handle {
@@ -121,10 +122,11 @@ struct Handle {
     float *log_u, *log_v;
     double *lin_u, *lin_v;
     double *perm_u, *perm_v;   // [R][n], [R][m]
-    double *acc_y, *acc_z;     // lp each: y = W v, z = U^T u
+    double *acc[3];            // lp each, rotating: launch t reads acc[t%3], adds into acc[(t+1)%3]
+    int phase;                 // number of half-iterations launched since the scalings were (re)set
+    int use_atomics;           // accumulate F^T out with fp64 atomics instead of partials + reduce kernel
     double *partial;           // [grid][lp + 2]
     double *query_out;         // [2 sides][2]: sum r log u, sum |r - a|
-    unsigned *done_counter;
     unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag
     int grid;
 
