@@ -328,13 +328,14 @@ hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lt, double
 __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const float *__restrict__ Z, int d, int cost,
                                                          double inv_lambda, const double *__restrict__ zn,
                                                          const float *__restrict__ U, const float *__restrict__ Wt,
-                                                         int lp, float *tiles, float *tilesT,
+                                                         int lp, float *vals_x, float *vals_y,
                                                          unsigned long long *unique_counter)
 {
     __shared__ float Ps[KCH][LDT];
     __shared__ float Cs[KCH][LDT];
     __shared__ float vals[TILE][TILE + 1];
     __shared__ long long xi[TILE], yj[TILE];
+    __shared__ long long xdst[TILE], ydst[TILE];  // where each row's / column's slice of this block starts
     __shared__ int bx[8][TILE], by[8][TILE];
     __shared__ unsigned cnt_sh;
 
@@ -366,12 +367,24 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
         int li = ti * 64 + tid;
         long long gi = li < nx ? xperm[li] : -1;
         xi[tid] = gi;
+        long long dst = -1;
+        if (gi >= 0) {
+            dst = B.rowbase_x[gi];
+            for (int q = 0; q < r; ++q) dst += B.seg_x[(long long)q * B.n + gi].len;
+        }
+        xdst[tid] = dst;
         for (int q = 0; q < r; ++q) bx[q][tid] = gi >= 0 ? B.bucket[(long long)q * N + gi] : -1;
     } else if (tid < 2 * TILE) {
         int t = tid - TILE;
         int lj = tj * 64 + t;
         long long gj = lj < ny ? yperm[lj] : -1;
         yj[t] = gj >= 0 ? B.n + gj : -1;  // row of Z
+        long long dst = -1;
+        if (gj >= 0) {
+            dst = B.rowbase_y[gj];
+            for (int q = 0; q < r; ++q) dst += B.seg_y[(long long)q * B.m + gj].len;
+        }
+        ydst[t] = dst;
         for (int q = 0; q < r; ++q) by[q][t] = gj >= 0 ? B.bucket[(long long)q * N + B.n + gj] : -2;
     }
     if (tid == 0) cnt_sh = 0;
@@ -438,14 +451,13 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
     atomicAdd(&cnt_sh, mine);
     __syncthreads();
     if (tid == 0) atomicAdd(unique_counter, (unsigned long long)cnt_sh);
-    // write the piece in both layouts, coalesced
-    const long long base = B.val_off[blk];
+    // write the piece into the row records of X and of Y, coalesced along each record
     const int lane = tid & 63, w = tid >> 6;
     for (int rr = w; rr < TILE; rr += 4) {
-        int li = ti * 64 + rr, lj = tj * 64 + lane;
-        if (li < nx && lj < ny) tiles[base + (long long)li * ny + lj] = vals[rr][lane];
-        int lj2 = tj * 64 + rr, li2 = ti * 64 + lane;
-        if (lj2 < ny && li2 < nx) tilesT[base + (long long)lj2 * nx + li2] = vals[lane][rr];
+        const int lj = tj * 64 + lane;
+        if (xdst[rr] >= 0 && lj < ny) vals_x[xdst[rr] + lj] = vals[rr][lane];
+        const int li = ti * 64 + lane;
+        if (ydst[rr] >= 0 && li < nx) vals_y[ydst[rr] + li] = vals[lane][rr];
     }
 }
 
@@ -456,7 +468,7 @@ hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s)
     hipLaunchKernelGGL(correction_kernel, dim3(ntiles), dim3(256), 0, s, h.sort, h.Z, h.d, h.cost, 1.0 / h.lambda,
                        h.cost == LCN_COST_COSINE ? h.zn : (const double *)nullptr,
                        lcn_mode ? h.U : (const float *)nullptr, lcn_mode ? h.Wt : (const float *)nullptr, h.lp,
-                       h.tiles, h.tilesT, h.counters + 3);
+                       h.vals_x, h.vals_y, h.counters + 3);
     return hipGetLastError();
 }
 

@@ -1,13 +1,15 @@
 // The Sinkhorn half-iteration (Sec. 2 eq. 2 on the decomposed kernel of Sec. 4):
 // for every row i of one side
-//     s_i   = F_i . acc_in  +  sum over hash rounds of  tile_row(i) . perm_in
+//     s_i   = F_i . acc_in  +  (row record of sparse values) . (gathered scalings)
 //     out_i = marg_i / s_i
 // and, in the same sweep, acc_out = F^T out for the other side's next sweep.
 // For the rows of X: F = U, acc_in = y = W v, acc_out = z = U^T u.
 // For the rows of Y: F = W^T, acc_in = z, acc_out = y.
 // Each stored value (factor entry or sparse value) is read exactly once per
 // sweep.  One wavefront owns a row: consecutive lanes read consecutive
-// addresses of the factor row, then of each tile row.
+// addresses of the factor row and of the row's record of sparse values; the
+// next row's factor entries and metadata are requested before the current
+// row is reduced, so that a wave always has loads in flight.
 //
 // Scalings are kept as fp64 linear values for the arithmetic (range e^+-700,
 // which covers what a log-domain float state can express) and reported as
@@ -18,12 +20,32 @@ namespace lcn {
 
 constexpr int PASS_THREADS = 1024;
 constexpr int PASS_WAVES = PASS_THREADS / 64;
+constexpr int MAXR = 8;
 
+// One step of a cross-lane sum of doubles through the DPP data path (no LDS):
+// adds to every lane the value of the lane that `CTRL` selects; lanes of rows
+// outside ROW_MASK add zero.
+template <int CTRL, int ROW_MASK>
+__device__ inline double dpp_add(double v)
+{
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    const int plo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xF, false);
+    const int phi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xF, false);
+    return v + __hiloint2double(phi, plo);
+}
+
+// Sum over the 64 lanes of a wavefront in a fixed order; every lane gets the result.
 __device__ inline double wave_sum(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    v = dpp_add<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141, 0xF>(v);  // row_half_mirror
+    v = dpp_add<0x140, 0xF>(v);  // row_mirror: every lane of a 16-lane row holds the row's sum
+    v = dpp_add<0x142, 0xA>(v);  // row_bcast15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);  // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
 }
 
 // natural log of a positive finite double: exponent taken out exactly, the
@@ -32,7 +54,7 @@ __device__ inline double fast_log(double x)
 {
     int e;
     double mant = frexp(x, &e);
-    return (double)logf((float)mant) + (double)e * 0.69314718055994530942;
+    return (double)__logf((float)mant) + (double)e * 0.69314718055994530942;
 }
 
 __device__ inline double fast_rcp(double x)
@@ -43,7 +65,67 @@ __device__ inline double fast_rcp(double x)
     return r;
 }
 
-template <int T, int MODE>
+// Factor row held by a wave.  lp = 64 T.  If T is a multiple of 4 a lane holds
+// 4 consecutive entries per 256 (one 16-byte load each), else one entry per 64.
+template <int T>
+struct FRow {
+    static constexpr int TT = T > 0 ? T : 1;
+    static constexpr bool VEC = (T > 0) && (T % 4 == 0);
+    float f[TT];
+    __device__ inline void load(const float *__restrict__ F, long long row, int lp, int lane)
+    {
+        if (T == 0) return;
+        if (VEC) {
+#pragma unroll
+            for (int q = 0; q < T / 4; ++q) {
+                const float4 v = *(const float4 *)(F + row * lp + 256 * q + 4 * lane);
+                f[4 * q + 0] = v.x;
+                f[4 * q + 1] = v.y;
+                f[4 * q + 2] = v.z;
+                f[4 * q + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < TT; ++t) f[t] = F[row * lp + 64 * t + lane];
+        }
+    }
+    // index into the length-lp vectors of register slot e
+    __device__ static inline int kidx(int e, int lane)
+    {
+        return VEC ? 256 * (e / 4) + 4 * lane + (e % 4) : 64 * e + lane;
+    }
+};
+
+// Per-row metadata, read from the packed record (see meta_kernel): wave-uniform,
+// so it lives in scalar registers.
+template <int RR>
+struct RowMeta {
+    long long base;
+    float marg;
+    double log_marg;
+    int vstart[RR];
+    int len[RR];
+    int pos;     // lane r < R: position of the row in round r's bucket order
+    double lin;  // query mode: the row's current scaling
+};
+
+template <int RR, int MODE>
+__device__ inline void load_meta(RowMeta<RR> &M, const PassSide &S, int R, long long row, int lane)
+{
+    const int *__restrict__ rec = S.meta + row * S.meta_stride;
+    M.base = ((long long)rec[1] << 32) | (unsigned)rec[0];
+    M.marg = __int_as_float(rec[2]);
+    M.log_marg = __hiloint2double(rec[5], rec[4]);
+#pragma unroll
+    for (int r = 0; r < RR; ++r) {
+        M.vstart[r] = r < R ? rec[6 + 2 * r] : 0;
+        M.len[r] = r < R ? rec[7 + 2 * r] : 0;
+    }
+    M.pos = (MODE != PASS_QUERY && lane < R) ? rec[6 + 2 * R + lane] : 0;
+    M.lin = MODE == PASS_QUERY ? S.lin_out[row] : 0.0;
+}
+
+template <int T, int RR, int MODE>
 __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, int lp, double *partial,
                                                             double *zero_buf, int use_atomics,
                                                             unsigned long long *counters, int empty_slot,
@@ -51,7 +133,8 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
 {
     constexpr int TT = T > 0 ? T : 1;
     extern __shared__ double zsh[];  // [PASS_WAVES / 2][lp + 2]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long long nwaves = (long long)gridDim.x * PASS_WAVES;
     const long long gw = (long long)blockIdx.x * PASS_WAVES + wave;
     const int stride = lp + 2;
@@ -59,7 +142,7 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     double yreg[TT], zacc[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
-        yreg[t] = (T > 0 && MODE != PASS_INIT) ? S.acc_in[lane + 64 * t] : 0.0;
+        yreg[t] = (T > 0 && MODE != PASS_INIT) ? S.acc_in[FRow<T>::kidx(t, lane)] : 0.0;
         zacc[t] = 0.0;
     }
     double q0 = 0.0, q1 = 0.0;
@@ -68,36 +151,66 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     if (zero_buf && blockIdx.x == 0)
         for (int k = threadIdx.x; k < lp; k += PASS_THREADS) zero_buf[k] = 0.0;
 
-    for (long long row = gw; row < S.rows; row += nwaves) {
-        float f[TT];
+    FRow<T> cur{}, nxt{};
+    RowMeta<RR> mc{}, mn{};
+    long long row = gw;
+    if (row < S.rows) {
+        cur.load(S.F, row, lp, lane);
+        load_meta<RR, MODE>(mc, S, R, row, lane);
+    }
+    while (row < S.rows) {
+        const long long next = row + nwaves;
         double out;
-        if (T > 0) {
-#pragma unroll
-            for (int t = 0; t < TT; ++t) f[t] = S.F[row * lp + lane + 64 * t];
-        }
         if (MODE == PASS_INIT) {
+            if (next < S.rows) {
+                nxt.load(S.F, next, lp, lane);
+                load_meta<RR, MODE>(mn, S, R, next, lane);
+            }
             out = exp((double)S.log_out[row]);
         } else {
+            // sparse part: the first 64 entries of every round's segment are requested
+            // before anything is used; what is left of long segments follows
             double acc = 0.0;
+            const float *__restrict__ vals = S.vals + mc.base;
+            int total_len = 0;
+            {
+                float tv[RR];
+                double vv[RR];
+                int segoff[RR];
+#pragma unroll
+                for (int r = 0; r < RR; ++r) {
+                    segoff[r] = total_len;
+                    total_len += mc.len[r];
+                    const bool ok = lane < mc.len[r];
+                    tv[r] = ok ? vals[segoff[r] + lane] : 0.f;
+                    vv[r] = ok ? S.perm_in[mc.vstart[r] + lane] : 0.0;
+                }
+                if (next < S.rows) {  // request the next row while this one is in flight
+                    nxt.load(S.F, next, lp, lane);
+                    load_meta<RR, MODE>(mn, S, R, next, lane);
+                }
+#pragma unroll
+                for (int r = 0; r < RR; ++r) acc = fma((double)tv[r], vv[r], acc);
+#pragma unroll
+                for (int r = 0; r < RR; ++r) {
+                    if (mc.len[r] > 64) {
+                        const float *tp = vals + segoff[r];
+                        const double *vp = S.perm_in + mc.vstart[r];
+                        for (int e = 64 + lane; e < mc.len[r]; e += 64) acc = fma((double)tp[e], vp[e], acc);
+                    }
+                }
+            }
             if (T > 0) {
 #pragma unroll
-                for (int t = 0; t < TT; ++t) acc = fma((double)f[t], yreg[t], acc);
-            }
-            int total_len = 0;
-            for (int r = 0; r < R; ++r) {
-                const RowInfo ri = S.rinfo[(long long)r * S.rows + row];
-                const float *tv = S.tiles + ri.start;
-                const double *vv = S.perm_in + ri.vstart;
-                for (int e = lane; e < ri.len; e += 64) acc = fma((double)tv[e], vv[e], acc);
-                total_len += ri.len;
+                for (int t = 0; t < TT; ++t) acc = fma((double)cur.f[t], yreg[t], acc);
             }
             const double s = wave_sum(acc);
-            const double marg = (double)S.marg[row];
+            const double marg = (double)mc.marg;
             if (MODE == PASS_UPDATE) {
                 float lo;
                 if (s > 0.0) {
                     out = marg * fast_rcp(s);
-                    lo = (float)(fast_log(marg) - fast_log(s));
+                    lo = (float)(mc.log_marg - fast_log(s));
                 } else if (T == 0 && total_len == 0) {
                     out = 0.0;
                     lo = -INFINITY;
@@ -109,7 +222,7 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
                 }
                 if (lane == 0) S.log_out[row] = lo;
             } else {  // PASS_QUERY
-                out = S.lin_out[row];
+                out = mc.lin;
                 const double ri = out * s;
                 if (lane == 0 && S.marg_out) S.marg_out[row] = (float)ri;
                 if (out > 0.0) q0 += ri * log(out);
@@ -118,12 +231,15 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
         }
         if (MODE != PASS_QUERY) {
             if (lane == 0) S.lin_out[row] = out;
-            if (lane < R) S.perm_out[(long long)lane * S.rows + S.pos[(long long)lane * S.rows + row]] = out;
+            if (lane < R) S.perm_out[(long long)lane * S.rows + mc.pos] = out;
             if (T > 0) {
 #pragma unroll
-                for (int t = 0; t < TT; ++t) zacc[t] = fma((double)f[t], out, zacc[t]);
+                for (int t = 0; t < TT; ++t) zacc[t] = fma((double)cur.f[t], out, zacc[t]);
             }
         }
+        cur = nxt;
+        mc = mn;
+        row = next;
     }
 
     // workgroup reduction of the per-wave accumulators (upper half of the waves
@@ -133,7 +249,7 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     if (wave >= HALF) {
         if (T > 0) {
 #pragma unroll
-            for (int t = 0; t < TT; ++t) mine[lane + 64 * t] = zacc[t];
+            for (int t = 0; t < TT; ++t) mine[FRow<T>::kidx(t, lane)] = zacc[t];
         }
         if (lane == 0) {
             mine[lp] = q0;
@@ -144,7 +260,7 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     if (wave < HALF) {
         if (T > 0) {
 #pragma unroll
-            for (int t = 0; t < TT; ++t) mine[lane + 64 * t] += zacc[t];
+            for (int t = 0; t < TT; ++t) mine[FRow<T>::kidx(t, lane)] += zacc[t];
         }
         if (lane == 0) {
             mine[lp] += q0;
@@ -172,24 +288,27 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     }
 }
 
-// Adds the per-workgroup partial sums of a sweep in workgroup order (so the
-// result does not depend on timing).  One workgroup per 64 entries.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const double *__restrict__ partial, int groups,
-                                                              int stride, int lp, double *acc_out, double *query_out,
-                                                              int is_query)
+// Adds the per-workgroup partial sums of a sweep in a fixed order (so the
+// result does not depend on timing).  One workgroup per 64 entries; wave w adds
+// the partials of workgroups w, w + 16, ..., then the 16 wave sums are added.
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const double *__restrict__ partial, int groups,
+                                                               int stride, int lp, double *acc_out,
+                                                               double *query_out, int is_query)
 {
-    __shared__ double sh[4][64];
+    __shared__ double sh[16][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int k = blockIdx.x * 64 + lane;
     double s = 0.0;
     if (k < stride) {
-#pragma unroll 8
-        for (int g = wave; g < groups; g += 4) s += partial[(long long)g * stride + k];
+#pragma unroll 16
+        for (int g = wave; g < groups; g += 16) s += partial[(long long)g * stride + k];
     }
     sh[wave][lane] = s;
     __syncthreads();
     if (wave == 0 && k < stride) {
-        s = (sh[0][lane] + sh[1][lane]) + (sh[2][lane] + sh[3][lane]);
+        s = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) s += sh[w][lane];
         if (k < lp) {
             if (!is_query) acc_out[k] = s;
         } else if (is_query) {
@@ -202,12 +321,13 @@ int pass_grid(const Handle &h)
 {
     long long rows = h.n > h.m ? h.n : h.m;
     long long g = (rows + PASS_WAVES - 1) / PASS_WAVES;
-    return (int)(g < 512 ? g : 512);
+    long long cap = h.grid_cap > 0 ? h.grid_cap : 512;
+    return (int)(g < cap ? g : cap);
 }
 
-template <int T>
-static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, double *zero_buf,
-                                hipStream_t s)
+template <int T, int RR>
+static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, int mode, double *zero_buf,
+                                 hipStream_t s)
 {
     long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
     int grid = (int)(g < h.grid ? g : h.grid);
@@ -215,20 +335,28 @@ static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, in
     double *qout = h.query_out + 2 * side;
     int empty_slot = 1 + side;
     if (mode == PASS_UPDATE)
-        hipLaunchKernelGGL((pass_kernel<T, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
+        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
                            h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
     else if (mode == PASS_QUERY)
-        hipLaunchKernelGGL((pass_kernel<T, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
+        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
                            h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
     else
-        hipLaunchKernelGGL((pass_kernel<T, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
+        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
                            h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
     if (!h.use_atomics) {
         const int stride = h.lp + 2;
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(256), 0, s, h.partial, grid, stride,
-                           h.lp, S.acc_out, qout, mode == PASS_QUERY ? 1 : 0);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(1024), 0, s, h.partial, grid,
+                           stride, h.lp, S.acc_out, qout, mode == PASS_QUERY ? 1 : 0);
     }
     return hipGetLastError();
+}
+
+template <int T>
+static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, double *zero_buf,
+                                hipStream_t s)
+{
+    if (h.R <= 4) return launch_pass_tr<T, 4>(S, h, side, mode, zero_buf, s);
+    return launch_pass_tr<T, 8>(S, h, side, mode, zero_buf, s);
 }
 
 // side 0: rows of X (updates u, consumes y = W v, produces z = U^T u); side 1: rows of Y.
@@ -240,10 +368,8 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
     if (side == 0) {
         S.rows = h.n;
         S.F = h.U;
-        S.tiles = h.tiles;
-        S.rinfo = h.sort.rinfo_x;
-        S.pos = h.sort.pos;
-        S.marg = h.a;
+        S.vals = h.vals_x;
+        S.meta = h.sort.meta_x;
         S.log_out = h.log_u;
         S.lin_out = h.lin_u;
         S.perm_out = h.perm_u;
@@ -251,10 +377,8 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
     } else {
         S.rows = h.m;
         S.F = h.Wt;
-        S.tiles = h.tilesT;
-        S.rinfo = h.sort.rinfo_y;
-        S.pos = h.sort.pos + (long long)h.R * h.n;
-        S.marg = h.b_marg;
+        S.vals = h.vals_y;
+        S.meta = h.sort.meta_y;
         S.log_out = h.log_v;
         S.lin_out = h.lin_v;
         S.perm_out = h.perm_v;
@@ -263,6 +387,7 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
     S.acc_in = acc_in >= 0 ? h.acc[acc_in] : nullptr;
     S.acc_out = acc_out >= 0 ? h.acc[acc_out] : nullptr;
     S.marg_out = marg_out;
+    S.meta_stride = h.sort.meta_stride;
     double *zb = (acc_zero >= 0 && h.use_atomics) ? h.acc[acc_zero] : nullptr;
     switch (h.lp / 64) {
         case 0: return launch_pass_t<0>(S, h, side, mode, zb, s);

@@ -283,6 +283,8 @@ hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_
 
 constexpr int CH = 1024;
 
+__global__ void scan_i64_kernel(long long *data, long long n);
+
 int sort_chunks(long long n, long long m)
 {
     long long mx = n > m ? n : m;
@@ -383,7 +385,6 @@ __global__ __launch_bounds__(1024) void sort_offsets_kernel(SortBuffers B)
             run += v;
             run2 += v2;
         }
-        B.val_off[nb] = run;
         B.tile_off[nb] = (int)run2;
         B.totals_out[0] = run;
         B.totals_out[1] = run2;
@@ -393,7 +394,6 @@ __global__ __launch_bounds__(1024) void sort_offsets_kernel(SortBuffers B)
     for (int i = lo; i < hi; ++i) {
         long long nx = B.totals[i];
         long long ny = B.totals[B.R * B.b + i];
-        B.val_off[i] = run;
         B.tile_off[i] = (int)run2;
         run += nx * ny;
         run2 += ((nx + 63) / 64) * ((ny + 63) / 64);
@@ -448,26 +448,27 @@ __global__ __launch_bounds__(64) void sort_scatter_kernel(SortBuffers B)
     }
 }
 
-// per (round, row): where the row's values and its slice of the input vector start
-__global__ void rowinfo_kernel(SortBuffers B)
+// per (round, row): the slice of the other side's bucket-ordered vector the row
+// multiplies; per row: the length of its record (written to rowbase, scanned after)
+__global__ void seg_kernel(SortBuffers B)
 {
-    const int r = blockIdx.y, side = blockIdx.z;
+    const int side = blockIdx.y;
     const long long cnt = side_count(B, side);
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt) return;
     const long long other = side ? B.n : B.m;
-    const int32_t *bk = B.bucket + (long long)r * (B.n + B.m) + (side ? B.n : 0);
-    const int beta = bk[i];
-    const int *off_me = B.off + (side * B.R + r) * (B.b + 1);
-    const int *off_ot = B.off + ((1 - side) * B.R + r) * (B.b + 1);
-    const int *pos = B.pos + (side ? (long long)B.R * B.n + (long long)r * B.m : (long long)r * B.n);
-    const int len = off_ot[beta + 1] - off_ot[beta];
-    const int local = pos[i] - off_me[beta];
-    RowInfo ri;
-    ri.start = B.val_off[r * B.b + beta] + (long long)local * len;
-    ri.vstart = (int)((long long)r * other + off_ot[beta]);
-    ri.len = len;
-    (side ? B.rinfo_y : B.rinfo_x)[(long long)r * cnt + i] = ri;
+    long long total = 0;
+    for (int r = 0; r < B.R; ++r) {
+        const int32_t *bk = B.bucket + (long long)r * (B.n + B.m) + (side ? B.n : 0);
+        const int beta = bk[i];
+        const int *off_ot = B.off + ((1 - side) * B.R + r) * (B.b + 1);
+        Seg sg;
+        sg.len = off_ot[beta + 1] - off_ot[beta];
+        sg.vstart = (int)((long long)r * other + off_ot[beta]);
+        (side ? B.seg_y : B.seg_x)[(long long)r * cnt + i] = sg;
+        total += sg.len;
+    }
+    (side ? B.rowbase_y : B.rowbase_x)[i] = total;
 }
 
 hipError_t launch_bucket_sort(const SortBuffers &B, hipStream_t s)
@@ -480,7 +481,48 @@ hipError_t launch_bucket_sort(const SortBuffers &B, hipStream_t s)
     hipLaunchKernelGGL(sort_offsets_kernel, dim3(1), dim3(1024), 0, s, B);
     hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(64), lds, s, B);
     long long mx = B.n > B.m ? B.n : B.m;
-    hipLaunchKernelGGL(rowinfo_kernel, dim3((unsigned)((mx + 255) / 256), B.R, 2), dim3(256), 0, s, B);
+    hipLaunchKernelGGL(seg_kernel, dim3((unsigned)((mx + 255) / 256), 2), dim3(256), 0, s, B);
+    hipLaunchKernelGGL(scan_i64_kernel, dim3(1), dim3(1024), 0, s, B.rowbase_x, B.n);
+    hipLaunchKernelGGL(scan_i64_kernel, dim3(1), dim3(1024), 0, s, B.rowbase_y, B.m);
+    return hipGetLastError();
+}
+
+// Packed per-row metadata read by the sweeps, one record per row:
+//   [0:1] start of the row's record of sparse values (int64)
+//   [2]   marginal (float)          [4:5] its natural log (double)
+//   [6 + 2r], [7 + 2r]  round r: start in the other side's bucket-ordered vector, length
+//   [6 + 2R + r]        round r: position of the row in its own side's bucket order
+int meta_stride_for(int R) { return (6 + 3 * R + 3) / 4 * 4; }
+
+__global__ void meta_kernel(SortBuffers B, const float *a, const float *b)
+{
+    const int side = blockIdx.y;
+    const long long cnt = side_count(B, side);
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    int *rec = (side ? B.meta_y : B.meta_x) + i * B.meta_stride;
+    const long long base = B.R > 0 ? (side ? B.rowbase_y : B.rowbase_x)[i] : 0;
+    const float marg = (side ? b : a)[i];
+    const double lm = log((double)marg);
+    rec[0] = (int)(unsigned)(base & 0xffffffffll);
+    rec[1] = (int)(base >> 32);
+    rec[2] = __float_as_int(marg);
+    rec[3] = 0;
+    rec[4] = __double2loint(lm);
+    rec[5] = __double2hiint(lm);
+    const int *pos = B.pos + (side ? (long long)B.R * B.n : 0);
+    for (int r = 0; r < B.R; ++r) {
+        const Seg sg = (side ? B.seg_y : B.seg_x)[(long long)r * cnt + i];
+        rec[6 + 2 * r] = sg.vstart;
+        rec[7 + 2 * r] = sg.len;
+        rec[6 + 2 * B.R + r] = pos[(long long)r * cnt + i];
+    }
+}
+
+hipError_t launch_build_meta(const SortBuffers &B, const float *a, const float *b, hipStream_t s)
+{
+    long long mx = B.n > B.m ? B.n : B.m;
+    hipLaunchKernelGGL(meta_kernel, dim3((unsigned)((mx + 255) / 256), 2), dim3(256), 0, s, B, a, b);
     return hipGetLastError();
 }
 
@@ -500,27 +542,33 @@ __device__ inline bool owned_by_earlier_round(const int32_t *bucket, long long N
 }
 
 template <bool FILL>
-__global__ void csr_kernel(SortBuffers B, const float *tiles, long long *rowcount, const long long *rowptr,
+__global__ void csr_kernel(SortBuffers B, const float *vals, long long *rowcount, const long long *rowptr,
                            int32_t *colidx, float *val)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B.n) return;
     const long long N = B.n + B.m;
-    int head[8];
-    for (int r = 0; r < B.R; ++r) head[r] = 0;
+    int head[8], segstart[8];
+    int run = 0;
+    for (int r = 0; r < B.R; ++r) {
+        head[r] = 0;
+        segstart[r] = run;
+        run += B.seg_x[(long long)r * B.n + i].len;
+    }
+    const long long base = B.rowbase_x[i];
     long long outp = FILL ? rowptr[i] : 0;
     long long cnt = 0;
     while (true) {
         int bestj = 0x7fffffff, bestr = -1;
         for (int r = 0; r < B.R; ++r) {
-            const RowInfo ri = B.rinfo_x[(long long)r * B.n + i];
+            const Seg sg = B.seg_x[(long long)r * B.n + i];
             const int *yperm = B.perm + (long long)B.R * B.n + (long long)r * B.m;
-            const int seg0 = ri.vstart - (int)((long long)r * B.m);
+            const int seg0 = sg.vstart - (int)((long long)r * B.m);
             // skip entries an earlier round owns
-            while (head[r] < ri.len &&
+            while (head[r] < sg.len &&
                    owned_by_earlier_round(B.bucket, N, B.n, r, i, yperm[seg0 + head[r]]))
                 ++head[r];
-            if (head[r] < ri.len) {
+            if (head[r] < sg.len) {
                 int j = yperm[seg0 + head[r]];
                 if (j < bestj) {
                     bestj = j;
@@ -530,9 +578,8 @@ __global__ void csr_kernel(SortBuffers B, const float *tiles, long long *rowcoun
         }
         if (bestr < 0) break;
         if (FILL) {
-            const RowInfo ri = B.rinfo_x[(long long)bestr * B.n + i];
             colidx[outp] = bestj;
-            if (val) val[outp] = tiles[ri.start + head[bestr]];
+            if (val) val[outp] = vals[base + segstart[bestr] + head[bestr]];
             ++outp;
         }
         ++cnt;
@@ -543,14 +590,14 @@ __global__ void csr_kernel(SortBuffers B, const float *tiles, long long *rowcoun
 
 hipError_t launch_csr_count(const Handle &h, long long *rowcount, hipStream_t s)
 {
-    hipLaunchKernelGGL(csr_kernel<false>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.tiles,
+    hipLaunchKernelGGL(csr_kernel<false>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.vals_x,
                        rowcount, (const long long *)nullptr, (int32_t *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_csr_fill(const Handle &h, const long long *rowptr, int32_t *colidx, float *val, hipStream_t s)
 {
-    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.tiles,
+    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.vals_x,
                        (long long *)nullptr, rowptr, colidx, val);
     return hipGetLastError();
 }

@@ -108,11 +108,15 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     B.off = bump.take<int>(2 * (size_t)(h.R > 0 ? h.R : 1) * (h.b + 1));
     B.perm = bump.take<int>((size_t)(h.R > 0 ? h.R : 1) * N);
     B.pos = bump.take<int>((size_t)(h.R > 0 ? h.R : 1) * N);
-    B.val_off = bump.take<long long>(Rb + 1);
     B.tile_off = bump.take<int>(Rb + 1);
     B.totals_out = sc.totals;
-    B.rinfo_x = bump.take<RowInfo>((size_t)(h.R > 0 ? h.R : 1) * h.n);
-    B.rinfo_y = bump.take<RowInfo>((size_t)(h.R > 0 ? h.R : 1) * h.m);
+    B.seg_x = bump.take<Seg>((size_t)(h.R > 0 ? h.R : 1) * h.n);
+    B.seg_y = bump.take<Seg>((size_t)(h.R > 0 ? h.R : 1) * h.m);
+    B.rowbase_x = bump.take<long long>((size_t)h.n + 1);
+    B.rowbase_y = bump.take<long long>((size_t)h.m + 1);
+    B.meta_stride = meta_stride_for(h.R);
+    B.meta_x = bump.take<int>((size_t)h.n * B.meta_stride);
+    B.meta_y = bump.take<int>((size_t)h.m * B.meta_stride);
 
     const size_t lp1 = h.lp > 0 ? h.lp : 1;
     h.U = bump.take<float>((size_t)h.n * lp1);
@@ -306,6 +310,10 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     h.ws_bytes = workspace_bytes;
     const long long N = n + m;
 
+    {
+        const char *env = getenv("LCN_PASS_GRID");
+        h.grid_cap = env ? atoi(env) : 0;
+    }
     Bump bump{h.ws, workspace_bytes, 0, false};
     Scratch sc{};
     layout(h, bump, sc);
@@ -350,14 +358,15 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         HIPCHK(launch_bucket_sort(h.sort, h.stream));
         HIPCHK(hipMemcpyAsync(totals, sc.totals, sizeof(totals), hipMemcpyDeviceToHost, h.stream));
     }
+    HIPCHK(launch_build_meta(h.sort, h.a, h.b_marg, h.stream));
     HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
     if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
     h.nnz_stored = totals[0];
     h.ntiles = (int)totals[1];
 
-    h.tiles = bump.take<float>((size_t)h.nnz_stored);
-    h.tilesT = bump.take<float>((size_t)h.nnz_stored);
+    h.vals_x = bump.take<float>((size_t)h.nnz_stored);
+    h.vals_y = bump.take<float>((size_t)h.nnz_stored);
     h.ws_used = bump.used;
     if (bytes_needed) *bytes_needed = bump.used + 256;
     if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;

@@ -9,12 +9,11 @@
 
 namespace lcn {
 
-// One row (or column) of the sparse part in one hash round: its values are
-// `len` consecutive floats starting at `start` in the tile array, and they
-// multiply `len` consecutive entries of the permuted input vector starting at
-// `vstart`.
-struct RowInfo {
-    long long start;
+// One row (or column) of the sparse part in one hash round: `len` values that
+// multiply `len` consecutive entries of the other side's bucket-ordered
+// scaling vector starting at `vstart`.  A row's values of all rounds are stored
+// back to back (round 0 first) starting at its row base.
+struct Seg {
     int vstart;
     int len;
 };
@@ -24,10 +23,9 @@ struct RowInfo {
 struct PassSide {
     long long rows;         // n or m
     const float *F;         // rows x lp factor (U or W^T), zero padded to lp
-    const float *tiles;     // sparse values laid out so that this side's rows are contiguous
-    const RowInfo *rinfo;   // [R][rows]
-    const int *pos;         // [R][rows] position of the row in its round's bucket order
-    const float *marg;      // a or b
+    const float *vals;      // sparse values, one contiguous record per row of this side
+    const int *meta;        // packed per-row metadata, meta_stride ints per row (see meta_kernel)
+    int meta_stride;
     float *log_out;         // log u or log v (fp32 state that is reported)
     double *lin_out;        // u or v, linear, by original index
     double *perm_out;       // [R][rows] u or v in bucket order of each round
@@ -62,13 +60,19 @@ struct SortBuffers {
     int *off;               // [2][R][b+1]  (x side then y side)
     int *perm;              // x: [R][n] then y: [R][m]
     int *pos;               // x: [R][n] then y: [R][m]
-    long long *val_off;     // [R*b + 1] start of each block's tile in the value array
     int *tile_off;          // [R*b + 1] start of each block in the list of 64x64 build tiles
     long long *totals_out;  // [2]: nnz_stored, build tiles
-    RowInfo *rinfo_x;       // [R][n]
-    RowInfo *rinfo_y;       // [R][m]
+    Seg *seg_x;             // [R][n]
+    Seg *seg_y;             // [R][m]
+    long long *rowbase_x;   // [n + 1]
+    long long *rowbase_y;   // [m + 1]
+    int *meta_x;            // [n][meta_stride] packed per-row metadata for the sweeps
+    int *meta_y;            // [m][meta_stride]
+    int meta_stride;        // ints per record: 6 + 3 R rounded up to a multiple of 4
 };
 hipError_t launch_bucket_sort(const SortBuffers &B, hipStream_t s);
+hipError_t launch_build_meta(const SortBuffers &B, const float *a, const float *b, hipStream_t s);
+int meta_stride_for(int R);
 int sort_chunks(long long n, long long m);
 
 hipError_t launch_csr_count(const Handle &h, long long *rowcount, hipStream_t s);
@@ -116,8 +120,8 @@ struct Handle {
     // factors
     float *U;          // n x lp
     float *Wt;         // m x lp
-    float *tiles;      // row-major tiles (rows of X contiguous)
-    float *tilesT;     // transposed tiles (rows of Y contiguous)
+    float *vals_x;     // sparse values, one record per row of X
+    float *vals_y;     // the same values, one record per row of Y
     // state
     float *log_u, *log_v;
     double *lin_u, *lin_v;
@@ -129,6 +133,7 @@ struct Handle {
     double *query_out;         // [2 sides][2]: sum r log u, sum |r - a|
     unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag
     int grid;
+    int grid_cap;              // upper bound on the workgroups of a sweep (0 = default)
 
     hipEvent_t ev0, ev1;
     float last_ms;
