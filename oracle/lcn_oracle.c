@@ -432,19 +432,89 @@ static double vec_max(const double *x, int64_t n)
     return isfinite(mx) ? mx : 0.0;
 }
 
+/* log of (K~ exp(log_in)) per row (or of the transpose per column) for a
+ * kernel without signed parts (dense K or sparse K^sp): the log-sum-exp
+ * trick of App. "Implementational details", log sum_j exp(x_j) = max_j x_j +
+ * log sum_j exp(x_j - max_j x_j) with x_j = log K_ij + log_in_j, so that
+ * nothing over- or underflows however far the scalings drift.  A row/column
+ * without any non-zero term gives -inf. */
+static void lse_apply(const orc_op *op, int transpose, const double *log_in, double *out)
+{
+    int64_t n = op->n, m = op->m;
+    int64_t n_out = transpose ? m : n;
+    double *mx = (double *)malloc(sizeof(double) * (size_t)n_out);
+    double *sm = (double *)malloc(sizeof(double) * (size_t)n_out);
+    for (int64_t o = 0; o < n_out; ++o) {
+        mx[o] = -INFINITY;
+        sm[o] = 0.0;
+    }
+    /* pass 0 finds max_j x_j of every output, pass 1 adds exp(x_j - max) */
+    for (int pass = 0; pass < 2; ++pass) {
+        if (op->Kd) {
+#pragma omp parallel for schedule(static)
+            for (int64_t o = 0; o < n_out; ++o) {
+                int64_t cnt = transpose ? n : m;
+                for (int64_t q = 0; q < cnt; ++q) {
+                    double k = transpose ? op->Kd[q * m + o] : op->Kd[o * m + q];
+                    if (!(k > 0.0)) continue;
+                    double x = log(k) + log_in[q];
+                    if (pass == 0) {
+                        if (x > mx[o]) mx[o] = x;
+                    } else if (x > -INFINITY) {
+                        sm[o] += exp(x - mx[o]);
+                    }
+                }
+            }
+        }
+        if (op->rowptr) {
+            for (int64_t i = 0; i < n; ++i)
+                for (int64_t e = op->rowptr[i]; e < op->rowptr[i + 1]; ++e) {
+                    double k = op->val[e];
+                    if (!(k > 0.0)) continue;
+                    int64_t j = op->colidx[e];
+                    int64_t o = transpose ? j : i;
+                    double x = log(k) + log_in[transpose ? i : j];
+                    if (pass == 0) {
+                        if (x > mx[o]) mx[o] = x;
+                    } else if (x > -INFINITY) {
+                        sm[o] += exp(x - mx[o]);
+                    }
+                }
+        }
+    }
+    for (int64_t o = 0; o < n_out; ++o) out[o] = sm[o] > 0.0 ? mx[o] + log(sm[o]) : -INFINITY;
+    free(mx);
+    free(sm);
+}
+
 /* One scaling update in log form: out_i = log(marg_i) - log(sum_i) where
- * sum = K~ exp(log_in) (or its transpose), evaluated with the largest
- * exponent taken out first (App. "Implementational details", the max-shift of
- * the log-sum-exp trick, applied once per vector because K~ has signed
- * entries and cannot itself be kept as logs).
- * A sum that is exactly zero because the row/column has no entry at all
- * (possible for the sparse kernel, App. "Limitations") gives log scaling
- * -inf, i.e. the point carries no mass, and is counted in *empty.  Any other
- * non-positive sum (possible for Nystrom/LCN, App. "Limitations") is counted
- * in *nonpos and yields NaN. */
+ * sum = K~ exp(log_in) (or its transpose).
+ * Kernels without signed parts (dense, sparse) go through lse_apply.  With a
+ * Nystrom part (Nystrom, LCN) K~ has signed entries and cannot itself be kept
+ * as logs (App. "Limitations": A^{-1} cannot be done in log space); there the
+ * max-shift of the log-sum-exp trick is applied once per vector: the largest
+ * exponent of log_in is taken out before the products are formed.
+ * A row/column of the sparse kernel without any entry (App. "Limitations")
+ * gives log scaling -inf, i.e. the point carries no mass, and is counted in
+ * *empty.  A non-positive sum (possible for Nystrom/LCN, App. "Limitations")
+ * is counted in *nonpos and yields NaN. */
 static void scaling_update(const orc_op *op, int transpose, const double *log_in, int64_t n_in, const double *marg,
                            int64_t n_out, double *log_out, int64_t *nonpos, int64_t *empty)
 {
+    if (op->l == 0) {
+        double *ls = (double *)malloc(sizeof(double) * (size_t)n_out);
+        lse_apply(op, transpose, log_in, ls);
+        for (int64_t i = 0; i < n_out; ++i) {
+            if (ls[i] > -INFINITY) {
+                log_out[i] = log(marg[i]) - ls[i];
+            } else {
+                log_out[i] = -INFINITY;
+                *empty += 1;
+            }
+        }
+        free(ls);
+        return;
+    }
     double M = vec_max(log_in, n_in);
     double *lin = (double *)malloc(sizeof(double) * (size_t)n_in);
     double *sum = (double *)malloc(sizeof(double) * (size_t)n_out);
@@ -456,9 +526,6 @@ static void scaling_update(const orc_op *op, int transpose, const double *log_in
     for (int64_t i = 0; i < n_out; ++i) {
         if (sum[i] > 0.0) {
             log_out[i] = log(marg[i]) - log(sum[i]) - M;
-        } else if (sum[i] == 0.0 && op->l == 0 && !op->Kd) {
-            log_out[i] = -INFINITY;
-            *empty += 1;
         } else {
             log_out[i] = NAN;
             *nonpos += 1;
@@ -515,6 +582,28 @@ void orc_marginals(int64_t n, int64_t m, int l, const double *Kd, const double *
                    double *resid)
 {
     orc_op op = make_op(n, m, l, Kd, U, W, rowptr, colidx, val);
+    double D = 0.0, E = 0.0;
+    if (l == 0) { /* kernels without signed parts: everything stays in logs */
+        double *lr = (double *)malloc(sizeof(double) * (size_t)n);
+        double *lc = (double *)malloc(sizeof(double) * (size_t)m);
+        lse_apply(&op, 0, log_v, lr);
+        lse_apply(&op, 1, log_u, lc);
+        for (int64_t i = 0; i < n; ++i) {
+            r[i] = (isinf(log_u[i]) || isinf(lr[i])) ? 0.0 : exp(log_u[i] + lr[i]);
+            if (r[i] != 0.0) D += r[i] * log_u[i];
+            E += fabs(r[i] - a[i]);
+        }
+        for (int64_t j = 0; j < m; ++j) {
+            c[j] = (isinf(log_v[j]) || isinf(lc[j])) ? 0.0 : exp(log_v[j] + lc[j]);
+            if (c[j] != 0.0) D += c[j] * log_v[j];
+            E += fabs(c[j] - b[j]);
+        }
+        free(lr);
+        free(lc);
+        *dist = lambda * D;
+        *resid = E;
+        return;
+    }
     double Mu = vec_max(log_u, n), Mv = vec_max(log_v, m);
     double *ul = (double *)malloc(sizeof(double) * (size_t)n);
     double *vl = (double *)malloc(sizeof(double) * (size_t)m);
@@ -522,7 +611,6 @@ void orc_marginals(int64_t n, int64_t m, int l, const double *Kd, const double *
     for (int64_t j = 0; j < m; ++j) vl[j] = exp(log_v[j] - Mv);
     op_apply(&op, vl, r);
     op_apply_t(&op, ul, c);
-    double D = 0.0, E = 0.0;
     for (int64_t i = 0; i < n; ++i) {
         r[i] = isinf(log_u[i]) ? 0.0 : exp(log_u[i] + Mv) * r[i];
         if (r[i] != 0.0) D += r[i] * log_u[i];
@@ -533,10 +621,10 @@ void orc_marginals(int64_t n, int64_t m, int l, const double *Kd, const double *
         if (c[j] != 0.0) D += c[j] * log_v[j];
         E += fabs(c[j] - b[j]);
     }
-    *dist = lambda * D;
-    *resid = E;
     free(ul);
     free(vl);
+    *dist = lambda * D;
+    *resid = E;
 }
 
 /* -------------------------------------- bipartite-matching augmentation -- */

@@ -328,7 +328,7 @@ hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lt, double
 __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const float *__restrict__ Z, int d, int cost,
                                                          double inv_lambda, const double *__restrict__ zn,
                                                          const float *__restrict__ U, const float *__restrict__ Wt,
-                                                         int lp, float *vals_x, float *vals_y,
+                                                         int lp, int log_values, float *vals_x, float *vals_y,
                                                          unsigned long long *unique_counter)
 {
     __shared__ float Ps[KCH][LDT];
@@ -411,7 +411,7 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
             double v = 0.0;
             if (gi >= 0 && gj >= 0) {
                 double c = cost_from_acc(acc.v[i][j], cost, zn ? zn[gi] : 0.0, zn ? zn[gj] : 0.0);
-                v = exp(-c * inv_lambda);
+                v = log_values ? -c * inv_lambda : exp(-c * inv_lambda);
             }
             kv[i][j] = v;
         }
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
             bool present = xi[li] >= 0 && yj[lj] >= 0;
             bool dup = false;
             for (int q = 0; q < r; ++q) dup |= bx[q][li] == by[q][lj];
-            if (!present || dup) kv[i][j] = 0.0;
+            if (!present || dup) kv[i][j] = log_values ? -INFINITY : 0.0;
             if (present && !dup) ++mine;
             vals[li][lj] = (float)kv[i][j];
         }
@@ -468,7 +468,7 @@ hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s)
     hipLaunchKernelGGL(correction_kernel, dim3(ntiles), dim3(256), 0, s, h.sort, h.Z, h.d, h.cost, 1.0 / h.lambda,
                        h.cost == LCN_COST_COSINE ? h.zn : (const double *)nullptr,
                        lcn_mode ? h.U : (const float *)nullptr, lcn_mode ? h.Wt : (const float *)nullptr, h.lp,
-                       h.vals_x, h.vals_y, h.counters + 3);
+                       h.log_domain, h.vals_x, h.vals_y, h.counters + 3);
     return hipGetLastError();
 }
 

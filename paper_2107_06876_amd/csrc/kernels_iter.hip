@@ -11,9 +11,14 @@
 // next row's factor entries and metadata are requested before the current
 // row is reduced, so that a wave always has loads in flight.
 //
-// Scalings are kept as fp64 linear values for the arithmetic (range e^+-700,
-// which covers what a log-domain float state can express) and reported as
-// fp32 natural logs; products are accumulated in fp64.
+// Log-domain stabilisation (App. "Implementational details"): the state is the
+// natural log of each scaling (fp32, what is reported).  Because the Nystrom
+// part and the correction have signed entries the kernel cannot itself be held
+// as logs, so the largest exponent is taken out per vector instead: the working
+// copy of a scaling vector is exp(log x - M) in fp64, with M the largest log of
+// that vector one iteration earlier (any reference works; logs move slowly), and
+// M travels with every quantity derived from the vector.  Products are
+// accumulated in fp64.
 #include "lcn_internal.h"
 
 namespace lcn {
@@ -21,6 +26,9 @@ namespace lcn {
 constexpr int PASS_THREADS = 1024;
 constexpr int PASS_WAVES = PASS_THREADS / 64;
 constexpr int MAXR = 8;
+#ifndef PASS_MIN_WAVES
+#define PASS_MIN_WAVES 1
+#endif
 
 // One step of a cross-lane sum of doubles through the DPP data path (no LDS):
 // adds to every lane the value of the lane that `CTRL` selects; lanes of rows
@@ -43,6 +51,30 @@ __device__ inline double wave_sum(double v)
     v = dpp_add<0x140, 0xF>(v);  // row_mirror: every lane of a 16-lane row holds the row's sum
     v = dpp_add<0x142, 0xA>(v);  // row_bcast15 into rows 1 and 3
     v = dpp_add<0x143, 0xC>(v);  // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ inline double dpp_max(double v)
+{
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    // lanes outside ROW_MASK receive their own value back
+    const int plo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, ROW_MASK, 0xF, false);
+    const int phi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, ROW_MASK, 0xF, false);
+    return fmax(v, __hiloint2double(phi, plo));
+}
+
+// Maximum over the 64 lanes of a wavefront; every lane gets the result.
+__device__ inline double wave_max(double v)
+{
+    v = dpp_max<0xB1, 0xF>(v);
+    v = dpp_max<0x4E, 0xF>(v);
+    v = dpp_max<0x141, 0xF>(v);
+    v = dpp_max<0x140, 0xF>(v);
+    v = dpp_max<0x142, 0xA>(v);
+    v = dpp_max<0x143, 0xC>(v);
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
     return __hiloint2double(hi, lo);
@@ -126,18 +158,22 @@ __device__ inline void load_meta(RowMeta<RR> &M, const PassSide &S, int R, long 
 }
 
 template <int T, int RR, int MODE>
-__global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, int lp, double *partial,
-                                                            double *zero_buf, int use_atomics,
-                                                            unsigned long long *counters, int empty_slot,
-                                                            double *query_out)
+__global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(PassSide S, int R, int lp, double *partial,
+                                                            unsigned long long *counters, int empty_slot)
 {
     constexpr int TT = T > 0 ? T : 1;
-    extern __shared__ double zsh[];  // [PASS_WAVES / 2][lp + 2]
+    extern __shared__ double zsh[];  // [PASS_WAVES / 2][lp + 3]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long long nwaves = (long long)gridDim.x * PASS_WAVES;
     const long long gw = (long long)blockIdx.x * PASS_WAVES + wave;
-    const int stride = lp + 2;
+    const int stride = lp + 3;
+    // exponents taken out of this side's vector (m_self) and of the input vectors (m_in)
+    // (a query reads the exponent its vector was stored with, kept beside the accumulator it produced)
+    const double m_self = MODE == PASS_QUERY ? S.acc_out[lp] : *S.shift_self;
+    const double m_in = MODE != PASS_INIT ? S.acc_in[lp] : 0.0;
+    const double e_out = MODE == PASS_UPDATE ? exp(-m_in - m_self) : (MODE == PASS_QUERY ? exp(m_in + m_self) : 1.0);
+    double maxlog = -INFINITY;
 
     double yreg[TT], zacc[TT];
 #pragma unroll
@@ -147,9 +183,6 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     }
     double q0 = 0.0, q1 = 0.0;
     unsigned long long nonpos = 0, empty = 0;
-    // the accumulator that the launch after this one adds into is cleared here
-    if (zero_buf && blockIdx.x == 0)
-        for (int k = threadIdx.x; k < lp; k += PASS_THREADS) zero_buf[k] = 0.0;
 
     FRow<T> cur{}, nxt{};
     RowMeta<RR> mc{}, mn{};
@@ -166,7 +199,9 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
                 nxt.load(S.F, next, lp, lane);
                 load_meta<RR, MODE>(mn, S, R, next, lane);
             }
-            out = exp((double)S.log_out[row]);
+            const double lo = (double)S.log_out[row];
+            out = exp(lo - m_self);
+            if (lo > maxlog && lo < INFINITY) maxlog = lo;
         } else {
             // sparse part: the first 64 entries of every round's segment are requested
             // before anything is used; what is left of long segments follows
@@ -209,9 +244,11 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
             if (MODE == PASS_UPDATE) {
                 float lo;
                 if (s > 0.0) {
-                    out = marg * fast_rcp(s);
-                    lo = (float)(mc.log_marg - fast_log(s));
-                } else if (T == 0 && total_len == 0) {
+                    out = marg * fast_rcp(s) * e_out;
+                    const double lg = mc.log_marg - fast_log(s) - m_in;
+                    lo = (float)lg;
+                    maxlog = fmax(maxlog, lg);
+                } else if (T == 0 && s == 0.0) {  // no kernel entry (or only zero ones): the point carries no mass
                     out = 0.0;
                     lo = -INFINITY;
                     ++empty;
@@ -223,9 +260,9 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
                 if (lane == 0) S.log_out[row] = lo;
             } else {  // PASS_QUERY
                 out = mc.lin;
-                const double ri = out * s;
+                const double ri = out * s * e_out;
                 if (lane == 0 && S.marg_out) S.marg_out[row] = (float)ri;
-                if (out > 0.0) q0 += ri * log(out);
+                if (out > 0.0) q0 += ri * (log(out) + m_self);
                 q1 += fabs(ri - marg);
             }
         }
@@ -254,6 +291,7 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
         if (lane == 0) {
             mine[lp] = q0;
             mine[lp + 1] = q1;
+            mine[lp + 2] = maxlog;
         }
     }
     __syncthreads();
@@ -265,22 +303,15 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
         if (lane == 0) {
             mine[lp] += q0;
             mine[lp + 1] += q1;
+            mine[lp + 2] = fmax(mine[lp + 2], maxlog);
         }
     }
     __syncthreads();
     for (int k = threadIdx.x; k < stride; k += PASS_THREADS) {
-        double s = 0.0;
+        double s = k == lp + 2 ? -INFINITY : 0.0;
 #pragma unroll
-        for (int w = 0; w < HALF; ++w) s += zsh[w * stride + k];
-        if (use_atomics) {
-            if (k < lp) {
-                if (MODE != PASS_QUERY) unsafeAtomicAdd(&S.acc_out[k], s);
-            } else if (MODE == PASS_QUERY) {
-                unsafeAtomicAdd(&query_out[k - lp], s);
-            }
-        } else {
-            partial[(long long)blockIdx.x * stride + k] = s;
-        }
+        for (int w = 0; w < HALF; ++w) s = k == lp + 2 ? fmax(s, zsh[w * stride + k]) : s + zsh[w * stride + k];
+        partial[(long long)blockIdx.x * stride + k] = s;
     }
     if (lane == 0 && (nonpos | empty)) {
         if (nonpos) atomicAdd(&counters[0], nonpos);
@@ -288,33 +319,171 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(PassSide S, int R, i
     }
 }
 
+// The half-iteration for kernels without signed parts (sparse K^sp, and the
+// dense kernel as its one-bucket case), entirely in logs: the stored values
+// are log K_ij = -C_ij / lambda, the vectors are log scalings, and a row's sum
+// is a log-sum-exp (App. "Implementational details") with a running maximum per
+// lane, so that scalings may drift arbitrarily far (a sparse kernel need not
+// have support, App. "Limitations") without over- or underflow.
+__device__ inline void lse_step(double t, double &mx, double &sm)
+{
+    if (t > -INFINITY) {
+        const double d = t - mx;
+        const double e = (double)__expf(-fabsf((float)d));
+        if (d > 0.0) {
+            sm = fma(sm, e, 1.0);
+            mx = t;
+        } else {
+            sm += e;
+        }
+    }
+}
+
+template <int RR, int MODE>
+__global__ __launch_bounds__(PASS_THREADS) void logpass_kernel(PassSide S, int R, double *partial,
+                                                               unsigned long long *counters, int empty_slot)
+{
+    __shared__ double qsh[PASS_WAVES][2];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long nwaves = (long long)gridDim.x * PASS_WAVES;
+    double q0 = 0.0, q1 = 0.0;
+    unsigned long long empty = 0;
+
+    RowMeta<RR> mc{}, mn{};
+    long long row = (long long)blockIdx.x * PASS_WAVES + wave;
+    if (row < S.rows) load_meta<RR, MODE>(mc, S, R, row, lane);
+    while (row < S.rows) {
+        const long long next = row + nwaves;
+        double lg;
+        if (MODE == PASS_INIT) {
+            if (next < S.rows) load_meta<RR, MODE>(mn, S, R, next, lane);
+            lg = (double)S.log_out[row];
+        } else {
+            const float *__restrict__ vals = S.vals + mc.base;
+            double mx = -INFINITY, sm = 0.0;
+            {
+                double t0[RR];
+                int segoff[RR];
+                int total_len = 0;
+#pragma unroll
+                for (int r = 0; r < RR; ++r) {
+                    segoff[r] = total_len;
+                    total_len += mc.len[r];
+                    t0[r] = lane < mc.len[r] ? (double)vals[segoff[r] + lane] + S.perm_in[mc.vstart[r] + lane]
+                                             : -INFINITY;
+                }
+                if (next < S.rows) load_meta<RR, MODE>(mn, S, R, next, lane);
+#pragma unroll
+                for (int r = 0; r < RR; ++r) lse_step(t0[r], mx, sm);
+#pragma unroll
+                for (int r = 0; r < RR; ++r) {
+                    if (mc.len[r] > 64) {
+                        const float *tp = vals + segoff[r];
+                        const double *vp = S.perm_in + mc.vstart[r];
+#pragma unroll 2
+                        for (int e = 64 + lane; e < mc.len[r]; e += 64) lse_step((double)tp[e] + vp[e], mx, sm);
+                    }
+                }
+            }
+            const double M = wave_max(mx);
+            const double part = mx > -INFINITY ? sm * exp(mx - M) : 0.0;
+            const double ssum = wave_sum(part);
+            const double lse = ssum > 0.0 ? M + log(ssum) : -INFINITY;
+            if (MODE == PASS_UPDATE) {
+                if (lse > -INFINITY) {
+                    lg = mc.log_marg - lse;
+                } else {  // no kernel entry reaches this point: it carries no mass
+                    lg = -INFINITY;
+                    ++empty;
+                }
+                if (lane == 0) S.log_out[row] = (float)lg;
+            } else {  // PASS_QUERY
+                lg = mc.lin;
+                const double ri = (lg > -INFINITY && lse > -INFINITY) ? exp(lg + lse) : 0.0;
+                if (lane == 0 && S.marg_out) S.marg_out[row] = (float)ri;
+                if (ri != 0.0) q0 += ri * lg;
+                q1 += fabs(ri - (double)mc.marg);
+            }
+        }
+        if (MODE != PASS_QUERY) {
+            if (lane == 0) S.lin_out[row] = lg;
+            if (lane < R) S.perm_out[(long long)lane * S.rows + mc.pos] = lg;
+        }
+        mc = mn;
+        row = next;
+    }
+    if (MODE == PASS_QUERY) {
+        if (lane == 0) {
+            qsh[wave][0] = q0;
+            qsh[wave][1] = q1;
+        }
+        __syncthreads();
+        if (threadIdx.x < 3) {
+            double s = threadIdx.x == 2 ? -INFINITY : 0.0;
+            if (threadIdx.x < 2)
+                for (int w = 0; w < PASS_WAVES; ++w) s += qsh[w][threadIdx.x];
+            partial[(long long)blockIdx.x * 3 + threadIdx.x] = s;
+        }
+    }
+    if (lane == 0 && empty) atomicAdd(&counters[empty_slot], empty);
+}
+
 // Adds the per-workgroup partial sums of a sweep in a fixed order (so the
 // result does not depend on timing).  One workgroup per 64 entries; wave w adds
 // the partials of workgroups w, w + 16, ..., then the 16 wave sums are added.
+// Entry lp + 2 is a maximum (the largest log scaling of the sweep), which
+// becomes this side's exponent for the next sweep; entry lp of the output
+// accumulator records the exponent that this sweep's vector was stored with.
 __global__ __launch_bounds__(1024) void reduce_partials_kernel(const double *__restrict__ partial, int groups,
                                                                int stride, int lp, double *acc_out,
-                                                               double *query_out, int is_query)
+                                                               double *query_out, double *shift_self, int mode)
 {
     __shared__ double sh[16][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int k = blockIdx.x * 64 + lane;
-    double s = 0.0;
+    const bool is_max = k == lp + 2;
+    double s = is_max ? -INFINITY : 0.0;
     if (k < stride) {
 #pragma unroll 16
-        for (int g = wave; g < groups; g += 16) s += partial[(long long)g * stride + k];
+        for (int g = wave; g < groups; g += 16) {
+            const double v = partial[(long long)g * stride + k];
+            s = is_max ? fmax(s, v) : s + v;
+        }
     }
     sh[wave][lane] = s;
     __syncthreads();
     if (wave == 0 && k < stride) {
-        s = 0.0;
+        s = is_max ? -INFINITY : 0.0;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) s += sh[w][lane];
+        for (int w = 0; w < 16; ++w) s = is_max ? fmax(s, sh[w][lane]) : s + sh[w][lane];
         if (k < lp) {
-            if (!is_query) acc_out[k] = s;
-        } else if (is_query) {
-            query_out[k - lp] = s;
+            if (mode != PASS_QUERY) acc_out[k] = s;
+        } else if (k < lp + 2) {
+            if (mode == PASS_QUERY) query_out[k - lp] = s;
+        } else if (mode != PASS_QUERY) {
+            acc_out[lp] = *shift_self;                              // exponent used by this sweep
+            *shift_self = (s > -INFINITY && s < INFINITY) ? s : 0.0;  // exponent for the next one
         }
     }
+}
+
+// largest finite entry of a float vector (0 if there is none); one workgroup
+__global__ __launch_bounds__(1024) void max_log_kernel(const float *__restrict__ x, long long n, double *out)
+{
+    __shared__ float sh[1024];
+    float m = -INFINITY;
+    for (long long i = threadIdx.x; i < n; i += 1024) {
+        const float v = x[i];
+        if (v > m && v < INFINITY) m = v;
+    }
+    sh[threadIdx.x] = m;
+    __syncthreads();
+    for (int o = 512; o > 0; o >>= 1) {
+        if (threadIdx.x < o) sh[threadIdx.x] = fmaxf(sh[threadIdx.x], sh[threadIdx.x + o]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = sh[0] > -INFINITY ? (double)sh[0] : 0.0;
 }
 
 int pass_grid(const Handle &h)
@@ -326,43 +495,40 @@ int pass_grid(const Handle &h)
 }
 
 template <int T, int RR>
-static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, int mode, double *zero_buf,
-                                 hipStream_t s)
+static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, int mode, hipStream_t s)
 {
     long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
     int grid = (int)(g < h.grid ? g : h.grid);
-    size_t lds = sizeof(double) * (size_t)(PASS_WAVES / 2) * (h.lp + 2);
+    const int stride = h.lp + 3;
+    size_t lds = sizeof(double) * (size_t)(PASS_WAVES / 2) * stride;
     double *qout = h.query_out + 2 * side;
     int empty_slot = 1 + side;
+    if (mode == PASS_INIT)
+        hipLaunchKernelGGL(max_log_kernel, dim3(1), dim3(1024), 0, s, S.log_out, S.rows, S.shift_self);
     if (mode == PASS_UPDATE)
         hipLaunchKernelGGL((pass_kernel<T, RR, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
+                           h.partial, h.counters, empty_slot);
     else if (mode == PASS_QUERY)
         hipLaunchKernelGGL((pass_kernel<T, RR, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
+                           h.partial, h.counters, empty_slot);
     else
         hipLaunchKernelGGL((pass_kernel<T, RR, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, zero_buf, h.use_atomics, h.counters, empty_slot, qout);
-    if (!h.use_atomics) {
-        const int stride = h.lp + 2;
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(1024), 0, s, h.partial, grid,
-                           stride, h.lp, S.acc_out, qout, mode == PASS_QUERY ? 1 : 0);
-    }
+                           h.partial, h.counters, empty_slot);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(1024), 0, s, h.partial, grid, stride,
+                       h.lp, S.acc_out, qout, S.shift_self, mode);
     return hipGetLastError();
 }
 
 template <int T>
-static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, double *zero_buf,
-                                hipStream_t s)
+static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, hipStream_t s)
 {
-    if (h.R <= 4) return launch_pass_tr<T, 4>(S, h, side, mode, zero_buf, s);
-    return launch_pass_tr<T, 8>(S, h, side, mode, zero_buf, s);
+    if (h.R <= 4) return launch_pass_tr<T, 4>(S, h, side, mode, s);
+    return launch_pass_tr<T, 8>(S, h, side, mode, s);
 }
 
 // side 0: rows of X (updates u, consumes y = W v, produces z = U^T u); side 1: rows of Y.
-// acc_in / acc_out / acc_zero index the three rotating accumulator buffers (-1: none).
-hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, int acc_zero, float *marg_out,
-                       hipStream_t s)
+// acc_in / acc_out index the accumulator buffers (-1: none).
+hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s)
 {
     PassSide S;
     if (side == 0) {
@@ -388,17 +554,47 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
     S.acc_out = acc_out >= 0 ? h.acc[acc_out] : nullptr;
     S.marg_out = marg_out;
     S.meta_stride = h.sort.meta_stride;
-    double *zb = (acc_zero >= 0 && h.use_atomics) ? h.acc[acc_zero] : nullptr;
+    S.shift_self = h.shift + side;
+    if (h.log_domain) {
+        long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
+        const int grid = (int)(g < h.grid ? g : h.grid);
+        const int empty_slot = 1 + side;
+        if (h.R <= 4) {
+            if (mode == PASS_UPDATE)
+                hipLaunchKernelGGL((logpass_kernel<4, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                                   h.partial, h.counters, empty_slot);
+            else if (mode == PASS_QUERY)
+                hipLaunchKernelGGL((logpass_kernel<4, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                                   h.partial, h.counters, empty_slot);
+            else
+                hipLaunchKernelGGL((logpass_kernel<4, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                                   h.partial, h.counters, empty_slot);
+        } else {
+            if (mode == PASS_UPDATE)
+                hipLaunchKernelGGL((logpass_kernel<8, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                                   h.partial, h.counters, empty_slot);
+            else if (mode == PASS_QUERY)
+                hipLaunchKernelGGL((logpass_kernel<8, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                                   h.partial, h.counters, empty_slot);
+            else
+                hipLaunchKernelGGL((logpass_kernel<8, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                                   h.partial, h.counters, empty_slot);
+        }
+        if (mode == PASS_QUERY)
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(1024), 0, s, h.partial, grid, 3, 0, S.acc_out,
+                               h.query_out + 2 * side, S.shift_self, mode);
+        return hipGetLastError();
+    }
     switch (h.lp / 64) {
-        case 0: return launch_pass_t<0>(S, h, side, mode, zb, s);
-        case 1: return launch_pass_t<1>(S, h, side, mode, zb, s);
-        case 2: return launch_pass_t<2>(S, h, side, mode, zb, s);
-        case 3: return launch_pass_t<3>(S, h, side, mode, zb, s);
-        case 4: return launch_pass_t<4>(S, h, side, mode, zb, s);
-        case 5: return launch_pass_t<5>(S, h, side, mode, zb, s);
-        case 6: return launch_pass_t<6>(S, h, side, mode, zb, s);
-        case 7: return launch_pass_t<7>(S, h, side, mode, zb, s);
-        case 8: return launch_pass_t<8>(S, h, side, mode, zb, s);
+        case 0: return launch_pass_t<0>(S, h, side, mode, s);
+        case 1: return launch_pass_t<1>(S, h, side, mode, s);
+        case 2: return launch_pass_t<2>(S, h, side, mode, s);
+        case 3: return launch_pass_t<3>(S, h, side, mode, s);
+        case 4: return launch_pass_t<4>(S, h, side, mode, s);
+        case 5: return launch_pass_t<5>(S, h, side, mode, s);
+        case 6: return launch_pass_t<6>(S, h, side, mode, s);
+        case 7: return launch_pass_t<7>(S, h, side, mode, s);
+        case 8: return launch_pass_t<8>(S, h, side, mode, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -542,8 +542,8 @@ __device__ inline bool owned_by_earlier_round(const int32_t *bucket, long long N
 }
 
 template <bool FILL>
-__global__ void csr_kernel(SortBuffers B, const float *vals, long long *rowcount, const long long *rowptr,
-                           int32_t *colidx, float *val)
+__global__ void csr_kernel(SortBuffers B, const float *vals, int log_values, long long *rowcount,
+                           const long long *rowptr, int32_t *colidx, float *val)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B.n) return;
@@ -579,7 +579,10 @@ __global__ void csr_kernel(SortBuffers B, const float *vals, long long *rowcount
         if (bestr < 0) break;
         if (FILL) {
             colidx[outp] = bestj;
-            if (val) val[outp] = vals[base + segstart[bestr] + head[bestr]];
+            if (val) {
+                const float v = vals[base + segstart[bestr] + head[bestr]];
+                val[outp] = log_values ? expf(v) : v;
+            }
             ++outp;
         }
         ++cnt;
@@ -591,14 +594,14 @@ __global__ void csr_kernel(SortBuffers B, const float *vals, long long *rowcount
 hipError_t launch_csr_count(const Handle &h, long long *rowcount, hipStream_t s)
 {
     hipLaunchKernelGGL(csr_kernel<false>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.vals_x,
-                       rowcount, (const long long *)nullptr, (int32_t *)nullptr, (float *)nullptr);
+                       h.log_domain, rowcount, (const long long *)nullptr, (int32_t *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_csr_fill(const Handle &h, const long long *rowptr, int32_t *colidx, float *val, hipStream_t s)
 {
     hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.vals_x,
-                       (long long *)nullptr, rowptr, colidx, val);
+                       h.log_domain, (long long *)nullptr, rowptr, colidx, val);
     return hipGetLastError();
 }
 

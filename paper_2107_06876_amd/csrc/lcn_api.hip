@@ -135,9 +135,10 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.lin_v = bump.take<double>((size_t)h.m);
     h.perm_u = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.n);
     h.perm_v = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.m);
-    for (int i = 0; i < 3; ++i) h.acc[i] = bump.take<double>(lp1);
+    for (int i = 0; i < 2; ++i) h.acc[i] = bump.take<double>(lp1 + 1);
+    h.shift = bump.take<double>(2);
     h.grid = pass_grid(h);
-    h.partial = bump.take<double>((size_t)h.grid * (h.lp + 2));
+    h.partial = bump.take<double>((size_t)h.grid * (h.lp + 3));
 }
 
 lcn_status check_params(long long n, long long m, int d, int dtype, float lambda, int cost, int mode,
@@ -181,6 +182,7 @@ void fill_shape(Handle &h, long long n, long long m, int d, int mode, const lcn_
     h.m = m;
     h.d = d;
     h.mode = mode;
+    h.log_domain = (mode == LCN_MODE_SPARSE || mode == LCN_MODE_DENSE) ? 1 : 0;
     h.l = uses_landmarks(mode) ? lm->num_landmarks : 0;
     h.lp = (h.l + 63) / 64 * 64;
     if (uses_lsh(mode)) {
@@ -231,15 +233,12 @@ lcn_status status_from_counters(Handle &h)
     return LCN_OK;
 }
 
-// From the stored log scalings: linear copies, bucket-ordered copies, and the
-// accumulators z = U^T u (buffer 2) and y = W v (buffer 0); phase 0.
+// From the stored log scalings: working copies, bucket-ordered copies, and the
+// accumulators z = U^T u (buffer 1) and y = W v (buffer 0).
 lcn_status init_state(Handle &h)
 {
-    const size_t lp1 = h.lp > 0 ? h.lp : 1;
-    for (int i = 0; i < 3; ++i) HIPCHK(hipMemsetAsync(h.acc[i], 0, sizeof(double) * lp1, h.stream));
-    HIPCHK(launch_pass(h, 0, PASS_INIT, -1, 2, -1, nullptr, h.stream));
-    HIPCHK(launch_pass(h, 1, PASS_INIT, -1, 0, -1, nullptr, h.stream));
-    h.phase = 0;
+    HIPCHK(launch_pass(h, 0, PASS_INIT, -1, 1, nullptr, h.stream));
+    HIPCHK(launch_pass(h, 1, PASS_INIT, -1, 0, nullptr, h.stream));
     return LCN_OK;
 }
 
@@ -394,10 +393,6 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     // scalings start at 1 (eq. 2)
     HIPCHK(hipMemsetAsync(h.log_u, 0, sizeof(float) * (size_t)n, h.stream));
     HIPCHK(hipMemsetAsync(h.log_v, 0, sizeof(float) * (size_t)m, h.stream));
-    {
-        const char *env = getenv("LCN_ACC_ATOMICS");
-        h.use_atomics = env ? atoi(env) : 0;
-    }
     st = init_state(h);
     if (st != LCN_OK) return st;
 
@@ -421,10 +416,9 @@ lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
     if (iters < 0) return LCN_ERR_INVALID_ARG;
     Handle &h = *(Handle *)hh;
     HIPCHK(hipEventRecord(h.ev0, h.stream));
-    for (int it = 0; it < 2 * iters; ++it) {
-        const int t = h.phase;
-        HIPCHK(launch_pass(h, it & 1, PASS_UPDATE, t % 3, (t + 1) % 3, (t + 2) % 3, nullptr, h.stream));
-        h.phase = t + 1;
+    for (int it = 0; it < iters; ++it) {
+        HIPCHK(launch_pass(h, 0, PASS_UPDATE, 0, 1, nullptr, h.stream));  // u from y = W v; produces z = U^T u
+        HIPCHK(launch_pass(h, 1, PASS_UPDATE, 1, 0, nullptr, h.stream));  // v from z; produces y
     }
     HIPCHK(hipEventRecord(h.ev1, h.stream));
     lcn_status st = status_from_counters(h);
@@ -438,11 +432,8 @@ lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
 
 static lcn_status query(Handle &h, float *row_dev, float *col_dev, double q[4])
 {
-    // y = W v is the input of the next sweep (buffer phase % 3); z = U^T u was the
-    // input of the last sweep over Y (buffer (phase + 2) % 3)
-    HIPCHK(hipMemsetAsync(h.query_out, 0, 4 * sizeof(double), h.stream));
-    HIPCHK(launch_pass(h, 0, PASS_QUERY, h.phase % 3, -1, -1, row_dev, h.stream));
-    HIPCHK(launch_pass(h, 1, PASS_QUERY, (h.phase + 2) % 3, -1, -1, col_dev, h.stream));
+    HIPCHK(launch_pass(h, 0, PASS_QUERY, 0, 1, row_dev, h.stream));  // acc_out is only read (its exponent slot)
+    HIPCHK(launch_pass(h, 1, PASS_QUERY, 1, 0, col_dev, h.stream));
     HIPCHK(hipMemcpyAsync(q, h.query_out, 4 * sizeof(double), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
     return LCN_OK;

@@ -30,8 +30,9 @@ struct PassSide {
     double *lin_out;        // u or v, linear, by original index
     double *perm_out;       // [R][rows] u or v in bucket order of each round
     const double *perm_in;  // [R][other] the other side's scaling in bucket order
-    const double *acc_in;   // lp: y = W v (for rows of U) or z = U^T u (for rows of W^T)
-    double *acc_out;        // lp: accumulated F^T out
+    const double *acc_in;   // lp + 1: y = W v (for rows of U) or z = U^T u (for rows of W^T), then its exponent
+    double *acc_out;        // lp + 1: accumulated F^T out, then the exponent taken out of `out`
+    double *shift_self;     // exponent taken out of this side's scaling vector (updated every sweep)
     float *marg_out;        // query mode: plan marginal of each row (nullable)
 };
 
@@ -93,8 +94,7 @@ hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N,
 hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s);
 
 // ---- iteration (kernels_iter.hip) ------------------------------------------
-hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, int acc_zero, float *marg_out,
-                       hipStream_t s);
+hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s);
 int pass_grid(const Handle &h);
 
 struct Handle {
@@ -102,6 +102,7 @@ struct Handle {
     long long n, m;
     int d, l, lp, R, b;
     int mode, cost, hash;
+    int log_domain;            // kernel without signed parts (sparse, dense): values and vectors are logs
     double lambda, ridge;
     hipStream_t stream;
     char *ws;
@@ -126,9 +127,8 @@ struct Handle {
     float *log_u, *log_v;
     double *lin_u, *lin_v;
     double *perm_u, *perm_v;   // [R][n], [R][m]
-    double *acc[3];            // lp each, rotating: launch t reads acc[t%3], adds into acc[(t+1)%3]
-    int phase;                 // number of half-iterations launched since the scalings were (re)set
-    int use_atomics;           // accumulate F^T out with fp64 atomics instead of partials + reduce kernel
+    double *acc[2];            // lp + 1 each: [0] y = W v, [1] z = U^T u, each followed by its exponent
+    double *shift;             // [2]: exponent taken out of u and of v
     double *partial;           // [grid][lp + 2]
     double *query_out;         // [2 sides][2]: sum r log u, sum |r - a|
     unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag

@@ -80,6 +80,16 @@ def compare(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, it
         scale = np.abs(B.op.val).max() if B.op.val.size else 1.0
         out["val_abs_over_max"] = float(np.max(np.abs(v - B.op.val)) / scale) if v.size else 0.0
         assert out["val_abs_over_max"] < 2e-6
+    if st.nonpositive > 0:
+        # the Nystrom part went negative (App. "Limitations"): both sides must say so; the first
+        # sweep's count of non-positive sums may differ by the few sums that are zero to rounding
+        status = lcn.sinkhorn_run(h, iters, check=False)
+        info = lcn.lcn_get_info(h)
+        out.update(status=status, nonpositive_gpu=info.nonpositive, nonpositive_oracle=st.nonpositive)
+        assert status == lcn.binding.ERR_NONPOSITIVE, out
+        assert abs(info.nonpositive - st.nonpositive) <= max(4, 0.02 * st.nonpositive), out
+        lcn.lcn_destroy(h)
+        return out
     status = lcn.sinkhorn_run(h, iters)
     lu, lv = lcn.lcn_get_scalings(h)
     lu, lv = lu.cpu().numpy().astype(np.float64), lv.cpu().numpy().astype(np.float64)

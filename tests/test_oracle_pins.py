@@ -590,3 +590,37 @@ def test_bp_single_pair_closed_form_and_infinite_deletion_cost():
     bal = oracle.sinkhorn(Operator(n, n, Kd=Kxy), abp[:n], abp[:n], 40)
     np.testing.assert_allclose(sbp.log_u[:n], bal.log_u, atol=1e-12)
     np.testing.assert_allclose(sbp.log_v[:n], bal.log_v, atol=1e-12)
+
+
+def test_log_domain_path_survives_diverging_scalings_and_matches_library_logsumexp():
+    """A sparse kernel without support (App. "Limitations": non-square blocks)
+    makes the scalings drift without bound; the log-sum-exp form (App.
+    "Implementational details") must keep working far beyond the range of
+    exp(), and agree with the same iteration written with the library's
+    logsumexp."""
+    import scipy.special
+    r = rng(23)
+    n, m = 7, 5
+    K = np.zeros((n, m))
+    K[:5, :2] = r.random((5, 2)) + 0.1      # block with 5 rows, 2 columns
+    K[5:, 2:] = r.random((2, 3)) + 0.1      # block with 2 rows, 3 columns
+    rows, cols = np.nonzero(K)
+    rowptr = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=n))]).astype(np.int64)
+    op = Operator(n, m, rowptr=rowptr, colidx=cols.astype(np.int32), val=K[rows, cols])
+    a = np.full(n, 1 / n)
+    b = np.full(m, 1 / m)
+    iters = 3000
+    st = oracle.sinkhorn(op, a, b, iters)
+    with np.errstate(divide="ignore"):
+        logK = np.log(K)
+    lu, lv = np.zeros(n), np.zeros(m)
+    for _ in range(iters):
+        lu = np.log(a) - scipy.special.logsumexp(logK + lv[None, :], axis=1)
+        lv = np.log(b) - scipy.special.logsumexp(logK + lu[:, None], axis=0)
+    assert np.abs(lu).max() > 800          # far outside what exp() can represent
+    np.testing.assert_allclose(st.log_u, lu, rtol=1e-10, atol=1e-8)
+    np.testing.assert_allclose(st.log_v, lv, rtol=1e-10, atol=1e-8)
+    assert st.nonpositive == 0 and st.empty_rows == 0
+    rr, cc, dist, resid = oracle.marginals(op, a, b, 1.0, st)
+    assert np.isfinite(dist) and np.isfinite(resid)
+    np.testing.assert_allclose(cc, b, atol=1e-12)   # columns were scaled last
