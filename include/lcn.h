@@ -161,6 +161,7 @@ typedef struct {
     int64_t nnz_stored, nnz_unique;
     int64_t nonpositive, empty_rows, empty_cols;
     size_t workspace_used;
+    int64_t undecided_last; /* points the MFMA filter left to the exact rule in the last k-means assignment */
 } lcn_info;
 lcn_status lcn_get_info(lcn_handle h, lcn_info *info_host);
 

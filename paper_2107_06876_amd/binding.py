@@ -33,7 +33,8 @@ class Info(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int64), ("m", ctypes.c_int64), ("d", ctypes.c_int32), ("l", ctypes.c_int32),
                 ("rounds", ctypes.c_int32), ("buckets", ctypes.c_int32), ("nnz_stored", ctypes.c_int64),
                 ("nnz_unique", ctypes.c_int64), ("nonpositive", ctypes.c_int64), ("empty_rows", ctypes.c_int64),
-                ("empty_cols", ctypes.c_int64), ("workspace_used", ctypes.c_size_t)]
+                ("empty_cols", ctypes.c_int64), ("workspace_used", ctypes.c_size_t),
+                ("undecided_last", ctypes.c_int64)]
 
 
 class LcnError(RuntimeError):

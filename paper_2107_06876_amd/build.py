@@ -15,6 +15,7 @@ LIB = os.path.join(HERE, "liblcn_hip.so")
 SOURCES = {
     "kernels_structure.hip": ["-ffp-contract=off"],   # bucket rule: separate multiply and add
     "kernels_factors.hip": [],
+    "kernels_mfma.hip": [],
     "kernels_iter.hip": [],
     "kernels_batched.hip": [],
     "lcn_api.hip": [],

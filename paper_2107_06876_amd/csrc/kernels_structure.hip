@@ -72,16 +72,23 @@ constexpr int LDT = TILE + 4;
 
 template <int KIND>
 __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ Z, long long N, int d,
-                                                     const float *__restrict__ C, int k, int32_t *__restrict__ out)
+                                                     const float *__restrict__ C, int k, int32_t *__restrict__ out,
+                                                     const int *__restrict__ list, const int *__restrict__ list_count)
 {
     __shared__ float Ps[KCH][LDT];
     __shared__ float Cs[KCH][LDT];
     __shared__ double red_v[TILE][17];
     __shared__ int red_i[TILE][17];
+    __shared__ long long pidx[TILE];  // the 64 points of this workgroup (-1: none)
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const long long p0 = (long long)blockIdx.x * TILE;
+    // with a list, only the listed points are decided (those the MFMA filter could not)
+    const long long cnt = list ? (long long)*list_count : N;
+    if (p0 >= cnt) return;
+    if (tid < TILE) pidx[tid] = p0 + tid < cnt ? (list ? (long long)list[p0 + tid] : p0 + tid) : -1;
+    __syncthreads();
 
     double bestv[4];
     int besti[4];
@@ -107,9 +114,9 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ Z
 #pragma unroll
                 for (int pass = 0; pass < 8; ++pass) {
                     int r = r0 + pass * 8;
-                    long long p = p0 + r;
+                    long long p = pidx[r];
                     float v = 0.f;
-                    if (p < N && k0 + kk < d) v = Z[p * d + k0 + kk];
+                    if (p >= 0 && k0 + kk < d) v = Z[p * d + k0 + kk];
                     Ps[kk][r] = v;
                 }
                 if (KIND == 0) {
@@ -208,15 +215,71 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ Z
                 bi = ix;
             }
         }
-        if (p0 + tid < N) out[p0 + tid] = bi;
+        if (pidx[tid] >= 0) out[pidx[tid]] = bi;
+    }
+}
+
+// Exact rule for a (short) list of points: one workgroup per listed point, one
+// thread per centroid (strided), each adding the dimensions left to right.
+__global__ __launch_bounds__(256) void assign_list_kernel(const float *__restrict__ Z, int d,
+                                                          const float *__restrict__ C, int k,
+                                                          int32_t *__restrict__ out, const int *__restrict__ list,
+                                                          const int *__restrict__ list_count)
+{
+    extern __shared__ float zrow[];  // d floats
+    __shared__ double bv_sh[256];
+    __shared__ int bi_sh[256];
+    const int cnt = *list_count;
+    for (int it = blockIdx.x; it < cnt; it += gridDim.x) {
+        const long long p = list[it];
+        __syncthreads();
+        for (int j = threadIdx.x; j < d; j += 256) zrow[j] = Z[p * d + j];
+        __syncthreads();
+        double bv = 0.0;
+        int bi = -1;
+        for (int c = threadIdx.x; c < k; c += 256) {
+            const float *cr = C + (long long)c * d;
+            double s = 0.0;
+            for (int j = 0; j < d; ++j) {
+                double t = (double)zrow[j] - (double)cr[j];
+                double t2 = t * t;
+                s = s + t2;
+            }
+            if (bi < 0 || s < bv) {  // ascending c: strict < keeps the lowest index
+                bv = s;
+                bi = c;
+            }
+        }
+        bv_sh[threadIdx.x] = bv;
+        bi_sh[threadIdx.x] = bi;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (threadIdx.x < o) {
+                const double v2 = bv_sh[threadIdx.x + o];
+                const int i2 = bi_sh[threadIdx.x + o];
+                const double v1 = bv_sh[threadIdx.x];
+                const int i1 = bi_sh[threadIdx.x];
+                if (i2 >= 0 && (i1 < 0 || v2 < v1 || (v2 == v1 && i2 < i1))) {
+                    bv_sh[threadIdx.x] = v2;
+                    bi_sh[threadIdx.x] = i2;
+                }
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) out[p] = bi_sh[0];
     }
 }
 
 hipError_t launch_assign_kmeans(const float *Z, long long N, int d, const float *cent, int k, int32_t *out,
-                                hipStream_t s)
+                                const int *list, const int *list_count, hipStream_t s)
 {
+    if (list) {
+        hipLaunchKernelGGL(assign_list_kernel, dim3(2048), dim3(256), sizeof(float) * (size_t)d, s, Z, d, cent, k, out,
+                           list, list_count);
+        return hipGetLastError();
+    }
     int grid = (int)((N + TILE - 1) / TILE);
-    hipLaunchKernelGGL(assign_kernel<0>, dim3(grid), dim3(256), 0, s, Z, N, d, cent, k, out);
+    hipLaunchKernelGGL(assign_kernel<0>, dim3(grid), dim3(256), 0, s, Z, N, d, cent, k, out, list, list_count);
     return hipGetLastError();
 }
 
@@ -224,7 +287,8 @@ hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const
                                        hipStream_t s)
 {
     int grid = (int)((N + TILE - 1) / TILE);
-    hipLaunchKernelGGL(assign_kernel<1>, dim3(grid), dim3(256), 0, s, Z, N, d, Rm, b / 2, out);
+    hipLaunchKernelGGL(assign_kernel<1>, dim3(grid), dim3(256), 0, s, Z, N, d, Rm, b / 2, out, (const int *)nullptr,
+                       (const int *)nullptr);
     return hipGetLastError();
 }
 
@@ -233,19 +297,43 @@ hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const
 // Member sums in 2^-32 fixed point: integer addition is associative, so the
 // atomics below give the same sums in any order.
 
-__global__ void kmeans_accumulate_kernel(const float *__restrict__ Z, long long N, int d,
-                                         const int32_t *__restrict__ assign, long long *sums, long long *counts)
+// A workgroup takes a chunk of points and a slice of DS dimensions, adds into
+// k x DS accumulators in LDS, and flushes the non-zero ones with global atomics.
+constexpr int ACC_POINTS = 2048;
+
+__global__ __launch_bounds__(256) void kmeans_accumulate_kernel(const float *__restrict__ Z, long long N, int d,
+                                                                const int32_t *__restrict__ assign, int k, int ds,
+                                                                long long *sums, long long *counts)
 {
-    long long total = N * d;
-    long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    long long stride = (long long)gridDim.x * blockDim.x;
-    for (; e < total; e += stride) {
-        long long p = e / d;
-        int j = (int)(e - p * d);
-        int c = assign[p];
-        long long q = __double2ll_rn((double)Z[e] * 4294967296.0);
-        atomicAdd((unsigned long long *)&sums[(long long)c * d + j], (unsigned long long)q);
-        if (j == 0) atomicAdd((unsigned long long *)&counts[c], 1ull);
+    extern __shared__ unsigned long long acc_sh[];  // [k][ds]
+    const int slice = blockIdx.y;
+    const long long p0 = (long long)blockIdx.x * ACC_POINTS;
+    const int j0 = slice * ds;
+    for (int t = threadIdx.x; t < k * ds; t += 256) acc_sh[t] = 0ull;
+    __syncthreads();
+    const int jj = threadIdx.x % ds;          // dimension within the slice
+    const int pp = threadIdx.x / ds;          // point within a step
+    const int step = 256 / ds;
+    if (j0 + jj < d) {
+        for (int q = pp; q < ACC_POINTS; q += step) {
+            const long long p = p0 + q;
+            if (p >= N) break;
+            const int c = assign[p];
+            const long long v = __double2ll_rn((double)Z[p * d + j0 + jj] * 4294967296.0);
+            atomicAdd(&acc_sh[c * ds + jj], (unsigned long long)v);
+        }
+    }
+    if (slice == 0) {
+        for (int q = threadIdx.x; q < ACC_POINTS; q += 256) {
+            const long long p = p0 + q;
+            if (p < N) atomicAdd((unsigned long long *)&counts[assign[p]], 1ull);
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < k * ds; t += 256) {
+        const unsigned long long v = acc_sh[t];
+        const int c = t / ds, j = j0 + t % ds;
+        if (v != 0ull && j < d) atomicAdd((unsigned long long *)&sums[(long long)c * d + j], v);
     }
 }
 
@@ -267,9 +355,11 @@ hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_
     if (e != hipSuccess) return e;
     e = hipMemsetAsync(counts, 0, sizeof(long long) * (size_t)k, s);
     if (e != hipSuccess) return e;
-    long long total = N * d;
-    int grid = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-    hipLaunchKernelGGL(kmeans_accumulate_kernel, dim3(grid), dim3(256), 0, s, Z, N, d, assign, sums, counts);
+    int ds = 16;
+    while (ds > 1 && (size_t)k * ds * sizeof(unsigned long long) > 48 * 1024) ds >>= 1;
+    dim3 grid((unsigned)((N + ACC_POINTS - 1) / ACC_POINTS), (unsigned)((d + ds - 1) / ds));
+    hipLaunchKernelGGL(kmeans_accumulate_kernel, grid, dim3(256), sizeof(unsigned long long) * (size_t)k * ds, s, Z,
+                       N, d, assign, k, ds, sums, counts);
     hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((k * d + 255) / 256), dim3(256), 0, s, sums, counts, k, d, cent);
     return hipGetLastError();
 }

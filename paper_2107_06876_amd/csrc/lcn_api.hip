@@ -71,6 +71,9 @@ struct Scratch {  // build-only buffers
     double *Vt64, *A64, *Lt, *Li, *Ainv, *ln;
     int *fail_flag;
     long long *totals;
+    float *cn;
+    unsigned *cmax_bits;
+    int *flagged, *nflagged;
 };
 
 // Lays out everything except the sparse values.  With bump.dry only sizes are
@@ -93,6 +96,10 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.sums = bump.take<long long>((size_t)kmax * h.d);
     sc.counts = bump.take<long long>((size_t)kmax);
     sc.assign = bump.take<int32_t>((size_t)N);
+    sc.cn = bump.take<float>((size_t)kmax);
+    sc.cmax_bits = bump.take<unsigned>(4);
+    sc.nflagged = bump.take<int>(4);
+    sc.flagged = bump.take<int>((size_t)N);
     h.bucket = bump.take<int32_t>((size_t)(h.R > 0 ? h.R : 1) * N);
 
     SortBuffers &B = h.sort;
@@ -217,7 +224,13 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
     HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
     HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
     for (int it = 0; it < T; ++it) {
-        HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, h.stream));
+        if (h.exact_assign_only) {
+            HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, h.stream));
+        } else {
+            HIPCHK(launch_assign_filter(h.Z, N, h.d, cent, k, h.zn, sc.cn, sc.cmax_bits, assign, sc.flagged,
+                                        sc.nflagged, h.stream));
+            HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, sc.flagged, sc.nflagged, h.stream));
+        }
         HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.sums, sc.counts, cent, h.stream));
     }
     return LCN_OK;
@@ -312,6 +325,8 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     {
         const char *env = getenv("LCN_PASS_GRID");
         h.grid_cap = env ? atoi(env) : 0;
+        env = getenv("LCN_EXACT_ASSIGN_ONLY");
+        h.exact_assign_only = env ? atoi(env) : 0;
     }
     Bump bump{h.ws, workspace_bytes, 0, false};
     Scratch sc{};
@@ -326,10 +341,11 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
     HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
     HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
+    HIPCHK(hipMemsetAsync(sc.nflagged, 0, 4 * sizeof(int), h.stream));
     HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
     HIPCHK(hipMemcpyAsync(h.b_marg, b, sizeof(float) * (size_t)m, hipMemcpyDeviceToDevice, h.stream));
     HIPCHK(launch_convert(X, n, Y, m, d, dtype, h.Z, (unsigned *)(h.counters + 4), h.stream));
-    if (cost == LCN_COST_COSINE) HIPCHK(launch_sqnorms(h.Z, N, d, h.zn, h.stream));
+    HIPCHK(launch_sqnorms(h.Z, N, d, h.zn, h.stream));
 
     // landmarks: centroids of k-means on X u Y (Sec. 4)
     if (h.l > 0) {
@@ -358,10 +374,13 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         HIPCHK(hipMemcpyAsync(totals, sc.totals, sizeof(totals), hipMemcpyDeviceToHost, h.stream));
     }
     HIPCHK(launch_build_meta(h.sort, h.a, h.b_marg, h.stream));
+    int undecided = 0;
+    HIPCHK(hipMemcpyAsync(&undecided, sc.nflagged, sizeof(int), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
     if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
     h.nnz_stored = totals[0];
+    h.undecided_last = undecided;
     h.ntiles = (int)totals[1];
 
     h.vals_x = bump.take<float>((size_t)h.nnz_stored);
@@ -561,6 +580,7 @@ lcn_status lcn_get_info(lcn_handle hh, lcn_info *info)
     info->empty_rows = (int64_t)c[1];
     info->empty_cols = (int64_t)c[2];
     info->workspace_used = h.ws_used;
+    info->undecided_last = h.undecided_last;
     return LCN_OK;
 }
 

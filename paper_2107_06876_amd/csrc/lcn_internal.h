@@ -44,7 +44,12 @@ struct Handle;
 hipError_t launch_convert(const void *X, long long n, const void *Y, long long m, int d, int dtype, float *Z,
                           unsigned *range_flag, hipStream_t s);
 hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k, float *out, hipStream_t s);
+// exact rule for all points (list == nullptr) or for the listed ones
 hipError_t launch_assign_kmeans(const float *Z, long long N, int d, const float *cent, int k, int32_t *out,
+                                const int *list, const int *list_count, hipStream_t s);
+// fp32 MFMA filter: writes the assignment of every point and lists those it could not decide
+hipError_t launch_assign_filter(const float *Z, long long N, int d, const float *cent, int k, const double *zn,
+                                float *cn, unsigned *cmax_bits, int32_t *out, int *flagged, int *nflagged,
                                 hipStream_t s);
 hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
                                        hipStream_t s);
@@ -117,6 +122,7 @@ struct Handle {
     int32_t *bucket;   // [R][n+m]
     SortBuffers sort;
     long long nnz_stored, nnz_unique;
+    long long undecided_last;
     int ntiles;
     // factors
     float *U;          // n x lp
@@ -134,6 +140,7 @@ struct Handle {
     unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag
     int grid;
     int grid_cap;              // upper bound on the workgroups of a sweep (0 = default)
+    int exact_assign_only;     // skip the MFMA filter and decide every bucket by the exact rule
 
     hipEvent_t ev0, ev1;
     float last_ms;
