@@ -160,69 +160,21 @@ hipError_t launch_kernel_matrix(const float *P, long long rows, const float *Q, 
 // ----------------------------------------------------------- fp64 inverse --
 //
 // A is symmetric positive definite (a PSD kernel matrix, plus the ridge).
-// One workgroup factors A = L L^T column by column (Lt holds L^T, so that a
-// column of L is contiguous), then inverts L by forward substitution; A^{-1} =
-// L^{-T} L^{-1} is formed by the GEMM kernel below.
+// Blocked right-looking Cholesky A = L L^T with 64-wide panels: the diagonal
+// block is factored and inverted in LDS by one workgroup, the panel below and
+// the trailing matrix are updated by tiled fp64 GEMMs.  Then X = L^{-1} is
+// built block row by block row from the inverted diagonal blocks, and
+// A^{-1} = X^T X.
 
-__global__ __launch_bounds__(1024) void cholesky_kernel(const double *__restrict__ A, int l, double ridge,
-                                                        double *Lt, int *fail_flag)
-{
-    __shared__ double red[4][512];
-    __shared__ double pivot;
-    const int tid = threadIdx.x;
-    const int ti = tid & 255, tg = tid >> 8;
-    for (int j = 0; j < l; ++j) {
-        // partial sums over k = tg, tg + 4, ... < j of Lt[k][i] * Lt[k][j], i = j .. l-1
-        for (int i = j + ti; i < l; i += 256) {
-            double s = 0.0;
-            for (int k = tg; k < j; k += 4) s = fma(Lt[(long long)k * l + i], Lt[(long long)k * l + j], s);
-            red[tg][i] = s;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            double s = A[(long long)j * l + j] + ridge - (red[0][j] + red[1][j] + red[2][j] + red[3][j]);
-            if (!(s > 0.0)) {
-                *fail_flag = 1;
-                s = 1.0;
-            }
-            pivot = sqrt(s);
-        }
-        __syncthreads();
-        const double piv = pivot;
-        if (tg == 0) {
-            for (int i = j + ti; i < l; i += 256) {
-                double v;
-                if (i == j)
-                    v = piv;
-                else
-                    v = (A[(long long)i * l + j] - (red[0][i] + red[1][i] + red[2][i] + red[3][i])) / piv;
-                Lt[(long long)j * l + i] = v;
-            }
-        }
-        __syncthreads();
-    }
-}
+constexpr int NB = 64;
 
-// Li = L^{-1} (lower triangular, row-major, zero above the diagonal); one thread per column
-__global__ __launch_bounds__(512) void tri_inverse_kernel(const double *__restrict__ Lt, int l, double *Li)
-{
-    const int c = threadIdx.x;
-    if (c >= l) return;
-    for (int i = 0; i < l; ++i) {
-        double v = 0.0;
-        if (i >= c) {
-            double t = (i == c) ? 1.0 : 0.0;
-            for (int k = c; k < i; ++k) t = fma(-Lt[(long long)k * l + i], Li[(long long)k * l + c], t);
-            v = t / Lt[(long long)i * l + i];
-        }
-        Li[(long long)i * l + c] = v;
-    }
-}
-
-// C (M x N) = op(A) * B with fp64 operands; op(A) = A (M x K) or A^T with A stored K x M.
-template <bool TRANSA>
-__global__ __launch_bounds__(256) void gemm_f64_kernel(const double *__restrict__ A, const double *__restrict__ B,
-                                                       long long M, int N, int K, float *C32, double *C64, int ldc)
+// C (M x N, ld ldc) = beta * C + alpha * op(A) * op(B); op = transpose when the flag is set.
+// A is M x K (lda) or, transposed, stored K x M; B is K x N (ldb) or, transposed, stored N x K.
+// Optional fp32 copy of the result (ld ldc32).
+__global__ __launch_bounds__(256) void gemm64_kernel(const double *A, int lda, int transA, const double *B, int ldb,
+                                                     int transB, double *C,
+                                                     int ldc, long long M, int N, int K, double alpha, double beta,
+                                                     float *C32, int ldc32)
 {
     constexpr int KC = 16;
     __shared__ double As[KC][TILE + 2];
@@ -238,32 +190,41 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const double *__restrict_
         for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
     for (int k0 = 0; k0 < K; k0 += KC) {
         __syncthreads();
-        if (TRANSA) {
+        if (transA) {
             const int rr = tid & 63, kq = tid >> 6;
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
-                int kk = kq + pass * 4;
+                const int kk = kq + pass * 4;
                 double v = 0.0;
-                if (r0 + rr < M && k0 + kk < K) v = A[(long long)(k0 + kk) * M + r0 + rr];
+                if (r0 + rr < M && k0 + kk < K) v = A[(long long)(k0 + kk) * lda + r0 + rr];
                 As[kk][rr] = v;
             }
         } else {
             const int kk = tid & 15, rq = tid >> 4;
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
-                int rr = rq + pass * 16;
+                const int rr = rq + pass * 16;
                 double v = 0.0;
-                if (r0 + rr < M && k0 + kk < K) v = A[(r0 + rr) * K + k0 + kk];
+                if (r0 + rr < M && k0 + kk < K) v = A[(r0 + rr) * lda + k0 + kk];
                 As[kk][rr] = v;
             }
         }
-        {
+        if (transB) {
+            const int kk = tid & 15, cq = tid >> 4;
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int cc = cq + pass * 16;
+                double v = 0.0;
+                if (c0 + cc < N && k0 + kk < K) v = B[(long long)(c0 + cc) * ldb + k0 + kk];
+                Bs[kk][cc] = v;
+            }
+        } else {
             const int cc = tid & 63, kq = tid >> 6;
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
-                int kk = kq + pass * 4;
+                const int kk = kq + pass * 4;
                 double v = 0.0;
-                if (c0 + cc < N && k0 + kk < K) v = B[(long long)(k0 + kk) * N + c0 + cc];
+                if (c0 + cc < N && k0 + kk < K) v = B[(long long)(k0 + kk) * ldb + c0 + cc];
                 Bs[kk][cc] = v;
             }
         }
@@ -283,37 +244,146 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const double *__restrict_
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        long long r = r0 + ty * 4 + i;
+        const long long r = r0 + ty * 4 + i;
         if (r >= M) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            int c = c0 + tx * 4 + j;
+            const int c = c0 + tx * 4 + j;
             if (c >= N) continue;
-            if (C32) C32[r * ldc + c] = (float)acc[i][j];
-            if (C64) C64[r * ldc + c] = acc[i][j];
+            double v = alpha * acc[i][j];
+            if (beta != 0.0) v += beta * C[r * ldc + c];
+            if (C) C[r * ldc + c] = v;
+            if (C32) C32[r * ldc32 + c] = (float)v;
         }
     }
+}
+
+static void gemm64(const double *A, int lda, bool tA, const double *B, int ldb, bool tB, double *C, int ldc,
+                   long long M, int N, int K, double alpha, double beta, float *C32, int ldc32, hipStream_t s)
+{
+    if (M <= 0 || N <= 0) return;
+    dim3 grid((unsigned)((M + TILE - 1) / TILE), (unsigned)((N + TILE - 1) / TILE));
+    hipLaunchKernelGGL(gemm64_kernel, grid, dim3(256), 0, s, A, lda, tA ? 1 : 0, B, ldb, tB ? 1 : 0, C, ldc, M, N, K,
+                       alpha, beta, C32, ldc32);
 }
 
 hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N, int K, float *C32, int ldc,
                            hipStream_t s)
 {
-    dim3 grid((unsigned)((M + TILE - 1) / TILE), (unsigned)((N + TILE - 1) / TILE));
-    hipLaunchKernelGGL(gemm_f64_kernel<false>, grid, dim3(256), 0, s, A, B, M, N, K, C32, (double *)nullptr, ldc);
+    gemm64(A, K, false, B, N, false, nullptr, 0, M, N, K, 1.0, 0.0, C32, ldc, s);
     return hipGetLastError();
 }
 
-hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lt, double *Li, double *Ainv, int *fail_flag,
-                              hipStream_t s)
+// One workgroup: Cholesky factor of the nb x nb diagonal block at (j0, j0) of Lm
+// (ridge added to its diagonal), written back into Lm's lower triangle, and the
+// inverse of that triangular factor into Dinv (NB x NB, zero above the diagonal).
+__global__ __launch_bounds__(256) void chol_diag_kernel(double *Lm, int l, int j0, int nb, double ridge, double *Dinv,
+                                                        int *fail_flag)
 {
-    hipError_t e = hipMemsetAsync(Lt, 0, sizeof(double) * (size_t)l * l, s);
+    __shared__ double S[NB][NB + 1];
+    __shared__ double X[NB][NB + 1];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < NB * NB; e += 256) {
+        const int i = e / NB, j = e % NB;
+        double v = 0.0;
+        if (i < nb && j < nb) v = Lm[(long long)(j0 + i) * l + j0 + j] + (i == j ? ridge : 0.0);
+        S[i][j] = v;
+        X[i][j] = 0.0;
+    }
+    __syncthreads();
+    for (int j = 0; j < nb; ++j) {
+        if (tid == 0) {
+            double dd = S[j][j];
+            if (!(dd > 0.0)) {
+                *fail_flag = 1;
+                dd = 1.0;
+            }
+            S[j][j] = sqrt(dd);
+        }
+        __syncthreads();
+        const double piv = S[j][j];
+        for (int i = j + 1 + tid; i < nb; i += 256) S[i][j] /= piv;
+        __syncthreads();
+        const int rem = nb - j - 1;
+        for (int e = tid; e < rem * rem; e += 256) {
+            const int i = j + 1 + e / rem, k = j + 1 + e % rem;
+            if (k <= i) S[i][k] -= S[i][j] * S[k][j];
+        }
+        __syncthreads();
+    }
+    // X = S^{-1} by forward substitution, one thread per column
+    if (tid < nb) {
+        const int c = tid;
+        for (int i = c; i < nb; ++i) {
+            double t = (i == c) ? 1.0 : 0.0;
+            for (int k = c; k < i; ++k) t = fma(-S[i][k], X[k][c], t);
+            X[i][c] = t / S[i][i];
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < NB * NB; e += 256) {
+        const int i = e / NB, j = e % NB;
+        Dinv[e] = X[i][j];
+        if (i < nb && j <= i) Lm[(long long)(j0 + i) * l + j0 + j] = S[i][j];
+    }
+}
+
+__global__ void copy_f64_kernel(const double *src, double *dst, long long count)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = src[i];
+}
+
+// dst (rows x cols, ld ldd) = src (ld lds)
+__global__ void copy_block_kernel(const double *src, int lds, double *dst, int ldd, int rows, int cols)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= rows * cols) return;
+    const int i = e / cols, j = e % cols;
+    dst[(long long)i * ldd + j] = src[(long long)i * lds + j];
+}
+
+// Lm: work copy that ends up holding L in its lower triangle; Xm: L^{-1};
+// Dinv: the inverted diagonal blocks, ceil(l / 64) of NB x NB; Tm: NB x l scratch;
+// Ainv: the result.
+hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lm, double *Xm, double *Ainv, double *Dinv,
+                              double *Tm, int *fail_flag, hipStream_t s)
+{
+    const long long ll = (long long)l * l;
+    hipLaunchKernelGGL(copy_f64_kernel, dim3((unsigned)((ll + 255) / 256)), dim3(256), 0, s, A, Lm, ll);
+    hipError_t e = hipMemsetAsync(Xm, 0, sizeof(double) * (size_t)ll, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(cholesky_kernel, dim3(1), dim3(1024), 0, s, A, l, ridge, Lt, fail_flag);
-    hipLaunchKernelGGL(tri_inverse_kernel, dim3(1), dim3(512), 0, s, Lt, l, Li);
-    dim3 grid((unsigned)((l + TILE - 1) / TILE), (unsigned)((l + TILE - 1) / TILE));
-    // A^{-1} = Li^T Li
-    hipLaunchKernelGGL(gemm_f64_kernel<true>, grid, dim3(256), 0, s, Li, Li, (long long)l, l, l, (float *)nullptr,
-                       Ainv, l);
+    const int panels = (l + NB - 1) / NB;
+    for (int p = 0; p < panels; ++p) {
+        const int j0 = p * NB;
+        const int nb = l - j0 < NB ? l - j0 : NB;
+        double *Dp = Dinv + (long long)p * NB * NB;
+        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(256), 0, s, Lm, l, j0, nb, ridge, Dp, fail_flag);
+        const int below = l - j0 - nb;
+        if (below > 0) {
+            double *A21 = Lm + (long long)(j0 + nb) * l + j0;
+            double *A22 = Lm + (long long)(j0 + nb) * l + j0 + nb;
+            // L21 = A21 * L11^{-T}, in place: nb <= 64 columns, so one workgroup owns a row tile and
+            // has read all of it before it writes
+            gemm64(A21, l, false, Dp, NB, true, A21, l, below, nb, nb, 1.0, 0.0, nullptr, 0, s);
+            // A22 -= L21 * L21^T
+            gemm64(A21, l, false, A21, l, true, A22, l, below, below, nb, -1.0, 1.0, nullptr, 0, s);
+        }
+    }
+    // X = L^{-1}, block row i:  X_ii = L_ii^{-1},  X_i,<i = -L_ii^{-1} (L_i,<i X_<i,<i)
+    for (int p = 0; p < panels; ++p) {
+        const int i0 = p * NB;
+        const int nb = l - i0 < NB ? l - i0 : NB;
+        double *Dp = Dinv + (long long)p * NB * NB;
+        hipLaunchKernelGGL(copy_block_kernel, dim3((nb * nb + 255) / 256), dim3(256), 0, s, Dp, NB,
+                           Xm + (long long)i0 * l + i0, l, nb, nb);
+        if (i0 > 0) {
+            gemm64(Lm + (long long)i0 * l, l, false, Xm, l, false, Tm, l, nb, i0, i0, -1.0, 0.0, nullptr, 0, s);
+            gemm64(Dp, NB, false, Tm, l, false, Xm + (long long)i0 * l, l, nb, i0, nb, 1.0, 0.0, nullptr, 0, s);
+        }
+    }
+    // A^{-1} = X^T X
+    gemm64(Xm, l, true, Xm, l, false, Ainv, l, l, l, l, 1.0, 0.0, nullptr, 0, s);
     return hipGetLastError();
 }
 

@@ -68,7 +68,7 @@ struct Scratch {  // build-only buffers
     float *cent;
     long long *sums, *counts;
     int32_t *assign;
-    double *Vt64, *A64, *Lt, *Li, *Ainv, *ln;
+    double *Vt64, *A64, *Lt, *Li, *Ainv, *ln, *Dinv, *Tm;
     int *fail_flag;
     long long *totals;
     float *cn;
@@ -135,6 +135,8 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.Li = bump.take<double>(l1 * l1);
     sc.Ainv = bump.take<double>(l1 * l1);
     sc.ln = bump.take<double>(l1);
+    sc.Dinv = bump.take<double>((l1 + 63) / 64 * 64 * 64);
+    sc.Tm = bump.take<double>(64 * l1);
 
     h.log_u = bump.take<float>((size_t)h.n);
     h.log_v = bump.take<float>((size_t)h.m);
@@ -402,7 +404,7 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
                                     cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, h.stream));
         HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
                                     cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, h.stream));
-        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.fail_flag, h.stream));
+        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, h.stream));
         // W^T = V^T A^{-1} (A^{-1} is symmetric)
         HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, h.stream));
     }

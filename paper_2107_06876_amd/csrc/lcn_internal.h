@@ -91,8 +91,8 @@ hipError_t launch_sqnorms(const float *P, long long rows, int d, double *out, hi
 hipError_t launch_kernel_matrix(const float *P, long long rows, const float *Q, int cols, int d, int cost,
                                 double lambda, const double *pn, const double *qn, float *out32, double *out64,
                                 int ldo, hipStream_t s);
-hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lt, double *Lit, double *Ainv, int *fail_flag,
-                              hipStream_t s);
+hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lm, double *Xm, double *Ainv, double *Dinv,
+                              double *Tm, int *fail_flag, hipStream_t s);
 // C (M x N, fp32, ld ldc) = A (M x K, fp64) * B (K x N, fp64)
 hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N, int K, float *C32, int ldc,
                            hipStream_t s);
