@@ -490,7 +490,7 @@ int pass_grid(const Handle &h)
 {
     long long rows = h.n > h.m ? h.n : h.m;
     long long g = (rows + PASS_WAVES - 1) / PASS_WAVES;
-    long long cap = h.grid_cap > 0 ? h.grid_cap : 512;
+    long long cap = h.grid_cap > 0 ? h.grid_cap : 256;  // one 1024-thread workgroup per compute unit
     return (int)(g < cap ? g : cap);
 }
 

@@ -71,26 +71,33 @@ __global__ __launch_bounds__(256) void assign_filter_kernel(const float *__restr
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
+        // the next chunk of dimensions is fetched into registers while the matrix
+        // instructions work on the current one
+        const int skk = tid & 31;
+        const int sr0 = tid >> 5;
+        float zreg[FP / 8], creg[FC / 8];
+        auto fetch = [&](int k0) {
+            const bool kin = k0 + skk < d;
+#pragma unroll
+            for (int pass = 0; pass < FP / 8; ++pass) {
+                const long long p = p0 + sr0 + pass * 8;
+                zreg[pass] = (kin && p < N) ? Z[p * d + k0 + skk] : 0.f;
+            }
+#pragma unroll
+            for (int pass = 0; pass < FC / 8; ++pass) {
+                const int c = c0 + sr0 + pass * 8;
+                creg[pass] = (kin && c < k) ? C[(long long)c * d + k0 + skk] : 0.f;
+            }
+        };
+        fetch(0);
         for (int k0 = 0; k0 < d; k0 += FK) {
             __syncthreads();
-            {
-                const int kk = tid & 31;
-                const int r0 = tid >> 5;
-                const bool kin = k0 + kk < d;
 #pragma unroll
-                for (int pass = 0; pass < FP / 8; ++pass) {
-                    const int r = r0 + pass * 8;
-                    const long long p = p0 + r;
-                    Zs[r][kk] = (kin && p < N) ? Z[p * d + k0 + kk] : 0.f;
-                }
+            for (int pass = 0; pass < FP / 8; ++pass) Zs[sr0 + pass * 8][skk] = zreg[pass];
 #pragma unroll
-                for (int pass = 0; pass < FC / 8; ++pass) {
-                    const int r = r0 + pass * 8;
-                    const int c = c0 + r;
-                    Cs[r][kk] = (kin && c < k) ? C[(long long)c * d + k0 + kk] : 0.f;
-                }
-            }
+            for (int pass = 0; pass < FC / 8; ++pass) Cs[sr0 + pass * 8][skk] = creg[pass];
             __syncthreads();
+            if (k0 + FK < d) fetch(k0 + FK);
 #pragma unroll
             for (int kk = 0; kk < FK; kk += 2) {
                 const float b = Zs[w * 32 + col][kk + half];
@@ -147,10 +154,8 @@ hipError_t launch_assign_filter(const float *Z, long long N, int d, const float 
                                 float *cn, unsigned *cmax_bits, int32_t *out, int *flagged, int *nflagged,
                                 hipStream_t s)
 {
-    hipError_t e = hipMemsetAsync(cmax_bits, 0, sizeof(unsigned), s);
-    if (e != hipSuccess) return e;
-    e = hipMemsetAsync(nflagged, 0, sizeof(int), s);
-    if (e != hipSuccess) return e;
+    // cmax_bits and nflagged are zero on entry: cleared by the caller before the first
+    // call and by the centroid update after every call
     hipLaunchKernelGGL(centroid_norms_kernel, dim3((k + 3) / 4), dim3(256), 0, s, cent, k, d, cn, cmax_bits);
     hipLaunchKernelGGL(assign_filter_kernel, dim3((unsigned)((N + FP - 1) / FP)), dim3(256), 0, s, Z, N, d, cent, k, cn,
                        zn, cmax_bits, out, flagged, nflagged);

@@ -240,7 +240,8 @@ __global__ __launch_bounds__(256) void assign_list_kernel(const float *__restric
         for (int c = threadIdx.x; c < k; c += 256) {
             const float *cr = C + (long long)c * d;
             double s = 0.0;
-            for (int j = 0; j < d; ++j) {
+#pragma unroll 8
+            for (int j = 0; j < d; ++j) {  // the order of the additions is the rule; unrolling only batches the loads
                 double t = (double)zrow[j] - (double)cr[j];
                 double t2 = t * t;
                 s = s + t2;
@@ -295,27 +296,36 @@ hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const
 // -------------------------------------------------------- k-means update --
 //
 // Member sums in 2^-32 fixed point: integer addition is associative, so the
-// atomics below give the same sums in any order.
+// sums are the same in any order.  A workgroup takes a chunk of points and a
+// slice of DS dimensions, adds into k x DS accumulators in LDS and writes them
+// out as that chunk's partial sums; the finalize kernel adds the chunks.
 
-// A workgroup takes a chunk of points and a slice of DS dimensions, adds into
-// k x DS accumulators in LDS, and flushes the non-zero ones with global atomics.
-constexpr int ACC_POINTS = 2048;
-
-__global__ __launch_bounds__(256) void kmeans_accumulate_kernel(const float *__restrict__ Z, long long N, int d,
-                                                                const int32_t *__restrict__ assign, int k, int ds,
-                                                                long long *sums, long long *counts)
+int kmeans_chunk_points(long long N)
 {
-    extern __shared__ unsigned long long acc_sh[];  // [k][ds]
+    long long per = (N + 31) / 32;           // at most 32 chunks
+    per = (per + 255) / 256 * 256;
+    return (int)(per < 2048 ? 2048 : per);
+}
+
+__global__ __launch_bounds__(256) void kmeans_partial_kernel(const float *__restrict__ Z, long long N, int d,
+                                                             const int32_t *__restrict__ assign, int k, int ds,
+                                                             int chunk_points, long long *__restrict__ psums,
+                                                             int *__restrict__ pcounts)
+{
+    extern __shared__ unsigned long long acc_sh[];  // [k][ds], then k counters
+    unsigned *cnt_sh = (unsigned *)(acc_sh + (size_t)k * ds);
     const int slice = blockIdx.y;
-    const long long p0 = (long long)blockIdx.x * ACC_POINTS;
+    const long long p0 = (long long)blockIdx.x * chunk_points;
     const int j0 = slice * ds;
     for (int t = threadIdx.x; t < k * ds; t += 256) acc_sh[t] = 0ull;
+    if (slice == 0)
+        for (int t = threadIdx.x; t < k; t += 256) cnt_sh[t] = 0u;
     __syncthreads();
-    const int jj = threadIdx.x % ds;          // dimension within the slice
-    const int pp = threadIdx.x / ds;          // point within a step
+    const int jj = threadIdx.x % ds;  // dimension within the slice
+    const int pp = threadIdx.x / ds;  // point within a step
     const int step = 256 / ds;
     if (j0 + jj < d) {
-        for (int q = pp; q < ACC_POINTS; q += step) {
+        for (int q = pp; q < chunk_points; q += step) {
             const long long p = p0 + q;
             if (p >= N) break;
             const int c = assign[p];
@@ -324,43 +334,53 @@ __global__ __launch_bounds__(256) void kmeans_accumulate_kernel(const float *__r
         }
     }
     if (slice == 0) {
-        for (int q = threadIdx.x; q < ACC_POINTS; q += 256) {
+        for (int q = threadIdx.x; q < chunk_points; q += 256) {
             const long long p = p0 + q;
-            if (p < N) atomicAdd((unsigned long long *)&counts[assign[p]], 1ull);
+            if (p < N) atomicAdd(&cnt_sh[assign[p]], 1u);
         }
     }
     __syncthreads();
+    long long *dst = psums + (long long)blockIdx.x * k * d;
     for (int t = threadIdx.x; t < k * ds; t += 256) {
-        const unsigned long long v = acc_sh[t];
         const int c = t / ds, j = j0 + t % ds;
-        if (v != 0ull && j < d) atomicAdd((unsigned long long *)&sums[(long long)c * d + j], v);
+        if (j < d) dst[(long long)c * d + j] = (long long)acc_sh[t];
     }
+    if (slice == 0)
+        for (int t = threadIdx.x; t < k; t += 256) pcounts[blockIdx.x * k + t] = (int)cnt_sh[t];
 }
 
-__global__ void kmeans_finalize_kernel(const long long *sums, const long long *counts, int k, int d, float *cent)
+__global__ void kmeans_finalize_kernel(const long long *__restrict__ psums, const int *__restrict__ pcounts,
+                                       int chunks, int k, int d, float *cent, unsigned *reset_a, int *reset_b)
 {
     int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e == 0) {  // scratch of the next assignment step starts from zero
+        if (reset_a) *reset_a = 0u;
+        if (reset_b) *reset_b = 0;
+    }
     if (e >= k * d) return;
     int c = e / d;
-    long long cnt = counts[c];
+    long long cnt = 0, sum = 0;
+    for (int q = 0; q < chunks; ++q) {
+        cnt += pcounts[q * k + c];
+        sum += psums[(long long)q * k * d + e];
+    }
     if (cnt == 0) return;  // an empty cluster keeps its centroid
-    double mean = ((double)sums[e] * (1.0 / 4294967296.0)) / (double)cnt;
+    double mean = ((double)sum * (1.0 / 4294967296.0)) / (double)cnt;
     cent[e] = (float)mean;
 }
 
-hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *sums,
-                                long long *counts, float *cent, hipStream_t s)
+hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *psums,
+                                int *pcounts, float *cent, unsigned *reset_a, int *reset_b, hipStream_t s)
 {
-    hipError_t e = hipMemsetAsync(sums, 0, sizeof(long long) * (size_t)k * d, s);
-    if (e != hipSuccess) return e;
-    e = hipMemsetAsync(counts, 0, sizeof(long long) * (size_t)k, s);
-    if (e != hipSuccess) return e;
     int ds = 16;
-    while (ds > 1 && (size_t)k * ds * sizeof(unsigned long long) > 48 * 1024) ds >>= 1;
-    dim3 grid((unsigned)((N + ACC_POINTS - 1) / ACC_POINTS), (unsigned)((d + ds - 1) / ds));
-    hipLaunchKernelGGL(kmeans_accumulate_kernel, grid, dim3(256), sizeof(unsigned long long) * (size_t)k * ds, s, Z,
-                       N, d, assign, k, ds, sums, counts);
-    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((k * d + 255) / 256), dim3(256), 0, s, sums, counts, k, d, cent);
+    while (ds > 1 && (size_t)k * ds * sizeof(unsigned long long) > 40 * 1024) ds >>= 1;
+    const int cp = kmeans_chunk_points(N);
+    const int chunks = (int)((N + cp - 1) / cp);
+    dim3 grid((unsigned)chunks, (unsigned)((d + ds - 1) / ds));
+    size_t lds = sizeof(unsigned long long) * (size_t)k * ds + sizeof(unsigned) * (size_t)k;
+    hipLaunchKernelGGL(kmeans_partial_kernel, grid, dim3(256), lds, s, Z, N, d, assign, k, ds, cp, psums, pcounts);
+    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((k * d + 255) / 256), dim3(256), 0, s, psums, pcounts, chunks, k, d,
+                       cent, reset_a, reset_b);
     return hipGetLastError();
 }
 

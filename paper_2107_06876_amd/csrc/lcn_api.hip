@@ -66,7 +66,8 @@ bool uses_lsh(int mode) { return mode == LCN_MODE_SPARSE || mode == LCN_MODE_LCN
 struct Scratch {  // build-only buffers
     long long *idx;
     float *cent;
-    long long *sums, *counts;
+    long long *psums;
+    int *pcounts;
     int32_t *assign;
     double *Vt64, *A64, *Lt, *Li, *Ainv, *ln, *Dinv, *Tm;
     int *fail_flag;
@@ -93,8 +94,12 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.L = bump.take<float>((size_t)(h.l > 0 ? h.l : 1) * h.d);
     sc.idx = bump.take<long long>((size_t)kmax);
     sc.cent = bump.take<float>((size_t)kmax * h.d);
-    sc.sums = bump.take<long long>((size_t)kmax * h.d);
-    sc.counts = bump.take<long long>((size_t)kmax);
+    {
+        const int cp = kmeans_chunk_points(N);
+        const size_t chunks = (size_t)((N + cp - 1) / cp);
+        sc.psums = bump.take<long long>(chunks * kmax * h.d);
+        sc.pcounts = bump.take<int>(chunks * kmax);
+    }
     sc.assign = bump.take<int32_t>((size_t)N);
     sc.cn = bump.take<float>((size_t)kmax);
     sc.cmax_bits = bump.take<unsigned>(4);
@@ -225,6 +230,8 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
     HIPCHK(hipMemcpyAsync(sc.idx, idx.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
     HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
+    HIPCHK(hipMemsetAsync(sc.cmax_bits, 0, sizeof(unsigned), h.stream));
+    HIPCHK(hipMemsetAsync(sc.nflagged, 0, sizeof(int), h.stream));
     for (int it = 0; it < T; ++it) {
         if (h.exact_assign_only) {
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, h.stream));
@@ -233,7 +240,9 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
                                         sc.nflagged, h.stream));
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, sc.flagged, sc.nflagged, h.stream));
         }
-        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.sums, sc.counts, cent, h.stream));
+        // the last iteration leaves the count of undecided points in place for lcn_get_info
+        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.psums, sc.pcounts, cent, sc.cmax_bits,
+                                    it + 1 < T ? sc.nflagged : nullptr, h.stream));
     }
     return LCN_OK;
 }

@@ -53,8 +53,11 @@ hipError_t launch_assign_filter(const float *Z, long long N, int d, const float 
                                 hipStream_t s);
 hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
                                        hipStream_t s);
-hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *sums,
-                                long long *counts, float *cent, hipStream_t s);
+// psums: [chunks][k][d] int64, pcounts: [chunks][k]; chunks = ceil(N / kmeans_chunk_points(N)) <= 32.
+// reset_a / reset_b (nullable) are cleared for the next assignment step.
+hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *psums,
+                                int *pcounts, float *cent, unsigned *reset_a, int *reset_b, hipStream_t s);
+int kmeans_chunk_points(long long N);
 
 struct SortBuffers {
     int R, b;
