@@ -117,6 +117,44 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
                      const lcn_lsh_params *lsh, void *workspace, size_t workspace_bytes, void *hip_stream,
                      size_t *bytes_needed, lcn_handle *out);
 
+/* A ragged batch of small problems (the graph-pair workloads of Sec. 6), all
+ * solved by one launch, one workgroup per problem.  Problem p owns rows
+ * x_off[p] .. x_off[p+1] of X and y_off[p] .. y_off[p+1] of Y (at most 64 each).
+ * With deletion costs the problem is the bipartite-matching form of Sec. 6:
+ *   C_BP = [[C, diag(c_{p,eps})], [diag(c_{eps,q}), 0]]   ((n+m) x (m+n)),
+ * uniform marginals 1/(n+m); without them plain OT with marginals 1/n, 1/m.
+ * The LSH / Nystrom approximation applies to the n x m block only. */
+typedef struct {
+    int32_t num_problems;
+    const int64_t *x_off;     /* host, num_problems + 1, x_off[0] = 0 */
+    const int64_t *y_off;     /* host, num_problems + 1 */
+    const float *lambda;      /* host, one regularisation per problem (> 0) */
+    const float *del_cost_x;  /* device, deletion cost c_{i,eps} of every X point, or NULL (both or neither) */
+    const float *del_cost_y;  /* device, deletion cost c_{eps,j} of every Y point, or NULL */
+} lcn_batch_desc;
+
+/* Build all problems of a batch.  X, Y: device fp32, (sum n_p) x d and
+ * (sum m_p) x d, d <= 64; they must stay valid until the build returns.
+ * landmarks: l <= 16, problem p uses seed + p; lsh: k-means hashing only,
+ * buckets <= 16, rounds <= 4, problem p round r uses seed + p*rounds + r.
+ * The handle works with sinkhorn_run, transport_cost (writes num_problems
+ * doubles), lcn_last_run_timing and lcn_destroy; results per problem come from
+ * lcn_batched_results / lcn_batched_get.  Errors as lcn_build. */
+lcn_status lcn_build_batched(const float *X, const float *Y, int32_t d, const lcn_batch_desc *desc, int32_t cost,
+                             int32_t mode, const lcn_landmark_params *landmarks, const lcn_lsh_params *lsh,
+                             void *workspace, size_t workspace_bytes, void *hip_stream, size_t *bytes_needed,
+                             lcn_handle *out);
+/* Sinkhorn distance and L1 marginal residual of every problem (host arrays of
+ * num_problems doubles, nullable) and the plan marginals (device fp32, nullable,
+ * problem p at offset x_off[p] + y_off[p], n+m entries with deletion rows). */
+lcn_status lcn_batched_results(lcn_handle h, double *dist_host, double *resid_host, float *row_dev, float *col_dev);
+/* Per-problem state and structure (device outputs, each nullable): log scalings
+ * as fp64 (problem p at offset x_off[p] + y_off[p]), landmarks
+ * [num_problems][l][d], bucket ids (problem p: [rounds][n_p + m_p] at
+ * rounds * (x_off[p] + y_off[p])), and the 64 x 64 kernel tiles. */
+lcn_status lcn_batched_get(lcn_handle h, double *log_u_dev, double *log_v_dev, float *landmarks_dev,
+                           int32_t *buckets_dev, float *kernel_dev);
+
 /* Run `iters` Sinkhorn iterations u = a ./ (K~ v), v = b ./ (K~^T u) (eq. 2),
  * continuing from the current scalings: N then M iterations equal N + M.
  * Returns after the work has finished.  NONPOSITIVE is reported if any sum

@@ -37,6 +37,11 @@ class Info(ctypes.Structure):
                 ("undecided_last", ctypes.c_int64)]
 
 
+class BatchDesc(ctypes.Structure):
+    _fields_ = [("num_problems", ctypes.c_int32), ("x_off", ctypes.c_void_p), ("y_off", ctypes.c_void_p),
+                ("lambda_", ctypes.c_void_p), ("del_cost_x", ctypes.c_void_p), ("del_cost_y", ctypes.c_void_p)]
+
+
 class LcnError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -64,6 +69,11 @@ def load_library():
         lib.lcn_build.argtypes = [vp, i64, vp, i64, i32, i32, vp, vp, ctypes.c_float, i32, i32,
                                   ctypes.POINTER(LandmarkParams), ctypes.POINTER(LshParams), vp, ctypes.c_size_t, vp,
                                   ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(vp)]
+        lib.lcn_build_batched.argtypes = [vp, vp, i32, ctypes.POINTER(BatchDesc), i32, i32,
+                                          ctypes.POINTER(LandmarkParams), ctypes.POINTER(LshParams), vp, ctypes.c_size_t,
+                                          vp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(vp)]
+        lib.lcn_batched_results.argtypes = [vp, vp, vp, vp, vp]
+        lib.lcn_batched_get.argtypes = [vp, vp, vp, vp, vp, vp]
         lib.sinkhorn_run.argtypes = [vp, i32]
         lib.transport_cost.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
         lib.plan_marginals.argtypes = [vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
@@ -79,7 +89,7 @@ def load_library():
         lib.lcn_destroy.restype = None
         lib.lcn_status_string.argtypes = [i32]
         lib.lcn_status_string.restype = ctypes.c_char_p
-        for name in ("lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
+        for name in ("lcn_build_batched", "lcn_batched_results", "lcn_batched_get", "lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
                      "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing"):
             getattr(lib, name).restype = i32
@@ -289,3 +299,85 @@ def lcn_destroy(h: LcnHandle):
     if getattr(h, "raw", None) is not None and h.raw.value:
         load_library().lcn_destroy(h.raw)
         h.raw = ctypes.c_void_p()
+
+
+# ------------------------------------------------------------ batched problems --
+
+class LcnBatchHandle(LcnHandle):
+    def __init__(self, raw, workspace, x_off, y_off, d, l, rounds, bp):
+        self.raw = raw
+        self.workspace = workspace
+        self.device = workspace.device
+        self.x_off, self.y_off = x_off, y_off
+        self.num_problems = len(x_off) - 1
+        self.d, self.l, self.rounds, self.bp = d, l, rounds, bp
+        self.total = int(x_off[-1] + y_off[-1])
+
+
+def lcn_build_batched(X, Y, x_off, y_off, lam, cost, mode, del_cost_x=None, del_cost_y=None, landmarks=None,
+                      lsh=None, workspace=None, stream=None) -> LcnBatchHandle:
+    """x_off, y_off: int64 numpy arrays (P+1); lam: float32 numpy array (P); X, Y and the deletion
+    costs: float32 device tensors."""
+    import numpy as np
+    lib = load_library()
+    X, Y = _dev(X, torch.float32), _dev(Y, torch.float32)
+    x_off = np.ascontiguousarray(x_off, dtype=np.int64)
+    y_off = np.ascontiguousarray(y_off, dtype=np.int64)
+    lam = np.ascontiguousarray(lam, dtype=np.float32)
+    P = lam.shape[0]
+    d = X.shape[1]
+    keep = []
+    lm, ls = _params(landmarks, lsh, keep)
+    desc = BatchDesc(P, x_off.ctypes.data, y_off.ctypes.data, lam.ctypes.data,
+                     None if del_cost_x is None else _dev(del_cost_x, torch.float32).data_ptr(),
+                     None if del_cost_y is None else _dev(del_cost_y, torch.float32).data_ptr())
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+    if workspace is None:
+        workspace = torch.empty(1 << 20, dtype=torch.uint8, device=X.device)
+    for _ in range(2):
+        raw = ctypes.c_void_p()
+        need = ctypes.c_size_t(0)
+        st = lib.lcn_build_batched(_ptr(X), _ptr(Y), d, ctypes.byref(desc), cost, mode,
+                                   None if lm is None else ctypes.byref(lm), None if ls is None else ctypes.byref(ls),
+                                   _ptr(workspace), workspace.numel(), ctypes.c_void_p(stream), ctypes.byref(need),
+                                   ctypes.byref(raw))
+        if st == ERR_ALLOC and need.value > workspace.numel():
+            workspace = torch.empty(need.value, dtype=torch.uint8, device=X.device)
+            continue
+        break
+    if st != OK:
+        raise LcnError(st, "lcn_build_batched")
+    h = LcnBatchHandle(raw, workspace, x_off, y_off, d, 0 if lm is None else lm.num_landmarks,
+                       0 if ls is None else ls.num_rounds, del_cost_x is not None)
+    h._keep = keep + [X, Y, del_cost_x, del_cost_y]
+    return h
+
+
+def lcn_batched_results(h: LcnBatchHandle, marginals: bool = False):
+    """Returns (distances (P,), residuals (P,)) as numpy arrays, plus the row and column
+    marginals (device tensors) if asked."""
+    import numpy as np
+    dist = np.empty(h.num_problems)
+    resid = np.empty(h.num_problems)
+    r = torch.empty(h.total, dtype=torch.float32, device=h.device) if marginals else None
+    c = torch.empty(h.total, dtype=torch.float32, device=h.device) if marginals else None
+    st = load_library().lcn_batched_results(h.raw, dist.ctypes.data, resid.ctypes.data, _ptr(r), _ptr(c))
+    if st != OK:
+        raise LcnError(st, "lcn_batched_results")
+    return (dist, resid, r, c) if marginals else (dist, resid)
+
+
+def lcn_batched_get(h: LcnBatchHandle):
+    """Returns dict(log_u, log_v (float64, total), landmarks (P, l, d), buckets (flat int32), kernel (P, 64, 64))."""
+    P = h.num_problems
+    out = dict(log_u=torch.empty(h.total, dtype=torch.float64, device=h.device),
+               log_v=torch.empty(h.total, dtype=torch.float64, device=h.device),
+               landmarks=torch.empty((P, max(h.l, 1), h.d), dtype=torch.float32, device=h.device),
+               buckets=torch.empty(max(h.rounds, 1) * h.total, dtype=torch.int32, device=h.device),
+               kernel=torch.empty((P, 64, 64), dtype=torch.float32, device=h.device))
+    st = load_library().lcn_batched_get(h.raw, _ptr(out["log_u"]), _ptr(out["log_v"]), _ptr(out["landmarks"]),
+                                        _ptr(out["buckets"]), _ptr(out["kernel"]))
+    if st != OK:
+        raise LcnError(st, "lcn_batched_get")
+    return out

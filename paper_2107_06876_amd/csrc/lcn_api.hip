@@ -442,8 +442,9 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
 
 lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
 {
-    if (!valid(hh)) return LCN_ERR_STATE;
     if (iters < 0) return LCN_ERR_INVALID_ARG;
+    if (is_batched_handle(hh)) return batched_run(hh, iters);
+    if (!valid(hh)) return LCN_ERR_STATE;
     Handle &h = *(Handle *)hh;
     HIPCHK(hipEventRecord(h.ev0, h.stream));
     for (int it = 0; it < iters; ++it) {
@@ -471,8 +472,9 @@ static lcn_status query(Handle &h, float *row_dev, float *col_dev, double q[4])
 
 lcn_status transport_cost(lcn_handle hh, double *d_host)
 {
-    if (!valid(hh)) return LCN_ERR_STATE;
     if (!d_host) return LCN_ERR_INVALID_ARG;
+    if (is_batched_handle(hh)) return batched_query(hh, d_host, nullptr, nullptr, nullptr);
+    if (!valid(hh)) return LCN_ERR_STATE;
     Handle &h = *(Handle *)hh;
     double q[4];
     lcn_status st = query(h, nullptr, nullptr, q);
@@ -597,6 +599,7 @@ lcn_status lcn_get_info(lcn_handle hh, lcn_info *info)
 
 lcn_status lcn_last_run_timing(lcn_handle hh, float *ms_host, int32_t *launches_host)
 {
+    if (is_batched_handle(hh)) return batched_timing(hh, ms_host, launches_host);
     if (!valid(hh)) return LCN_ERR_STATE;
     Handle &h = *(Handle *)hh;
     if (ms_host) *ms_host = h.last_ms;
@@ -606,6 +609,10 @@ lcn_status lcn_last_run_timing(lcn_handle hh, float *ms_host, int32_t *launches_
 
 void lcn_destroy(lcn_handle hh)
 {
+    if (is_batched_handle(hh)) {
+        batched_destroy(hh);
+        return;
+    }
     if (!valid(hh)) return;
     Handle *h = (Handle *)hh;
     (void)hipStreamSynchronize(h->stream);

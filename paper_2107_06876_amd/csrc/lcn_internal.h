@@ -105,6 +105,13 @@ hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s);
 hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s);
 int pass_grid(const Handle &h);
 
+// ---- batched small problems (kernels_batched.hip) ---------------------------
+bool is_batched_handle(const void *h);
+lcn_status batched_run(void *h, int iters);
+lcn_status batched_query(void *h, double *dist_host, double *resid_host, float *row_dev, float *col_dev);
+lcn_status batched_timing(void *h, float *ms, int *launches);
+void batched_destroy(void *h);
+
 struct Handle {
     uint32_t magic;
     long long n, m;
