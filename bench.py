@@ -57,6 +57,65 @@ def cpu_baseline(p, sample_iters: int):
     }, (st, dist, resid)
 
 
+def bench_batched(args):
+    """Config 4: 1024 small pairs with deletion rows/columns, one launch."""
+    import numpy as np
+    import torch
+
+    import paper_2107_06876_amd as lcn
+    import workloads
+
+    B = workloads.config4()
+    dev = "cuda:0"
+    X = torch.from_numpy(B.X).to(dev)
+    Y = torch.from_numpy(B.Y).to(dev)
+    dx = torch.from_numpy(B.del_x).to(dev)
+    dy = torch.from_numpy(B.del_y).to(dev)
+    lm = dict(num_landmarks=B.num_landmarks, kmeans_iters=B.kmeans_iters, seed=B.landmark_seed, ridge=B.ridge)
+    lsh = dict(num_buckets=B.num_buckets, num_rounds=1, kmeans_iters=B.kmeans_iters, seed=B.lsh_seed)
+    ws = None
+
+    def step():
+        nonlocal ws
+        t0 = time.perf_counter()
+        h = lcn.lcn_build_batched(X, Y, B.x_off, B.y_off, B.lam, B.cost, lcn.MODE_LCN, dx, dy, landmarks=lm, lsh=lsh,
+                                  workspace=ws)
+        ws = h.workspace
+        t1 = time.perf_counter()
+        lcn.sinkhorn_run(h, B.iters)
+        ms, _ = lcn.lcn_last_run_timing(h)
+        dist, resid = lcn.lcn_batched_results(h)
+        lcn.lcn_destroy(h)
+        return 1e3 * (t1 - t0), ms, dist
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    bms, rms = [], []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        b, r, dist = step()
+        bms.append(b)
+        rms.append(r)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    run_mean = float(np.mean(rms))
+    P = B.num_problems
+    out = {
+        "metric": "batched LCN-Sinkhorn (1024 pairs): aggregate Sinkhorn iterations/s", "value": P * B.iters / (run_mean * 1e-3),
+        "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * (t1 - t0) / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 storage, f64 accumulate", "data": "synthetic",
+        "config": {"workload": "C4 1024 pairs n,m in [16,64] d=32 Euclid + deletion cost 1, l=8 b=4 it=50", "mode": "lcn"},
+        "build_ms": float(np.mean(bms)), "sinkhorn_ms": run_mean, "pairs_per_s": P / (run_mean * 1e-3),
+        "mean_distance": float(np.mean(dist)),
+        "roofline": {"bound": "alu", "kernel": "batched_run_kernel", "achieved": None, "peak": None, "unit": "TFLOP/s",
+                     "frac": None, "traffic": None,
+                     "note": "LDS-resident iteration, synchronisation bound; neither HBM nor MFMA"},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +129,8 @@ def main():
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
                          "--gpus %d is not supported" % args.gpus)
+    if args.config == 4:
+        return bench_batched(args)
 
     import numpy as np
     import torch

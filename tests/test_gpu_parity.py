@@ -94,3 +94,29 @@ def test_resumable_and_set_scalings():
     U1, W1 = lcn.lcn_get_factors(h1)
     U2, W2 = lcn.lcn_get_factors(h2)
     assert torch.equal(U1, U2) and torch.equal(W1, W2)
+
+
+def test_config3_full_size():
+    """The benchmark configuration itself (n = m = 20 000, d = 300, l = 256,
+    128 buckets x 3 rounds, 200 iterations), in the launch configuration
+    bench.py times: every landmark, bucket id, CSR entry and scaling is
+    compared with the oracle."""
+    from parity import compare
+    p = workloads.config3()
+    out = compare(p, "lcn")
+    print("C3 full", out, flush=True)
+
+
+def test_config2_full_size_dense_and_sparse():
+    """Config 2 at full size: the dense 10k x 10k path (the accuracy reference)
+    and sparse Sinkhorn against the oracle on a reduced iteration count (the
+    dense oracle costs seconds per iteration); LCN at this lambda reports
+    non-positive sums on both sides (see test_config2_reduced)."""
+    from parity import compare
+    p = workloads.config2()
+    out = compare(p, "sparse", iters=20)
+    print("C2 full sparse", out, flush=True)
+    out = compare(p, "lcn", iters=3)
+    print("C2 full lcn", out, flush=True)
+    out = compare(p, "dense", iters=4)
+    print("C2 full dense", out, flush=True)
