@@ -123,6 +123,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-accuracy", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a 256 MiB device-to-device copy so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                         "can be scaled by what the same counter reads for a copy of known size")
     ap.add_argument("--cpu-iters", type=int, default=5)
     ap.add_argument("--mode", default="lcn", choices=["lcn", "sparse", "nystrom", "dense"])
     args = ap.parse_args()
@@ -206,6 +210,26 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": bytes_launch, "launch_us": launch_us},
     }
+    if args.copy_calibration:
+        src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration_bytes_each_way"] = src.numel() * 4
+    if args.config in (1, 2, 3) and args.mode == "lcn" and not args.no_accuracy:
+        # accuracy of the approximation (Table 1's first column): the dense sibling on the GPU, outside the timed region
+        try:
+            hd = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, lcn.MODE_DENSE)
+            lcn.sinkhorn_run(hd, p.iters)
+            d_dense = lcn.transport_cost(hd)
+            lcn.lcn_destroy(hd)
+            del hd
+            out["cost_rel_err_vs_dense"] = abs(dist - d_dense) / abs(d_dense)
+            out["distance_dense"] = d_dense
+        except lcn.LcnError as e:
+            out["cost_rel_err_vs_dense"] = None
+            out["accuracy_note"] = str(e)
     if not args.no_cpu_baseline:
         base, (st, dist_o, resid_o) = cpu_baseline(p, args.cpu_iters)
         out["cpu_baseline"] = base
