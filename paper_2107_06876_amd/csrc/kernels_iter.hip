@@ -184,60 +184,73 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
     double q0 = 0.0, q1 = 0.0;
     unsigned long long nonpos = 0, empty = 0;
 
-    FRow<T> cur{}, nxt{};
-    RowMeta<RR> mc{}, mn{};
-    long long row = gw;
+    // Three-stage software pipeline over the rows a wave owns: metadata is read
+    // two rows ahead (scalar loads), the factor row and the first 64 entries of
+    // every round's segment one row ahead, and the current row is reduced while
+    // those loads are in flight.
+    struct RowData {
+        FRow<T> f;
+        float tv[RR];
+        double vv[RR];
+    };
+    auto issue = [&](RowData &D, const RowMeta<RR> &M, long long r) {
+        D.f.load(S.F, r, lp, lane);
+        if (MODE != PASS_INIT) {
+            const float *__restrict__ vals = S.vals + M.base;
+            int off = 0;
+#pragma unroll
+            for (int q = 0; q < RR; ++q) {
+                const bool ok = lane < M.len[q];
+                D.tv[q] = ok ? vals[off + lane] : 0.f;
+                D.vv[q] = ok ? S.perm_in[M.vstart[q] + lane] : 0.0;
+                off += M.len[q];
+            }
+        }
+    };
+    RowData cur{}, nxt{};
+    RowMeta<RR> mc{}, mn{}, mn2{};
+    const int Rm = MODE == PASS_INIT ? 0 : R;
+    long long row = gw, next = gw + nwaves, next2 = gw + 2 * nwaves;
     if (row < S.rows) {
-        cur.load(S.F, row, lp, lane);
-        load_meta<RR, MODE>(mc, S, R, row, lane);
+        load_meta<RR, MODE>(mc, S, Rm, row, lane);
+        if (MODE == PASS_INIT && lane < R) mc.pos = S.meta[row * S.meta_stride + 6 + 2 * R + lane];
+        issue(cur, mc, row);
+    }
+    if (next < S.rows) {
+        load_meta<RR, MODE>(mn, S, Rm, next, lane);
+        if (MODE == PASS_INIT && lane < R) mn.pos = S.meta[next * S.meta_stride + 6 + 2 * R + lane];
     }
     while (row < S.rows) {
-        const long long next = row + nwaves;
+        if (next < S.rows) issue(nxt, mn, next);
+        if (next2 < S.rows) {
+            load_meta<RR, MODE>(mn2, S, Rm, next2, lane);
+            if (MODE == PASS_INIT && lane < R) mn2.pos = S.meta[next2 * S.meta_stride + 6 + 2 * R + lane];
+        }
         double out;
         if (MODE == PASS_INIT) {
-            if (next < S.rows) {
-                nxt.load(S.F, next, lp, lane);
-                load_meta<RR, MODE>(mn, S, R, next, lane);
-            }
             const double lo = (double)S.log_out[row];
             out = exp(lo - m_self);
             if (lo > maxlog && lo < INFINITY) maxlog = lo;
         } else {
-            // sparse part: the first 64 entries of every round's segment are requested
-            // before anything is used; what is left of long segments follows
             double acc = 0.0;
-            const float *__restrict__ vals = S.vals + mc.base;
-            int total_len = 0;
-            {
-                float tv[RR];
-                double vv[RR];
-                int segoff[RR];
 #pragma unroll
-                for (int r = 0; r < RR; ++r) {
-                    segoff[r] = total_len;
-                    total_len += mc.len[r];
-                    const bool ok = lane < mc.len[r];
-                    tv[r] = ok ? vals[segoff[r] + lane] : 0.f;
-                    vv[r] = ok ? S.perm_in[mc.vstart[r] + lane] : 0.0;
-                }
-                if (next < S.rows) {  // request the next row while this one is in flight
-                    nxt.load(S.F, next, lp, lane);
-                    load_meta<RR, MODE>(mn, S, R, next, lane);
-                }
+            for (int q = 0; q < RR; ++q) acc = fma((double)cur.tv[q], cur.vv[q], acc);
+            {   // what is left of segments longer than a wavefront
+                const float *__restrict__ vals = S.vals + mc.base;
+                int off = 0;
 #pragma unroll
-                for (int r = 0; r < RR; ++r) acc = fma((double)tv[r], vv[r], acc);
-#pragma unroll
-                for (int r = 0; r < RR; ++r) {
-                    if (mc.len[r] > 64) {
-                        const float *tp = vals + segoff[r];
-                        const double *vp = S.perm_in + mc.vstart[r];
-                        for (int e = 64 + lane; e < mc.len[r]; e += 64) acc = fma((double)tp[e], vp[e], acc);
+                for (int q = 0; q < RR; ++q) {
+                    if (mc.len[q] > 64) {
+                        const float *tp = vals + off;
+                        const double *vp = S.perm_in + mc.vstart[q];
+                        for (int e = 64 + lane; e < mc.len[q]; e += 64) acc = fma((double)tp[e], vp[e], acc);
                     }
+                    off += mc.len[q];
                 }
             }
             if (T > 0) {
 #pragma unroll
-                for (int t = 0; t < TT; ++t) acc = fma((double)cur.f[t], yreg[t], acc);
+                for (int t = 0; t < TT; ++t) acc = fma((double)cur.f.f[t], yreg[t], acc);
             }
             const double s = wave_sum(acc);
             const double marg = (double)mc.marg;
@@ -271,12 +284,15 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
             if (lane < R) S.perm_out[(long long)lane * S.rows + mc.pos] = out;
             if (T > 0) {
 #pragma unroll
-                for (int t = 0; t < TT; ++t) zacc[t] = fma((double)cur.f[t], out, zacc[t]);
+                for (int t = 0; t < TT; ++t) zacc[t] = fma((double)cur.f.f[t], out, zacc[t]);
             }
         }
         cur = nxt;
         mc = mn;
+        mn = mn2;
         row = next;
+        next = next2;
+        next2 += nwaves;
     }
 
     // workgroup reduction of the per-wave accumulators (upper half of the waves
