@@ -502,11 +502,48 @@ __global__ __launch_bounds__(1024) void max_log_kernel(const float *__restrict__
     if (threadIdx.x == 0) *out = sh[0] > -INFINITY ? (double)sh[0] : 0.0;
 }
 
+// Workgroups of a sweep: as many as are resident at once (compute units x
+// workgroups per compute unit that the kernel's register use allows), so that
+// every row slot is dealt out once and the partial sums stay few.
+template <int T, int RR>
+static int resident_blocks()
+{
+    int dev = 0, cus = 256, per_cu = 1;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    }
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pass_kernel<T, RR, PASS_UPDATE>, PASS_THREADS,
+                                                     sizeof(double) * (PASS_WAVES / 2) * (64 * T + 3)) != hipSuccess ||
+        per_cu < 1)
+        per_cu = 1;
+    (void)hipGetLastError();
+    return cus * per_cu;
+}
+
 int pass_grid(const Handle &h)
 {
     long long rows = h.n > h.m ? h.n : h.m;
     long long g = (rows + PASS_WAVES - 1) / PASS_WAVES;
-    long long cap = h.grid_cap > 0 ? h.grid_cap : 256;  // one 1024-thread workgroup per compute unit
+    long long cap = h.grid_cap;
+    if (cap <= 0) {
+        if (h.log_domain) {
+            cap = 512;
+        } else {
+            const bool r8 = h.R > 4;
+            switch (h.lp / 64) {
+                case 0: cap = r8 ? resident_blocks<0, 8>() : resident_blocks<0, 4>(); break;
+                case 1: cap = r8 ? resident_blocks<1, 8>() : resident_blocks<1, 4>(); break;
+                case 2: cap = r8 ? resident_blocks<2, 8>() : resident_blocks<2, 4>(); break;
+                case 3: cap = r8 ? resident_blocks<3, 8>() : resident_blocks<3, 4>(); break;
+                case 4: cap = r8 ? resident_blocks<4, 8>() : resident_blocks<4, 4>(); break;
+                case 5: cap = r8 ? resident_blocks<5, 8>() : resident_blocks<5, 4>(); break;
+                case 6: cap = r8 ? resident_blocks<6, 8>() : resident_blocks<6, 4>(); break;
+                case 7: cap = r8 ? resident_blocks<7, 8>() : resident_blocks<7, 4>(); break;
+                default: cap = r8 ? resident_blocks<8, 8>() : resident_blocks<8, 4>(); break;
+            }
+        }
+    }
     return (int)(g < cap ? g : cap);
 }
 

@@ -151,8 +151,8 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.perm_v = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.m);
     for (int i = 0; i < 2; ++i) h.acc[i] = bump.take<double>(lp1 + 1);
     h.shift = bump.take<double>(2);
-    h.grid = pass_grid(h);
-    h.partial = bump.take<double>((size_t)h.grid * (h.lp + 3));
+    h.grid = bump.dry ? 1024 : pass_grid(h);
+    h.partial = bump.take<double>((size_t)(bump.dry ? 1024 : h.grid) * (h.lp + 3));
 }
 
 lcn_status check_params(long long n, long long m, int d, int dtype, float lambda, int cost, int mode,
