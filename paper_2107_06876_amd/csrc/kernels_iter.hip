@@ -19,114 +19,9 @@
 // that vector one iteration earlier (any reference works; logs move slowly), and
 // M travels with every quantity derived from the vector.  Products are
 // accumulated in fp64.
-#include "lcn_internal.h"
+#include "iter_common.h"
 
 namespace lcn {
-
-constexpr int PASS_THREADS = 1024;
-constexpr int PASS_WAVES = PASS_THREADS / 64;
-constexpr int MAXR = 8;
-#ifndef PASS_MIN_WAVES
-#define PASS_MIN_WAVES 1
-#endif
-
-// One step of a cross-lane sum of doubles through the DPP data path (no LDS):
-// adds to every lane the value of the lane that `CTRL` selects; lanes of rows
-// outside ROW_MASK add zero.
-template <int CTRL, int ROW_MASK>
-__device__ inline double dpp_add(double v)
-{
-    const int lo = __double2loint(v), hi = __double2hiint(v);
-    const int plo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xF, false);
-    const int phi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xF, false);
-    return v + __hiloint2double(phi, plo);
-}
-
-// Sum over the 64 lanes of a wavefront in a fixed order; every lane gets the result.
-__device__ inline double wave_sum(double v)
-{
-    v = dpp_add<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
-    v = dpp_add<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
-    v = dpp_add<0x141, 0xF>(v);  // row_half_mirror
-    v = dpp_add<0x140, 0xF>(v);  // row_mirror: every lane of a 16-lane row holds the row's sum
-    v = dpp_add<0x142, 0xA>(v);  // row_bcast15 into rows 1 and 3
-    v = dpp_add<0x143, 0xC>(v);  // row_bcast31 into rows 2 and 3: lane 63 holds the total
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
-    return __hiloint2double(hi, lo);
-}
-
-template <int CTRL, int ROW_MASK>
-__device__ inline double dpp_max(double v)
-{
-    const int lo = __double2loint(v), hi = __double2hiint(v);
-    // lanes outside ROW_MASK receive their own value back
-    const int plo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, ROW_MASK, 0xF, false);
-    const int phi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, ROW_MASK, 0xF, false);
-    return fmax(v, __hiloint2double(phi, plo));
-}
-
-// Maximum over the 64 lanes of a wavefront; every lane gets the result.
-__device__ inline double wave_max(double v)
-{
-    v = dpp_max<0xB1, 0xF>(v);
-    v = dpp_max<0x4E, 0xF>(v);
-    v = dpp_max<0x141, 0xF>(v);
-    v = dpp_max<0x140, 0xF>(v);
-    v = dpp_max<0x142, 0xA>(v);
-    v = dpp_max<0x143, 0xC>(v);
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
-    return __hiloint2double(hi, lo);
-}
-
-// natural log of a positive finite double: exponent taken out exactly, the
-// mantissa's log in single precision (absolute error about 5e-8)
-__device__ inline double fast_log(double x)
-{
-    int e;
-    double mant = frexp(x, &e);
-    return (double)__logf((float)mant) + (double)e * 0.69314718055994530942;
-}
-
-__device__ inline double fast_rcp(double x)
-{
-    double r = __builtin_amdgcn_rcp(x);
-    r = fma(fma(-x, r, 1.0), r, r);
-    r = fma(fma(-x, r, 1.0), r, r);
-    return r;
-}
-
-// Factor row held by a wave.  lp = 64 T.  If T is a multiple of 4 a lane holds
-// 4 consecutive entries per 256 (one 16-byte load each), else one entry per 64.
-template <int T>
-struct FRow {
-    static constexpr int TT = T > 0 ? T : 1;
-    static constexpr bool VEC = (T > 0) && (T % 4 == 0);
-    float f[TT];
-    __device__ inline void load(const float *__restrict__ F, long long row, int lp, int lane)
-    {
-        if (T == 0) return;
-        if (VEC) {
-#pragma unroll
-            for (int q = 0; q < T / 4; ++q) {
-                const float4 v = *(const float4 *)(F + row * lp + 256 * q + 4 * lane);
-                f[4 * q + 0] = v.x;
-                f[4 * q + 1] = v.y;
-                f[4 * q + 2] = v.z;
-                f[4 * q + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < TT; ++t) f[t] = F[row * lp + 64 * t + lane];
-        }
-    }
-    // index into the length-lp vectors of register slot e
-    __device__ static inline int kidx(int e, int lane)
-    {
-        return VEC ? 256 * (e / 4) + 4 * lane + (e % 4) : 64 * e + lane;
-    }
-};
 
 // Per-row metadata, read from the packed record (see meta_kernel): wave-uniform,
 // so it lives in scalar registers.
@@ -144,7 +39,10 @@ struct RowMeta {
 template <int RR, int MODE>
 __device__ inline void load_meta(RowMeta<RR> &M, const PassSide &S, int R, long long row, int lane)
 {
-    const int *__restrict__ rec = S.meta + row * S.meta_stride;
+    // the records are written once at build time: reading them through the constant
+    // address space lets the compiler use scalar loads although the kernel also stores
+    typedef const __attribute__((address_space(4))) int *const_int_ptr;
+    const_int_ptr rec = (const_int_ptr)(S.meta + row * S.meta_stride);
     M.base = ((long long)rec[1] << 32) | (unsigned)rec[0];
     M.marg = __int_as_float(rec[2]);
     M.log_marg = __hiloint2double(rec[5], rec[4]);
@@ -157,29 +55,47 @@ __device__ inline void load_meta(RowMeta<RR> &M, const PassSide &S, int R, long 
     M.lin = MODE == PASS_QUERY ? S.lin_out[row] : 0.0;
 }
 
-template <int T, int RR, int MODE>
+// FUSED (update sweeps after the first of a run): the previous sweep's partial
+// sums have not been added up yet.  The first ceil((lp + 3) / 64) workgroups of
+// this launch do that before their own rows and publish the totals; every
+// workgroup requests its first rows, then waits for the totals (bounded wait;
+// the reducing workgroups have the lowest indices, are dispatched first and
+// wait for nothing, so the wait ends).  This saves a dependent kernel launch
+// per sweep without any device-wide fence.
+template <int T, int RR, int MODE, bool FUSED>
 __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(PassSide S, int R, int lp, double *partial,
-                                                            unsigned long long *counters, int empty_slot)
+                                                            unsigned long long *counters, int empty_slot,
+                                                            FuseArgs Fz)
 {
     constexpr int TT = T > 0 ? T : 1;
-    extern __shared__ double zsh[];  // [PASS_WAVES / 2][lp + 3]
+    extern __shared__ double zsh[];  // [PASS_WAVES / 2][lp + 3], then [lp + 2] and [16][64] if FUSED
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long long nwaves = (long long)gridDim.x * PASS_WAVES;
-    const long long gw = (long long)blockIdx.x * PASS_WAVES + wave;
+    // FUSED: the reducing workgroups start late, so they take the row slots that may hold one row less
+    const long long gw = (long long)(FUSED ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * PASS_WAVES + wave;
     const int stride = lp + 3;
     // exponents taken out of this side's vector (m_self) and of the input vectors (m_in)
     // (a query reads the exponent its vector was stored with, kept beside the accumulator it produced)
+    if (MODE == PASS_UPDATE) mark_pending(Fz, lp);
+    if (FUSED && (int)blockIdx.x < (stride + 63) / 64)
+        reduce_publish(Fz, blockIdx.x, lp, zsh + (size_t)(PASS_WAVES / 2) * stride + lp + 2);
     const double m_self = MODE == PASS_QUERY ? S.acc_out[lp] : *S.shift_self;
-    const double m_in = MODE != PASS_INIT ? S.acc_in[lp] : 0.0;
-    const double e_out = MODE == PASS_UPDATE ? exp(-m_in - m_self) : (MODE == PASS_QUERY ? exp(m_in + m_self) : 1.0);
+    double m_in = 0.0, e_out = 1.0;
     double maxlog = -INFINITY;
 
     double yreg[TT], zacc[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
-        yreg[t] = (T > 0 && MODE != PASS_INIT) ? S.acc_in[FRow<T>::kidx(t, lane)] : 0.0;
+        yreg[t] = 0.0;
         zacc[t] = 0.0;
+    }
+    if (!FUSED) {
+        m_in = MODE != PASS_INIT ? S.acc_in[lp] : 0.0;
+        e_out = MODE == PASS_UPDATE ? exp(-m_in - m_self) : (MODE == PASS_QUERY ? exp(m_in + m_self) : 1.0);
+#pragma unroll
+        for (int t = 0; t < TT; ++t)
+            yreg[t] = (T > 0 && MODE != PASS_INIT) ? S.acc_in[FRow<T>::kidx(t, lane)] : 0.0;
     }
     double q0 = 0.0, q1 = 0.0;
     unsigned long long nonpos = 0, empty = 0;
@@ -193,17 +109,20 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
         float tv[RR];
         double vv[RR];
     };
+    // Loads are issued for whole wavefront-wide chunks without predication: lanes
+    // beyond a segment's length read the next stored values (masked when used; the
+    // arrays end with 64 entries of slack) and the zero slot behind the gathered vector.
+    const unsigned zero_slot = (unsigned)((R > 0 ? R : 1) * S.rows_in);
     auto issue = [&](RowData &D, const RowMeta<RR> &M, long long r) {
         D.f.load(S.F, r, lp, lane);
         if (MODE != PASS_INIT) {
             const float *__restrict__ vals = S.vals + M.base;
-            int off = 0;
+            unsigned off = lane;
 #pragma unroll
             for (int q = 0; q < RR; ++q) {
-                const bool ok = lane < M.len[q];
-                D.tv[q] = ok ? vals[off + lane] : 0.f;
-                D.vv[q] = ok ? S.perm_in[M.vstart[q] + lane] : 0.0;
-                off += M.len[q];
+                D.tv[q] = vals[off];
+                D.vv[q] = S.perm_in[lane < M.len[q] ? (unsigned)M.vstart[q] + lane : zero_slot];
+                off += (unsigned)M.len[q];
             }
         }
     };
@@ -220,8 +139,20 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
         load_meta<RR, MODE>(mn, S, Rm, next, lane);
         if (MODE == PASS_INIT && lane < R) mn.pos = S.meta[next * S.meta_stride + 6 + 2 * R + lane];
     }
-    while (row < S.rows) {
-        if (next < S.rows) issue(nxt, mn, next);
+    if (FUSED) {
+        double *ysh = zsh + (size_t)(PASS_WAVES / 2) * stride;
+        if (wave == 0) fused_fetch(Fz, S.acc_in, lp, ysh);
+        __syncthreads();
+        m_in = ysh[lp];
+        e_out = ysh[lp + 1];
+        if (T > 0) {
+#pragma unroll
+            for (int t = 0; t < TT; ++t) yreg[t] = ysh[FRow<T>::kidx(t, lane)];
+        }
+    }
+    // one row: `C` holds the row's data, `N` receives the next row's
+    auto step = [&](RowData &C, RowData &N) {
+        if (next < S.rows) issue(N, mn, next);
         if (next2 < S.rows) {
             load_meta<RR, MODE>(mn2, S, Rm, next2, lane);
             if (MODE == PASS_INIT && lane < R) mn2.pos = S.meta[next2 * S.meta_stride + 6 + 2 * R + lane];
@@ -234,23 +165,37 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
         } else {
             double acc = 0.0;
 #pragma unroll
-            for (int q = 0; q < RR; ++q) acc = fma((double)cur.tv[q], cur.vv[q], acc);
+            for (int q = 0; q < RR; ++q) acc = fma((double)(lane < mc.len[q] ? C.tv[q] : 0.f), C.vv[q], acc);
             {   // what is left of segments longer than a wavefront
                 const float *__restrict__ vals = S.vals + mc.base;
                 int off = 0;
 #pragma unroll
                 for (int q = 0; q < RR; ++q) {
                     if (mc.len[q] > 64) {
+                        // 256 entries per trip, all eight loads requested before the first is used
                         const float *tp = vals + off;
                         const double *vp = S.perm_in + mc.vstart[q];
-                        for (int e = 64 + lane; e < mc.len[q]; e += 64) acc = fma((double)tp[e], vp[e], acc);
+                        for (int e0 = 64; e0 < mc.len[q]; e0 += 256) {
+                            float tt[4];
+                            double pv[4];
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const int e = e0 + 64 * k + lane;
+                                const bool ok = e < mc.len[q];
+                                tt[k] = tp[ok ? e : 0];
+                                pv[k] = vp[ok ? e : 0];
+                                if (!ok) tt[k] = 0.f;
+                            }
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) acc = fma((double)tt[k], pv[k], acc);
+                        }
                     }
                     off += mc.len[q];
                 }
             }
             if (T > 0) {
 #pragma unroll
-                for (int t = 0; t < TT; ++t) acc = fma((double)cur.f.f[t], yreg[t], acc);
+                for (int t = 0; t < TT; ++t) acc = fma((double)C.f.f[t], yreg[t], acc);
             }
             const double s = wave_sum(acc);
             const double marg = (double)mc.marg;
@@ -284,15 +229,28 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
             if (lane < R) S.perm_out[(long long)lane * S.rows + mc.pos] = out;
             if (T > 0) {
 #pragma unroll
-                for (int t = 0; t < TT; ++t) zacc[t] = fma((double)cur.f.f[t], out, zacc[t]);
+                for (int t = 0; t < TT; ++t) zacc[t] = fma((double)C.f.f[t], out, zacc[t]);
             }
         }
-        cur = nxt;
         mc = mn;
         mn = mn2;
         row = next;
         next = next2;
         next2 += nwaves;
+    };
+    if (T < 6) {
+        // the two data buffers swap roles from row to row (no register copies)
+        while (row < S.rows) {
+            step(cur, nxt);
+            if (row >= S.rows) break;
+            step(nxt, cur);
+        }
+    } else {
+        // long factor rows: one copy of the loop body keeps the kernel within its registers
+        while (row < S.rows) {
+            step(cur, nxt);
+            cur = nxt;
+        }
     }
 
     // workgroup reduction of the per-wave accumulators (upper half of the waves
@@ -502,19 +460,33 @@ __global__ __launch_bounds__(1024) void max_log_kernel(const float *__restrict__
     if (threadIdx.x == 0) *out = sh[0] > -INFINITY ? (double)sh[0] : 0.0;
 }
 
+static size_t pass_lds_bytes(int lp, bool fused)
+{
+    size_t doubles = (size_t)(PASS_WAVES / 2) * (lp + 3);
+    if (fused) doubles += (size_t)lp + 2 + 16 * 64;
+    return sizeof(double) * doubles;
+}
+
 // Workgroups of a sweep: as many as are resident at once (compute units x
 // workgroups per compute unit that the kernel's register use allows), so that
 // every row slot is dealt out once and the partial sums stay few.
-template <int T, int RR>
-static int resident_blocks()
+int device_compute_units()
 {
-    int dev = 0, cus = 256, per_cu = 1;
+    int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
     }
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pass_kernel<T, RR, PASS_UPDATE>, PASS_THREADS,
-                                                     sizeof(double) * (PASS_WAVES / 2) * (64 * T + 3)) != hipSuccess ||
+    (void)hipGetLastError();
+    return cus;
+}
+
+template <int T, int RR>
+static int resident_blocks()
+{
+    int cus = device_compute_units(), per_cu = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pass_kernel<T, RR, PASS_UPDATE, true>, PASS_THREADS,
+                                                     pass_lds_bytes(64 * T, true)) != hipSuccess ||
         per_cu < 1)
         per_cu = 1;
     (void)hipGetLastError();
@@ -548,40 +520,47 @@ int pass_grid(const Handle &h)
 }
 
 template <int T, int RR>
-static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, int mode, hipStream_t s)
+static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, int mode, const FuseArgs *fuse,
+                                 bool fused_in, bool reduce_after, double *partial, hipStream_t s)
 {
     long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
     int grid = (int)(g < h.grid ? g : h.grid);
     const int stride = h.lp + 3;
-    size_t lds = sizeof(double) * (size_t)(PASS_WAVES / 2) * stride;
     double *qout = h.query_out + 2 * side;
     int empty_slot = 1 + side;
+    FuseArgs none{};
     if (mode == PASS_INIT)
         hipLaunchKernelGGL(max_log_kernel, dim3(1), dim3(1024), 0, s, S.log_out, S.rows, S.shift_self);
-    if (mode == PASS_UPDATE)
-        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, h.counters, empty_slot);
+    if (mode == PASS_UPDATE && fused_in)
+        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_UPDATE, true>), dim3(grid), dim3(PASS_THREADS),
+                           pass_lds_bytes(h.lp, true), s, S, h.R, h.lp, partial, h.counters, empty_slot, *fuse);
+    else if (mode == PASS_UPDATE)
+        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_UPDATE, false>), dim3(grid), dim3(PASS_THREADS),
+                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, h.counters, empty_slot,
+                           fuse ? *fuse : none);
     else if (mode == PASS_QUERY)
-        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, h.counters, empty_slot);
+        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_QUERY, false>), dim3(grid), dim3(PASS_THREADS),
+                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, h.counters, empty_slot, none);
     else
-        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), lds, s, S, h.R, h.lp,
-                           h.partial, h.counters, empty_slot);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(1024), 0, s, h.partial, grid, stride,
-                       h.lp, S.acc_out, qout, S.shift_self, mode);
+        hipLaunchKernelGGL((pass_kernel<T, RR, PASS_INIT, false>), dim3(grid), dim3(PASS_THREADS),
+                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, h.counters, empty_slot, none);
+    if (reduce_after)
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(1024), 0, s, partial, grid, stride,
+                           h.lp, S.acc_out, qout, S.shift_self, mode);
     return hipGetLastError();
 }
 
 template <int T>
-static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, hipStream_t s)
+static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, const FuseArgs *fuse,
+                                bool fused_in, bool reduce_after, double *partial, hipStream_t s)
 {
-    if (h.R <= 4) return launch_pass_tr<T, 4>(S, h, side, mode, s);
-    return launch_pass_tr<T, 8>(S, h, side, mode, s);
+    if (h.R <= 4) return launch_pass_tr<T, 4>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+    return launch_pass_tr<T, 8>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
 }
 
 // side 0: rows of X (updates u, consumes y = W v, produces z = U^T u); side 1: rows of Y.
 // acc_in / acc_out index the accumulator buffers (-1: none).
-hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s)
+static PassSide make_side(const Handle &h, int side, int acc_in, int acc_out, float *marg_out)
 {
     PassSide S;
     if (side == 0) {
@@ -593,6 +572,7 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
         S.lin_out = h.lin_u;
         S.perm_out = h.perm_u;
         S.perm_in = h.perm_v;
+        S.rows_in = h.m;
     } else {
         S.rows = h.m;
         S.F = h.Wt;
@@ -602,54 +582,118 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
         S.lin_out = h.lin_v;
         S.perm_out = h.perm_v;
         S.perm_in = h.perm_u;
+        S.rows_in = h.n;
     }
     S.acc_in = acc_in >= 0 ? h.acc[acc_in] : nullptr;
     S.acc_out = acc_out >= 0 ? h.acc[acc_out] : nullptr;
     S.marg_out = marg_out;
     S.meta_stride = h.sort.meta_stride;
     S.shift_self = h.shift + side;
-    if (h.log_domain) {
-        long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
-        const int grid = (int)(g < h.grid ? g : h.grid);
-        const int empty_slot = 1 + side;
-        if (h.R <= 4) {
-            if (mode == PASS_UPDATE)
-                hipLaunchKernelGGL((logpass_kernel<4, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
-                                   h.partial, h.counters, empty_slot);
-            else if (mode == PASS_QUERY)
-                hipLaunchKernelGGL((logpass_kernel<4, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
-                                   h.partial, h.counters, empty_slot);
-            else
-                hipLaunchKernelGGL((logpass_kernel<4, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
-                                   h.partial, h.counters, empty_slot);
-        } else {
-            if (mode == PASS_UPDATE)
-                hipLaunchKernelGGL((logpass_kernel<8, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
-                                   h.partial, h.counters, empty_slot);
-            else if (mode == PASS_QUERY)
-                hipLaunchKernelGGL((logpass_kernel<8, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
-                                   h.partial, h.counters, empty_slot);
-            else
-                hipLaunchKernelGGL((logpass_kernel<8, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
-                                   h.partial, h.counters, empty_slot);
-        }
-        if (mode == PASS_QUERY)
-            hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(1024), 0, s, h.partial, grid, 3, 0, S.acc_out,
-                               h.query_out + 2 * side, S.shift_self, mode);
-        return hipGetLastError();
+    return S;
+}
+
+static hipError_t launch_logpass(const PassSide &S, const Handle &h, int side, int mode, hipStream_t s)
+{
+    long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
+    const int grid = (int)(g < h.grid ? g : h.grid);
+    const int empty_slot = 1 + side;
+    if (h.R <= 4) {
+        if (mode == PASS_UPDATE)
+            hipLaunchKernelGGL((logpass_kernel<4, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                               h.partial, h.counters, empty_slot);
+        else if (mode == PASS_QUERY)
+            hipLaunchKernelGGL((logpass_kernel<4, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                               h.partial, h.counters, empty_slot);
+        else
+            hipLaunchKernelGGL((logpass_kernel<4, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                               h.partial, h.counters, empty_slot);
+    } else {
+        if (mode == PASS_UPDATE)
+            hipLaunchKernelGGL((logpass_kernel<8, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                               h.partial, h.counters, empty_slot);
+        else if (mode == PASS_QUERY)
+            hipLaunchKernelGGL((logpass_kernel<8, PASS_QUERY>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                               h.partial, h.counters, empty_slot);
+        else
+            hipLaunchKernelGGL((logpass_kernel<8, PASS_INIT>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
+                               h.partial, h.counters, empty_slot);
     }
+    if (mode == PASS_QUERY)
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(1024), 0, s, h.partial, grid, 3, 0, S.acc_out,
+                           h.query_out + 2 * side, S.shift_self, mode);
+    return hipGetLastError();
+}
+
+// workgroups of a sweep over `rows` rows (= partial sums it leaves)
+static int sweep_groups(const Handle &h, long long rows)
+{
+    const long long g = (rows + PASS_WAVES - 1) / PASS_WAVES;
+    return (int)(g < h.grid ? g : h.grid);
+}
+
+static hipError_t dispatch_pass(const PassSide &S, const Handle &h, int side, int mode, const FuseArgs *fuse,
+                                bool fused_in, bool reduce_after, double *partial, hipStream_t s)
+{
     switch (h.lp / 64) {
-        case 0: return launch_pass_t<0>(S, h, side, mode, s);
-        case 1: return launch_pass_t<1>(S, h, side, mode, s);
-        case 2: return launch_pass_t<2>(S, h, side, mode, s);
-        case 3: return launch_pass_t<3>(S, h, side, mode, s);
-        case 4: return launch_pass_t<4>(S, h, side, mode, s);
-        case 5: return launch_pass_t<5>(S, h, side, mode, s);
-        case 6: return launch_pass_t<6>(S, h, side, mode, s);
-        case 7: return launch_pass_t<7>(S, h, side, mode, s);
-        case 8: return launch_pass_t<8>(S, h, side, mode, s);
+        case 0: return launch_pass_t<0>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 1: return launch_pass_t<1>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 2: return launch_pass_t<2>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 3: return launch_pass_t<3>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 4: return launch_pass_t<4>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 5: return launch_pass_t<5>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 6: return launch_pass_t<6>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 7: return launch_pass_t<7>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 8: return launch_pass_t<8>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s)
+{
+    const PassSide S = make_side(h, side, acc_in, acc_out, marg_out);
+    if (h.log_domain) return launch_logpass(S, h, side, mode, s);
+    return dispatch_pass(S, h, side, mode, nullptr, false, true, h.partial, s);
+}
+
+// `iters` iterations = 2 iters update sweeps (rows of X, then rows of Y).  With
+// fused reduction every sweep but the first adds up its predecessor's partial
+// sums itself (two partial buffers alternate) and one reduction launch at the end
+// completes the state; otherwise every sweep is followed by its reduction launch.
+hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s)
+{
+    const bool fused = h.fused_reduce && !h.log_domain;
+    for (int t = 0; t < 2 * iters; ++t) {
+        const int side = t & 1;
+        const PassSide S = make_side(h, side, side == 0 ? 0 : 1, side == 0 ? 1 : 0, nullptr);
+        hipError_t e;
+        if (h.log_domain) {
+            e = launch_logpass(S, h, side, PASS_UPDATE, s);
+        } else if (!fused) {
+            e = dispatch_pass(S, h, side, PASS_UPDATE, nullptr, false, true, h.partial, s);
+        } else {
+            double *mine = (t & 1) ? h.partial2 : h.partial;
+            const bool last = t == 2 * iters - 1;
+            if (t == 0) {
+                // not fused itself, but its successor reduces into this sweep's output accumulator
+                FuseArgs F{};
+                F.mark_pending = last ? nullptr : h.acc[1];
+                e = dispatch_pass(S, h, side, PASS_UPDATE, &F, false, last, mine, s);
+            } else {
+                const long long rows_prev = side == 0 ? h.m : h.n;
+                FuseArgs F;
+                F.prev_partial = (t & 1) ? h.partial : h.partial2;
+                F.prev_groups = sweep_groups(h, rows_prev);
+                F.acc = h.acc[side == 0 ? 0 : 1];
+                F.shift_other = h.shift + (1 - side);
+                F.shift_self = h.shift + side;
+                F.mark_pending = last ? nullptr : h.acc[side == 0 ? 1 : 0];
+                F.timeouts = h.counters + 5;
+                e = dispatch_pass(S, h, side, PASS_UPDATE, &F, true, last, mine, s);
+            }
+        }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace lcn

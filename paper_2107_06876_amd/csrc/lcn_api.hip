@@ -147,12 +147,14 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.log_v = bump.take<float>((size_t)h.m);
     h.lin_u = bump.take<double>((size_t)h.n);
     h.lin_v = bump.take<double>((size_t)h.m);
-    h.perm_u = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.n);
-    h.perm_v = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.m);
-    for (int i = 0; i < 2; ++i) h.acc[i] = bump.take<double>(lp1 + 1);
+    // each is followed by a slot that stays zero (what masked-out lanes of a sweep read)
+    h.perm_u = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.n + 8);
+    h.perm_v = bump.take<double>((size_t)(h.R > 0 ? h.R : 1) * h.m + 8);
+    for (int i = 0; i < 2; ++i) h.acc[i] = bump.take<double>(lp1 + 2);
     h.shift = bump.take<double>(2);
     h.grid = bump.dry ? 1024 : pass_grid(h);
     h.partial = bump.take<double>((size_t)(bump.dry ? 1024 : h.grid) * (h.lp + 3));
+    h.partial2 = bump.take<double>((size_t)(bump.dry ? 1024 : h.grid) * (h.lp + 3));
 }
 
 lcn_status check_params(long long n, long long m, int d, int dtype, float lambda, int cost, int mode,
@@ -249,9 +251,10 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
 
 lcn_status status_from_counters(Handle &h)
 {
-    unsigned long long c[3];
+    unsigned long long c[6];
     HIPCHK(hipMemcpyAsync(c, h.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
+    if (c[5]) return LCN_ERR_DEVICE;  // a sweep gave up waiting for its totals
     if (c[0]) return LCN_ERR_NONPOSITIVE;
     if (c[1] | c[2]) return LCN_WARN_NO_SUPPORT;
     return LCN_OK;
@@ -261,6 +264,9 @@ lcn_status status_from_counters(Handle &h)
 // accumulators z = U^T u (buffer 1) and y = W v (buffer 0).
 lcn_status init_state(Handle &h)
 {
+    const size_t R1 = (size_t)(h.R > 0 ? h.R : 1);
+    HIPCHK(hipMemsetAsync(h.perm_u + R1 * h.n, 0, 8 * sizeof(double), h.stream));
+    HIPCHK(hipMemsetAsync(h.perm_v + R1 * h.m, 0, 8 * sizeof(double), h.stream));
     HIPCHK(launch_pass(h, 0, PASS_INIT, -1, 1, nullptr, h.stream));
     HIPCHK(launch_pass(h, 1, PASS_INIT, -1, 0, nullptr, h.stream));
     return LCN_OK;
@@ -292,8 +298,8 @@ lcn_status lcn_workspace_bytes(int64_t n, int64_t m, int32_t d, int32_t mode, co
         else
             nnz = 0;
     }
-    bump.take<float>((size_t)nnz);
-    bump.take<float>((size_t)nnz);
+    bump.take<float>((size_t)nnz + 64);
+    bump.take<float>((size_t)nnz + 64);
     *bytes = bump.used + 256;
     return LCN_OK;
 }
@@ -338,6 +344,9 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         h.grid_cap = env ? atoi(env) : 0;
         env = getenv("LCN_EXACT_ASSIGN_ONLY");
         h.exact_assign_only = env ? atoi(env) : 0;
+        env = getenv("LCN_FUSED_REDUCE");
+        h.fused_reduce = env ? atoi(env) : 1;
+        h.cus = device_compute_units();
     }
     Bump bump{h.ws, workspace_bytes, 0, false};
     Scratch sc{};
@@ -394,8 +403,9 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     h.undecided_last = undecided;
     h.ntiles = (int)totals[1];
 
-    h.vals_x = bump.take<float>((size_t)h.nnz_stored);
-    h.vals_y = bump.take<float>((size_t)h.nnz_stored);
+    // 64 entries of slack: a sweep reads whole wavefront-wide chunks and masks the excess
+    h.vals_x = bump.take<float>((size_t)h.nnz_stored + 64);
+    h.vals_y = bump.take<float>((size_t)h.nnz_stored + 64);
     h.ws_used = bump.used;
     if (bytes_needed) *bytes_needed = bump.used + 256;
     if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;
@@ -447,10 +457,8 @@ lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
     if (!valid(hh)) return LCN_ERR_STATE;
     Handle &h = *(Handle *)hh;
     HIPCHK(hipEventRecord(h.ev0, h.stream));
-    for (int it = 0; it < iters; ++it) {
-        HIPCHK(launch_pass(h, 0, PASS_UPDATE, 0, 1, nullptr, h.stream));  // u from y = W v; produces z = U^T u
-        HIPCHK(launch_pass(h, 1, PASS_UPDATE, 1, 0, nullptr, h.stream));  // v from z; produces y
-    }
+    // per iteration: u from y = W v (produces z = U^T u), then v from z (produces y)
+    HIPCHK(launch_update_sweeps(h, iters, h.stream));
     HIPCHK(hipEventRecord(h.ev1, h.stream));
     lcn_status st = status_from_counters(h);
     if (st == LCN_ERR_DEVICE) return st;
@@ -578,9 +586,10 @@ lcn_status lcn_get_info(lcn_handle hh, lcn_info *info)
     if (!valid(hh)) return LCN_ERR_STATE;
     if (!info) return LCN_ERR_INVALID_ARG;
     Handle &h = *(Handle *)hh;
-    unsigned long long c[3];
+    unsigned long long c[6];
     HIPCHK(hipMemcpyAsync(c, h.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
+    if (c[5]) return LCN_ERR_DEVICE;  // a sweep gave up waiting for its totals
     info->n = h.n;
     info->m = h.m;
     info->d = h.d;

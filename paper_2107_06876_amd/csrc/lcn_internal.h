@@ -29,7 +29,8 @@ struct PassSide {
     float *log_out;         // log u or log v (fp32 state that is reported)
     double *lin_out;        // u or v, linear, by original index
     double *perm_out;       // [R][rows] u or v in bucket order of each round
-    const double *perm_in;  // [R][other] the other side's scaling in bucket order
+    const double *perm_in;  // [R][other] the other side's scaling in bucket order, then a slot that stays zero
+    long long rows_in;      // rows of the other side
     const double *acc_in;   // lp + 1: y = W v (for rows of U) or z = U^T u (for rows of W^T), then its exponent
     double *acc_out;        // lp + 1: accumulated F^T out, then the exponent taken out of `out`
     double *shift_self;     // exponent taken out of this side's scaling vector (updated every sweep)
@@ -103,6 +104,8 @@ hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s);
 
 // ---- iteration (kernels_iter.hip) ------------------------------------------
 hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s);
+hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s);
+int device_compute_units();
 int pass_grid(const Handle &h);
 
 // ---- batched small problems (kernels_batched.hip) ---------------------------
@@ -143,11 +146,14 @@ struct Handle {
     float *log_u, *log_v;
     double *lin_u, *lin_v;
     double *perm_u, *perm_v;   // [R][n], [R][m]
-    double *acc[2];            // lp + 1 each: [0] y = W v, [1] z = U^T u, each followed by its exponent
+    double *acc[2];            // lp + 2 each (last slot: scratch of the fused reduction): [0] y = W v, [1] z = U^T u, each followed by its exponent
     double *shift;             // [2]: exponent taken out of u and of v
-    double *partial;           // [grid][lp + 2]
+    double *partial;           // [grid][lp + 3] per-workgroup partial sums of a sweep
+    double *partial2;          // second buffer: consecutive sweeps alternate when the reduction is fused
+    int fused_reduce;          // sweeps add up their predecessor's partial sums themselves
+    int cus;                   // compute units of the device
     double *query_out;         // [2 sides][2]: sum r log u, sum |r - a|
-    unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag
+    unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag, wait timeouts
     int grid;
     int grid_cap;              // upper bound on the workgroups of a sweep (0 = default)
     int exact_assign_only;     // skip the MFMA filter and decide every bucket by the exact rule
