@@ -72,8 +72,10 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long long nwaves = (long long)gridDim.x * PASS_WAVES;
-    // FUSED: the reducing workgroups start late, so they take the row slots that may hold one row less
-    const long long gw = (long long)(FUSED ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * PASS_WAVES + wave;
+    // Rows are dealt out from the last workgroup down: the reducing workgroups of a fused
+    // sweep (the first few) start late, so they get the row slots that may hold one row less.
+    // The dealing is the same with and without fusion, so both give the same bits.
+    const long long gw = (long long)(gridDim.x - 1 - blockIdx.x) * PASS_WAVES + wave;
     const int stride = lp + 3;
     // exponents taken out of this side's vector (m_self) and of the input vectors (m_in)
     // (a query reads the exponent its vector was stored with, kept beside the accumulator it produced)

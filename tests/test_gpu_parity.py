@@ -96,6 +96,34 @@ def test_resumable_and_set_scalings():
     assert torch.equal(U1, U2) and torch.equal(W1, W2)
 
 
+def test_fused_reduction_matches_separate_launches(monkeypatch):
+    """A sweep that adds up its predecessor's partial sums itself gives the
+    same bits as a sweep followed by the separate reduction launch, also when
+    the iterations are split into runs of 1, 2 and 3 (first, inner and last
+    sweep of a run take different paths)."""
+    import torch
+    import paper_2107_06876_amd as lcn
+    from parity import gpu_build
+    for p in (workloads.config1(), workloads.config3(n=3000, d=48, landmarks=96, buckets=12, rounds=3, iters=6,
+                                                      name="C3 reduced")):
+        res = {}
+        for fused in ("1", "0"):
+            monkeypatch.setenv("LCN_FUSED_REDUCE", fused)
+            h = gpu_build(p, "lcn")
+            lcn.sinkhorn_run(h, 6)
+            res[fused] = lcn.lcn_get_scalings(h) + (lcn.transport_cost(h),)
+            lcn.lcn_destroy(h)
+        assert torch.equal(res["1"][0], res["0"][0]) and torch.equal(res["1"][1], res["0"][1])
+        assert res["1"][2] == res["0"][2]
+        monkeypatch.setenv("LCN_FUSED_REDUCE", "1")
+        h = gpu_build(p, "lcn")
+        for k in (1, 2, 3):
+            lcn.sinkhorn_run(h, k)
+        u, v = lcn.lcn_get_scalings(h)
+        assert torch.equal(u, res["1"][0]) and torch.equal(v, res["1"][1])
+        lcn.lcn_destroy(h)
+
+
 def test_config3_full_size():
     """The benchmark configuration itself (n = m = 20 000, d = 300, l = 256,
     128 buckets x 3 rounds, 200 iterations), in the launch configuration
