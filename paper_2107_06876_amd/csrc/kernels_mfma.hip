@@ -2,11 +2,27 @@
 //
 // The bucket of a point is defined by an exact fp64 rule (see
 // kernels_structure.hip).  Evaluating that rule for every (point, centroid)
-// pair is ALU bound; here the scores  ||c||^2 - 2 z.c  are computed with fp32
-// matrix instructions (v_mfma_f32_32x32x2f32), which ranks the centroids of a
-// point up to a rigorous rounding bound delta.  If the two best scores of a
-// point are further apart than 2 delta, the best one is also the exact rule's
-// answer; otherwise the point is put on a list and decided by the exact rule.
+// pair is ALU bound; here the scores  ||c||^2 - 2 z.c  are computed on the
+// matrix cores, which ranks the centroids of a point up to a rounding bound
+// delta.  If the two best scores of a point are further apart than 2 delta,
+// the best one is also the exact rule's answer; otherwise the point is put on a
+// list and decided by the exact rule.
+//
+// Arithmetic: every fp32 value is split into bf16 planes, x = x1 + x2 + r with
+// x1 = bf16(x), x2 = bf16(x - x1), |r| <= 2^-16 |x|, and the dot product is
+// taken as  z1.c1 + z1.c2 + z2.c1  with v_mfma_f32_32x32x16_bf16 (products of
+// bf16 values are exact in the fp32 accumulators): three bf16 instructions do
+// the work of eight fp32 ones (v_mfma_f32_32x32x2f32) at sixteen times their
+// rate.  Inputs that were given as bf16 have z2 = 0 and need two products.
+//
+// Layout: the planes are stored in the order the instruction wants its
+// operands.  For a group of 32 rows (points or centroids) and a step of 16
+// dimensions, lane l holds row l % 32, dimensions 8 (l / 32) .. + 7: one
+// 16-byte piece per lane, 1 KB per (group, step), so an operand is ONE fully
+// coalesced 16-byte load per lane, from global memory (points: private to a
+// wavefront, read once per pass over the centroids) or from LDS (centroids:
+// shared by the four wavefronts of a workgroup, staged two steps at a time
+// through two buffers).
 //
 // Tiling for 64-wide wavefronts: a workgroup of 4 waves takes 128 points and
 // walks over the centroids 128 at a time; each wave owns 32 points (the N side
@@ -19,11 +35,59 @@
 namespace lcn {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+
+// bf16 of a finite float, round to nearest even: |x - bf16(x)| <= 2^-8 |x|
+__device__ inline unsigned bf16_bits(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
 
 constexpr int FP = 128;  // points per workgroup
 constexpr int FC = 128;  // centroids per pass
-constexpr int FK = 32;   // dimensions per staged chunk
-constexpr int FLD = FK + 1;
+
+static inline int steps_of(int d) { return (d + 15) / 16; }
+
+size_t split_plane_bytes(long long rows, int d)
+{
+    return (size_t)((rows + 31) / 32) * (size_t)steps_of(d) * 1024;
+}
+
+// Splits the rows of `src` (rows x d, fp32) into `planes` bf16 planes in operand
+// order: out[plane][group][step][lane] (16 bytes each); rows and dimensions
+// beyond the matrix are zero.  One workgroup per group of 32 rows.
+__global__ __launch_bounds__(256) void split_planes_kernel(const float *__restrict__ src, long long rows, int d, int S,
+                                                           int planes, bf16x8 *__restrict__ out, long long plane_stride)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const long long group = blockIdx.x;
+    const long long row = group * 32 + (lane & 31);
+    for (int s = w; s < S; s += 4) {
+        const int k0 = 16 * s + 8 * (lane >> 5);
+        u16x8 p1, p2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x = (row < rows && k0 + e < d) ? src[row * d + k0 + e] : 0.f;
+            const unsigned h = bf16_bits(x);
+            p1[e] = (unsigned short)h;
+            p2[e] = (unsigned short)bf16_bits(x - __uint_as_float(h << 16));  // the difference is exact in fp32
+        }
+        const long long at = (group * S + s) * 64 + lane;
+        out[at] = __builtin_bit_cast(bf16x8, p1);
+        if (planes > 1) out[plane_stride + at] = __builtin_bit_cast(bf16x8, p2);
+    }
+}
+
+hipError_t launch_split_planes(const float *src, long long rows, int d, int planes, void *out, hipStream_t s)
+{
+    const long long groups = (rows + 31) / 32;
+    const int S = steps_of(d);
+    hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)groups), dim3(256), 0, s, src, rows, d, S, planes,
+                       (bf16x8 *)out, (long long)(split_plane_bytes(rows, d) / 16));
+    return hipGetLastError();
+}
 
 // squared norms of the centroids as fp32 plus their maximum (bit pattern of a
 // non-negative float orders like an unsigned integer)
@@ -46,20 +110,31 @@ __global__ void centroid_norms_kernel(const float *__restrict__ C, int k, int d,
     }
 }
 
-__global__ __launch_bounds__(256) void assign_filter_kernel(const float *__restrict__ Z, long long N, int d,
-                                                            const float *__restrict__ C, int k,
-                                                            const float *__restrict__ cn,
+// ZP: planes of the points (2: fp32 input, 1: input exactly representable in bf16)
+template <int ZP>
+__global__ __launch_bounds__(256) void assign_filter_kernel(const bf16x8 *__restrict__ Zt, long long zplane, long long N,
+                                                            int S, const bf16x8 *__restrict__ Ct, long long cplane,
+                                                            int k, const float *__restrict__ cn,
                                                             const double *__restrict__ zn,
-                                                            const unsigned *__restrict__ cmax_bits,
+                                                            const unsigned *__restrict__ cmax_bits, float err_coef,
                                                             int32_t *__restrict__ out, int *__restrict__ flagged,
                                                             int *nflagged)
 {
-    __shared__ float Zs[FP][FLD];
-    __shared__ float Cs[FC][FLD];
+    // [buffer][step of the stage][centroid group][plane][lane]: 32 KB
+    __shared__ bf16x8 Cs[2][2][4][2][64];
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const long long p0 = (long long)blockIdx.x * FP;
+    const long long ngroups = (N + 31) / 32;
+    long long P = (long long)blockIdx.x * (FP / 32) + w;  // the wave's group of 32 points
+    const bool active = P < ngroups;
+    if (!active) P = ngroups - 1;  // idle waves of the last workgroup repeat a group and write nothing
+    const bf16x8 *__restrict__ zsrc = Zt + P * S * 64 + lane;
+    const int cgroups = (k + 31) / 32;
+    const int nstage = (S + 1) / 2;
+    bf16x8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.f;
 
     float best = INFINITY, second = INFINITY;
     int bidx = 0;
@@ -71,42 +146,65 @@ __global__ __launch_bounds__(256) void assign_filter_kernel(const float *__restr
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
-        // the next chunk of dimensions is fetched into registers while the matrix
-        // instructions work on the current one
-        const int skk = tid & 31;
-        const int sr0 = tid >> 5;
-        float zreg[FP / 8], creg[FC / 8];
-        auto fetch = [&](int k0) {
-            const bool kin = k0 + skk < d;
+        // A stage is 16 pieces of 1 KB: (step ks, centroid group t, plane pl); thread tid
+        // fetches lane tid % 64 of pieces tid / 64 + 4 j.
+        bf16x8 creg[4];
+        auto fetch_c = [&](int stage) {
 #pragma unroll
-            for (int pass = 0; pass < FP / 8; ++pass) {
-                const long long p = p0 + sr0 + pass * 8;
-                zreg[pass] = (kin && p < N) ? Z[p * d + k0 + skk] : 0.f;
-            }
-#pragma unroll
-            for (int pass = 0; pass < FC / 8; ++pass) {
-                const int c = c0 + sr0 + pass * 8;
-                creg[pass] = (kin && c < k) ? C[(long long)c * d + k0 + skk] : 0.f;
+            for (int j = 0; j < 4; ++j) {
+                const int piece = w + 4 * j;
+                const int ks = piece >> 3, t = (piece >> 1) & 3, pl = piece & 1;
+                const int s = 2 * stage + ks;
+                const int cg = c0 / 32 + t;
+                creg[j] = (s < S && cg < cgroups) ? Ct[pl * cplane + ((long long)cg * S + s) * 64 + lane] : zero;
             }
         };
-        fetch(0);
-        for (int k0 = 0; k0 < d; k0 += FK) {
-            __syncthreads();
+        auto store_c = [&](int buf) {
 #pragma unroll
-            for (int pass = 0; pass < FP / 8; ++pass) Zs[sr0 + pass * 8][skk] = zreg[pass];
+            for (int j = 0; j < 4; ++j) {
+                const int piece = w + 4 * j;
+                Cs[buf][piece >> 3][(piece >> 1) & 3][piece & 1][lane] = creg[j];
+            }
+        };
+        bf16x8 zcur[2][ZP], znext[2][ZP];
+        auto fetch_z = [&](int stage, bf16x8 (&dst)[2][ZP]) {
 #pragma unroll
-            for (int pass = 0; pass < FC / 8; ++pass) Cs[sr0 + pass * 8][skk] = creg[pass];
-            __syncthreads();
-            if (k0 + FK < d) fetch(k0 + FK);
+            for (int ks = 0; ks < 2; ++ks) {
+                const int s = 2 * stage + ks;
 #pragma unroll
-            for (int kk = 0; kk < FK; kk += 2) {
-                const float b = Zs[w * 32 + col][kk + half];
+                for (int pl = 0; pl < ZP; ++pl) dst[ks][pl] = s < S ? zsrc[pl * zplane + (long long)s * 64] : zero;
+            }
+        };
+        __syncthreads();  // the previous pass has finished reading the buffers
+        fetch_c(0);
+        fetch_z(0, zcur);
+        store_c(0);
+        __syncthreads();
+        for (int i = 0; i < nstage; ++i) {
+            const int buf = i & 1;
+            if (i + 1 < nstage) {
+                fetch_c(i + 1);
+                fetch_z(i + 1, znext);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const float a = Cs[t * 32 + col][kk + half];
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[t], 0, 0, 0);
+                    const bf16x8 c1 = Cs[buf][ks][t][0][lane];
+                    const bf16x8 c2 = Cs[buf][ks][t][1][lane];
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, zcur[ks][0], acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c2, zcur[ks][0], acc[t], 0, 0, 0);
+                    if (ZP > 1) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, zcur[ks][ZP - 1], acc[t], 0, 0, 0);
                 }
             }
+            if (i + 1 < nstage) {
+                store_c(buf ^ 1);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int pl = 0; pl < ZP; ++pl) zcur[ks][pl] = znext[ks][pl];
+            }
+            __syncthreads();
         }
         // scores of this pass's centroids for the lane's point; element v of tile t is
         // centroid row (v / 4) * 8 + half * 4 + v % 4 of the tile
@@ -137,12 +235,12 @@ __global__ __launch_bounds__(256) void assign_filter_kernel(const float *__restr
         best = ob;
         bidx = oi;
     }
-    const long long p = p0 + w * 32 + col;
-    if (half == 0 && p < N) {
+    const long long p = P * 32 + col;
+    if (active && half == 0 && p < N) {
         out[p] = bidx;
-        // rounding bound of a score: (d + 4) u (||z||^2 + ||c||^2) with u = 2^-24, doubled for safety
+        // |score - exact score| <= err_coef (||z||^2 + max ||c||^2), see launch_assign_filter
         const float cmax = __uint_as_float(*cmax_bits);
-        const float delta = 2.5f * (float)(d + 4) * 5.9604645e-8f * ((float)zn[p] * 1.0000002f + cmax);
+        const float delta = err_coef * ((float)zn[p] * 1.0000002f + cmax);
         if (!(second - best > 2.f * delta)) {
             const int slot = atomicAdd(nflagged, 1);
             flagged[slot] = (int)p;
@@ -150,15 +248,38 @@ __global__ __launch_bounds__(256) void assign_filter_kernel(const float *__restr
     }
 }
 
-hipError_t launch_assign_filter(const float *Z, long long N, int d, const float *cent, int k, const double *zn,
-                                float *cn, unsigned *cmax_bits, int32_t *out, int *flagged, int *nflagged,
-                                hipStream_t s)
+// Zt: the points' planes (launch_split_planes, `zplanes` of them); Ct: room for two planes of k centroids.
+hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d, const float *cent, int k, void *Ct,
+                                const double *zn, float *cn, unsigned *cmax_bits, int32_t *out, int *flagged,
+                                int *nflagged, hipStream_t s)
 {
     // cmax_bits and nflagged are zero on entry: cleared by the caller before the first
     // call and by the centroid update after every call
+    const int S = steps_of(d);
     hipLaunchKernelGGL(centroid_norms_kernel, dim3((k + 3) / 4), dim3(256), 0, s, cent, k, d, cn, cmax_bits);
-    hipLaunchKernelGGL(assign_filter_kernel, dim3((unsigned)((N + FP - 1) / FP)), dim3(256), 0, s, Z, N, d, cent, k, cn,
-                       zn, cmax_bits, out, flagged, nflagged);
+    hipError_t e = launch_split_planes(cent, k, d, 2, Ct, s);
+    if (e != hipSuccess) return e;
+    // Bound on |computed score - exact score| / (||z||^2 + max ||c||^2):
+    //  * dropped products: z.c - (z1.c1 + z1.c2 + z2.c1) = z2.c2 + r_z.c + z.r_c - ..., each at most
+    //    2^-16 sum |z_k||c_k| (plus terms of order 2^-24), and sum |z_k||c_k| <= (||z||^2 + ||c||^2) / 2;
+    //    with z2 = r_z = 0 only z.r_c remains;
+    //  * accumulation: every matrix instruction adds 16 exact products to an fp32 accumulator; charged
+    //    with 16 units in the last place of the largest partial sum, 16 * 2^-24 sum |z_k||c_k| each;
+    //  * ||c||^2 rounded to fp32 and the final subtraction: below 2^-21 (||z||^2 + ||c||^2).
+    // The score doubles the dot product's error, which cancels the 1/2 above.
+    const int products = zplanes > 1 ? 3 : 2;
+    const float err_coef = (zplanes > 1 ? 3.05f : 1.05f) * 1.52587890625e-5f +
+                           (float)(products * S) * 9.5367431640625e-7f + 4.76837158203125e-7f;
+    const float err_safe = 1.02f * err_coef;  // |z1| and |c1| may exceed |z| and |c| by a factor 1 + 2^-8
+    const long long zplane = (long long)(split_plane_bytes(N, d) / 16);
+    const long long cplane = (long long)(split_plane_bytes(k, d) / 16);
+    const unsigned grid = (unsigned)((N + FP - 1) / FP);
+    if (zplanes > 1)
+        hipLaunchKernelGGL(assign_filter_kernel<2>, dim3(grid), dim3(256), 0, s, (const bf16x8 *)Zt, zplane, N, S,
+                           (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, nflagged);
+    else
+        hipLaunchKernelGGL(assign_filter_kernel<1>, dim3(grid), dim3(256), 0, s, (const bf16x8 *)Zt, zplane, N, S,
+                           (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, nflagged);
     return hipGetLastError();
 }
 

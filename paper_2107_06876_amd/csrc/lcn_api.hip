@@ -75,6 +75,8 @@ struct Scratch {  // build-only buffers
     float *cn;
     unsigned *cmax_bits;
     int *flagged, *nflagged;
+    char *zt, *ct;  // bf16 planes of the points and of the centroids (assignment filter)
+    int zplanes;
 };
 
 // Lays out everything except the sparse values.  With bump.dry only sizes are
@@ -102,6 +104,10 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     }
     sc.assign = bump.take<int32_t>((size_t)N);
     sc.cn = bump.take<float>((size_t)kmax);
+    // bf16 planes for the assignment filter: points (one plane if the input was bf16), centroids
+    sc.zplanes = h.in_dtype == LCN_BF16 ? 1 : 2;
+    sc.zt = bump.take<char>((size_t)sc.zplanes * split_plane_bytes(N, h.d));
+    sc.ct = bump.take<char>(2 * split_plane_bytes(kmax, h.d));
     sc.cmax_bits = bump.take<unsigned>(4);
     sc.nflagged = bump.take<int>(4);
     sc.flagged = bump.take<int>((size_t)N);
@@ -238,8 +244,8 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
         if (h.exact_assign_only) {
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, h.stream));
         } else {
-            HIPCHK(launch_assign_filter(h.Z, N, h.d, cent, k, h.zn, sc.cn, sc.cmax_bits, assign, sc.flagged,
-                                        sc.nflagged, h.stream));
+            HIPCHK(launch_assign_filter(sc.zt, sc.zplanes, N, h.d, cent, k, sc.ct, h.zn, sc.cn, sc.cmax_bits, assign,
+                                        sc.flagged, sc.nflagged, h.stream));
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, sc.flagged, sc.nflagged, h.stream));
         }
         // the last iteration leaves the count of undecided points in place for lcn_get_info
@@ -331,6 +337,7 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     } guard{hp};
 
     fill_shape(h, n, m, d, mode, lm, lsh);
+    h.in_dtype = dtype;
     h.cost = cost;
     h.lambda = (double)lambda;
     h.ridge = uses_landmarks(mode) ? lm->ridge : 0.0;
@@ -366,6 +373,9 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     HIPCHK(hipMemcpyAsync(h.b_marg, b, sizeof(float) * (size_t)m, hipMemcpyDeviceToDevice, h.stream));
     HIPCHK(launch_convert(X, n, Y, m, d, dtype, h.Z, (unsigned *)(h.counters + 4), h.stream));
     HIPCHK(launch_sqnorms(h.Z, N, d, h.zn, h.stream));
+    // bf16 planes of the points for the assignment filter of every k-means run
+    if (!h.exact_assign_only && (h.l > 0 || (uses_lsh(mode) && h.hash == LCN_HASH_KMEANS)))
+        HIPCHK(launch_split_planes(h.Z, N, d, sc.zplanes, sc.zt, h.stream));
 
     // landmarks: centroids of k-means on X u Y (Sec. 4)
     if (h.l > 0) {

@@ -48,10 +48,14 @@ hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k
 // exact rule for all points (list == nullptr) or for the listed ones
 hipError_t launch_assign_kmeans(const float *Z, long long N, int d, const float *cent, int k, int32_t *out,
                                 const int *list, const int *list_count, hipStream_t s);
-// fp32 MFMA filter: writes the assignment of every point and lists those it could not decide
-hipError_t launch_assign_filter(const float *Z, long long N, int d, const float *cent, int k, const double *zn,
-                                float *cn, unsigned *cmax_bits, int32_t *out, int *flagged, int *nflagged,
-                                hipStream_t s);
+// bf16 planes of a row-major fp32 matrix in matrix-instruction operand order (kernels_mfma.hip)
+size_t split_plane_bytes(long long rows, int d);
+hipError_t launch_split_planes(const float *src, long long rows, int d, int planes, void *out, hipStream_t s);
+// MFMA filter: writes the assignment of every point and lists those it could not decide.
+// Zt: planes of the points (zplanes of them); Ct: room for two planes of k centroids.
+hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d, const float *cent, int k, void *Ct,
+                                const double *zn, float *cn, unsigned *cmax_bits, int32_t *out, int *flagged,
+                                int *nflagged, hipStream_t s);
 hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
                                        hipStream_t s);
 // psums: [chunks][k][d] int64, pcounts: [chunks][k]; chunks = ceil(N / kmeans_chunk_points(N)) <= 32.
@@ -120,6 +124,7 @@ struct Handle {
     long long n, m;
     int d, l, lp, R, b;
     int mode, cost, hash;
+    int in_dtype;              // storage type X and Y were given in
     int log_domain;            // kernel without signed parts (sparse, dense): values and vectors are logs
     double lambda, ridge;
     hipStream_t stream;
