@@ -50,6 +50,10 @@ constexpr int FC = 128;  // centroids per pass
 
 static inline int steps_of(int d) { return (d + 15) / 16; }
 
+// With more than 256 centroids a thread of the exact list kernel walks several chains of d
+// dependent additions; then it pays to separate the points that have just two candidates.
+bool filter_uses_pairs(int k) { return k > 256; }
+
 size_t split_plane_bytes(long long rows, int d)
 {
     return (size_t)((rows + 31) / 32) * (size_t)steps_of(d) * 1024;
@@ -110,18 +114,22 @@ __global__ void centroid_norms_kernel(const float *__restrict__ C, int k, int d,
     }
 }
 
-// ZP: planes of the points (2: fp32 input, 1: input exactly representable in bf16)
-template <int ZP>
-__global__ __launch_bounds__(256) void assign_filter_kernel(const bf16x8 *__restrict__ Zt, long long zplane, long long N,
+// ZP: planes of the points (2: fp32 input, 1: input exactly representable in bf16).
+// TOP3: also track the third smallest score and the second's centroid, so that a point
+// with exactly two candidates goes to the exact rule on those two; pays off when the
+// exact rule over all centroids is long (many centroids).
+template <int ZP, bool TOP3>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void assign_filter_kernel(const bf16x8 *__restrict__ Zt, long long zplane, long long N,
                                                             int S, const bf16x8 *__restrict__ Ct, long long cplane,
                                                             int k, const float *__restrict__ cn,
                                                             const double *__restrict__ zn,
                                                             const unsigned *__restrict__ cmax_bits, float err_coef,
                                                             int32_t *__restrict__ out, int *__restrict__ flagged,
-                                                            int *nflagged)
+                                                            int *__restrict__ pairs, int *nflagged)
 {
     // [buffer][step of the stage][centroid group][plane][lane]: 32 KB
     __shared__ bf16x8 Cs[2][2][4][2][64];
+    __shared__ float cn_s[FC];  // squared norms of the pass's centroids (+inf beyond the last one)
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -136,8 +144,19 @@ __global__ __launch_bounds__(256) void assign_filter_kernel(const bf16x8 *__rest
 #pragma unroll
     for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.f;
 
-    float best = INFINITY, second = INFINITY;
-    int bidx = 0;
+    // the three smallest scores of the lane's point so far, with the centroids of the first two
+    float best = INFINITY, second = INFINITY, third = INFINITY;
+    int bidx = 0, sidx = 0;
+    auto offer = [&](float s, int c) {
+        const bool lt1 = s < best, lt2 = s < second;
+        if (TOP3) {
+            third = fminf(third, fmaxf(s, second));
+            sidx = lt1 ? bidx : (lt2 ? c : sidx);
+        }
+        second = fminf(second, fmaxf(s, best));
+        bidx = lt1 ? c : bidx;
+        best = fminf(best, s);
+    };
 
     for (int c0 = 0; c0 < k; c0 += FC) {
         floatx16 acc[4];
@@ -176,6 +195,7 @@ __global__ __launch_bounds__(256) void assign_filter_kernel(const bf16x8 *__rest
             }
         };
         __syncthreads();  // the previous pass has finished reading the buffers
+        if (tid < FC) cn_s[tid] = c0 + tid < k ? cn[c0 + tid] : INFINITY;
         fetch_c(0);
         fetch_z(0, zcur);
         store_c(0);
@@ -207,53 +227,56 @@ __global__ __launch_bounds__(256) void assign_filter_kernel(const bf16x8 *__rest
             __syncthreads();
         }
         // scores of this pass's centroids for the lane's point; element v of tile t is
-        // centroid row (v / 4) * 8 + half * 4 + v % 4 of the tile
+        // centroid row (v / 4) * 8 + half * 4 + v % 4 of the tile (a centroid beyond the
+        // last one scores +inf and never wins)
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int c = c0 + t * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                if (c < k) {
-                    const float s = cn[c] - 2.f * acc[t][v];
-                    if (s < best) {
-                        second = best;
-                        best = s;
-                        bidx = c;
-                    } else if (s < second) {
-                        second = s;
-                    }
-                }
+                const int cl = t * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                offer(fmaf(-2.f, acc[t][v], cn_s[cl]), c0 + cl);
             }
     }
-    // merge the two half-waves that share a point
-    const float ob = __shfl_xor(best, 32, 64);
-    const float os = __shfl_xor(second, 32, 64);
-    const int oi = __shfl_xor(bidx, 32, 64);
-    const float hi = fmaxf(best, ob);
-    second = fminf(hi, fminf(second, os));
-    if (ob < best || (ob == best && oi < bidx)) {
-        best = ob;
-        bidx = oi;
+    // merge the two half-waves that share a point: the other half's three smallest are offered in turn
+    {
+        const float ob = __shfl_xor(best, 32, 64), os = __shfl_xor(second, 32, 64), ot = __shfl_xor(third, 32, 64);
+        const int oi = __shfl_xor(bidx, 32, 64), osi = __shfl_xor(sidx, 32, 64);
+        offer(ob, oi);
+        offer(os, osi);
+        offer(ot, 0);  // cannot rank above third: two scores of the other half are not larger
     }
     const long long p = P * 32 + col;
     if (active && half == 0 && p < N) {
         out[p] = bidx;
-        // |score - exact score| <= err_coef (||z||^2 + max ||c||^2), see launch_assign_filter
+        // |score - exact score| <= delta = err_coef (||z||^2 + max ||c||^2), see launch_assign_filter.
+        // The exact rule's winner scores at most best + 2 delta, so:
+        //   second beyond that      -> bidx is the winner;
+        //   only third beyond that  -> the winner is bidx or sidx (decided by the exact rule on those two);
+        //   otherwise               -> the exact rule over all centroids.
         const float cmax = __uint_as_float(*cmax_bits);
         const float delta = err_coef * ((float)zn[p] * 1.0000002f + cmax);
         if (!(second - best > 2.f * delta)) {
-            const int slot = atomicAdd(nflagged, 1);
-            flagged[slot] = (int)p;
+            if (TOP3 && third - best > 2.f * delta) {
+                const int slot = atomicAdd(nflagged + 1, 1);
+                pairs[3 * (long long)slot] = (int)p;
+                pairs[3 * (long long)slot + 1] = bidx;
+                pairs[3 * (long long)slot + 2] = sidx;
+            } else {
+                const int slot = atomicAdd(nflagged, 1);
+                flagged[slot] = (int)p;
+            }
         }
     }
 }
 
 // Zt: the points' planes (launch_split_planes, `zplanes` of them); Ct: room for two planes of k centroids.
+// flagged: points for the exact rule over all centroids (count nflagged[0]); pairs: (point, centroid, centroid)
+// triples for the exact rule on two centroids (count nflagged[1]).
 hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d, const float *cent, int k, void *Ct,
                                 const double *zn, float *cn, unsigned *cmax_bits, int32_t *out, int *flagged,
-                                int *nflagged, hipStream_t s)
+                                int *pairs, int *nflagged, hipStream_t s)
 {
-    // cmax_bits and nflagged are zero on entry: cleared by the caller before the first
+    // cmax_bits and nflagged[0..1] are zero on entry: cleared by the caller before the first
     // call and by the centroid update after every call
     const int S = steps_of(d);
     hipLaunchKernelGGL(centroid_norms_kernel, dim3((k + 3) / 4), dim3(256), 0, s, cent, k, d, cn, cmax_bits);
@@ -274,12 +297,22 @@ hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d,
     const long long zplane = (long long)(split_plane_bytes(N, d) / 16);
     const long long cplane = (long long)(split_plane_bytes(k, d) / 16);
     const unsigned grid = (unsigned)((N + FP - 1) / FP);
-    if (zplanes > 1)
-        hipLaunchKernelGGL(assign_filter_kernel<2>, dim3(grid), dim3(256), 0, s, (const bf16x8 *)Zt, zplane, N, S,
-                           (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, nflagged);
-    else
-        hipLaunchKernelGGL(assign_filter_kernel<1>, dim3(grid), dim3(256), 0, s, (const bf16x8 *)Zt, zplane, N, S,
-                           (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, nflagged);
+    const bool top3 = filter_uses_pairs(k);
+#define LCN_FILTER_LAUNCH(ZP_, T3_)                                                                                   \
+    hipLaunchKernelGGL((assign_filter_kernel<ZP_, T3_>), dim3(grid), dim3(256), 0, s, (const bf16x8 *)Zt, zplane, N,  \
+                       S, (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, pairs, nflagged)
+    if (zplanes > 1) {
+        if (top3)
+            LCN_FILTER_LAUNCH(2, true);
+        else
+            LCN_FILTER_LAUNCH(2, false);
+    } else {
+        if (top3)
+            LCN_FILTER_LAUNCH(1, true);
+        else
+            LCN_FILTER_LAUNCH(1, false);
+    }
+#undef LCN_FILTER_LAUNCH
     return hipGetLastError();
 }
 

@@ -240,8 +240,19 @@ __global__ __launch_bounds__(256) void assign_list_kernel(const float *__restric
         for (int c = threadIdx.x; c < k; c += 256) {
             const float *cr = C + (long long)c * d;
             double s = 0.0;
-#pragma unroll 8
-            for (int j = 0; j < d; ++j) {  // the order of the additions is the rule; unrolling only batches the loads
+            int j = 0;
+            for (; j + 32 <= d; j += 32) {  // the order of the additions is the rule; 32 loads are requested at once
+                float cv[32];
+#pragma unroll
+                for (int e = 0; e < 32; ++e) cv[e] = cr[j + e];
+#pragma unroll
+                for (int e = 0; e < 32; ++e) {
+                    double t = (double)zrow[j + e] - (double)cv[e];
+                    double t2 = t * t;
+                    s = s + t2;
+                }
+            }
+            for (; j < d; ++j) {
                 double t = (double)zrow[j] - (double)cr[j];
                 double t2 = t * t;
                 s = s + t2;
@@ -269,6 +280,59 @@ __global__ __launch_bounds__(256) void assign_list_kernel(const float *__restric
         }
         if (threadIdx.x == 0) out[p] = bi_sh[0];
     }
+}
+
+// Exact rule on two candidate centroids: a thread adds the dimensions of one
+// (point, centroid) pair left to right; neighbouring threads hold the two
+// candidates of a point and the smaller sum wins (the lower index if equal).
+__global__ __launch_bounds__(256) void assign_pairs_kernel(const float *__restrict__ Z, int d,
+                                                           const float *__restrict__ C, int32_t *__restrict__ out,
+                                                           const int *__restrict__ pairs,
+                                                           const int *__restrict__ pair_count)
+{
+    const long long cnt = *pair_count;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    // every trip is taken by whole pairs of lanes, so the exchange below always has its partner
+    for (long long t0 = (long long)blockIdx.x * blockDim.x; t0 < 2 * cnt; t0 += stride) {
+        const long long t = t0 + threadIdx.x;
+        const bool live = t < 2 * cnt;
+        const long long slot = live ? t >> 1 : 0;
+        const long long p = pairs[3 * slot];
+        const int c = pairs[3 * slot + 1 + (int)(t & 1)];
+        const float *zr = Z + p * d;
+        const float *cr = C + (long long)c * d;
+        double s = 0.0;
+        int j = 0;
+        for (; j + 32 <= d; j += 32) {  // the order of the additions is the rule; 64 loads are requested at once
+            float zv[32], cv[32];
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                zv[e] = zr[j + e];
+                cv[e] = cr[j + e];
+            }
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                double u = (double)zv[e] - (double)cv[e];
+                double u2 = u * u;
+                s = s + u2;
+            }
+        }
+        for (; j < d; ++j) {
+            double u = (double)zr[j] - (double)cr[j];
+            double u2 = u * u;
+            s = s + u2;
+        }
+        const double so = __shfl_xor(s, 1, 64);
+        const int co = __shfl_xor(c, 1, 64);
+        if (live && (t & 1) == 0) out[p] = (so < s || (so == s && co < c)) ? co : c;
+    }
+}
+
+hipError_t launch_assign_pairs(const float *Z, int d, const float *cent, int32_t *out, const int *pairs,
+                               const int *pair_count, hipStream_t s)
+{
+    hipLaunchKernelGGL(assign_pairs_kernel, dim3(512), dim3(256), 0, s, Z, d, cent, out, pairs, pair_count);
+    return hipGetLastError();
 }
 
 hipError_t launch_assign_kmeans(const float *Z, long long N, int d, const float *cent, int k, int32_t *out,
@@ -355,7 +419,10 @@ __global__ void kmeans_finalize_kernel(const long long *__restrict__ psums, cons
     int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e == 0) {  // scratch of the next assignment step starts from zero
         if (reset_a) *reset_a = 0u;
-        if (reset_b) *reset_b = 0;
+        if (reset_b) {
+            reset_b[0] = 0;
+            reset_b[1] = 0;
+        }
     }
     if (e >= k * d) return;
     int c = e / d;

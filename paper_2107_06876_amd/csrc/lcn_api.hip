@@ -74,7 +74,7 @@ struct Scratch {  // build-only buffers
     long long *totals;
     float *cn;
     unsigned *cmax_bits;
-    int *flagged, *nflagged;
+    int *flagged, *nflagged, *pairs;
     char *zt, *ct;  // bf16 planes of the points and of the centroids (assignment filter)
     int zplanes;
 };
@@ -111,6 +111,7 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.cmax_bits = bump.take<unsigned>(4);
     sc.nflagged = bump.take<int>(4);
     sc.flagged = bump.take<int>((size_t)N);
+    sc.pairs = bump.take<int>(3 * (size_t)N);
     h.bucket = bump.take<int32_t>((size_t)(h.R > 0 ? h.R : 1) * N);
 
     SortBuffers &B = h.sort;
@@ -239,13 +240,15 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
     HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
     HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
     HIPCHK(hipMemsetAsync(sc.cmax_bits, 0, sizeof(unsigned), h.stream));
-    HIPCHK(hipMemsetAsync(sc.nflagged, 0, sizeof(int), h.stream));
+    HIPCHK(hipMemsetAsync(sc.nflagged, 0, 2 * sizeof(int), h.stream));
     for (int it = 0; it < T; ++it) {
         if (h.exact_assign_only) {
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, h.stream));
         } else {
             HIPCHK(launch_assign_filter(sc.zt, sc.zplanes, N, h.d, cent, k, sc.ct, h.zn, sc.cn, sc.cmax_bits, assign,
-                                        sc.flagged, sc.nflagged, h.stream));
+                                        sc.flagged, sc.pairs, sc.nflagged, h.stream));
+            if (filter_uses_pairs(k))
+                HIPCHK(launch_assign_pairs(h.Z, h.d, cent, assign, sc.pairs, sc.nflagged + 1, h.stream));
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, sc.flagged, sc.nflagged, h.stream));
         }
         // the last iteration leaves the count of undecided points in place for lcn_get_info
@@ -404,13 +407,13 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         HIPCHK(hipMemcpyAsync(totals, sc.totals, sizeof(totals), hipMemcpyDeviceToHost, h.stream));
     }
     HIPCHK(launch_build_meta(h.sort, h.a, h.b_marg, h.stream));
-    int undecided = 0;
-    HIPCHK(hipMemcpyAsync(&undecided, sc.nflagged, sizeof(int), hipMemcpyDeviceToHost, h.stream));
+    int undecided2[2] = {0, 0};  // points sent to the exact rule over all centroids, and over two
+    HIPCHK(hipMemcpyAsync(undecided2, sc.nflagged, 2 * sizeof(int), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
     if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
     h.nnz_stored = totals[0];
-    h.undecided_last = undecided;
+    h.undecided_last = (long long)undecided2[0] + undecided2[1];
     h.ntiles = (int)totals[1];
 
     // 64 entries of slack: a sweep reads whole wavefront-wide chunks and masks the excess

@@ -55,7 +55,11 @@ hipError_t launch_split_planes(const float *src, long long rows, int d, int plan
 // Zt: planes of the points (zplanes of them); Ct: room for two planes of k centroids.
 hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d, const float *cent, int k, void *Ct,
                                 const double *zn, float *cn, unsigned *cmax_bits, int32_t *out, int *flagged,
-                                int *nflagged, hipStream_t s);
+                                int *pairs, int *nflagged, hipStream_t s);
+bool filter_uses_pairs(int k);
+// exact rule on two candidate centroids per listed point: pairs = (point, c1, c2) triples
+hipError_t launch_assign_pairs(const float *Z, int d, const float *cent, int32_t *out, const int *pairs,
+                               const int *pair_count, hipStream_t s);
 hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
                                        hipStream_t s);
 // psums: [chunks][k][d] int64, pcounts: [chunks][k]; chunks = ceil(N / kmeans_chunk_points(N)) <= 32.
