@@ -360,94 +360,157 @@ hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const
 // -------------------------------------------------------- k-means update --
 //
 // Member sums in 2^-32 fixed point: integer addition is associative, so the
-// sums are the same in any order.  A workgroup takes a chunk of points and a
-// slice of DS dimensions, adds into k x DS accumulators in LDS and writes them
-// out as that chunk's partial sums; the finalize kernel adds the chunks.
+// sums are the same in any order (and the counting sort below may place the
+// members of a cluster in any order).  Per Lloyd update:
+//   count   -- members per cluster (histogram in LDS, one device atomic per
+//              workgroup and cluster present);
+//   scatter -- point indices grouped by cluster (each workgroup redoes the
+//              small scan of the counts, reserves its ranges with one atomic per
+//              cluster present and ranks its points in LDS);
+//   sum     -- one workgroup per (cluster, slice of 64 dimensions): its 16
+//              wavefronts share out the members, every member is one coalesced
+//              256-byte read, and the mean is written straight to the centroid.
+// The point matrix is read once, by rows; nothing but the centroids is written.
+// The count and cursor arrays exist twice and alternate between updates: the sum
+// kernel clears the pair the next update will use.
 
-int kmeans_chunk_points(long long N)
-{
-    long long per = (N + 31) / 32;           // at most 32 chunks
-    per = (per + 255) / 256 * 256;
-    return (int)(per < 2048 ? 2048 : per);
-}
+constexpr int KM_POINTS = 2048;  // points per workgroup of count and scatter
 
-__global__ __launch_bounds__(256) void kmeans_partial_kernel(const float *__restrict__ Z, long long N, int d,
-                                                             const int32_t *__restrict__ assign, int k, int ds,
-                                                             int chunk_points, long long *__restrict__ psums,
-                                                             int *__restrict__ pcounts)
+__global__ __launch_bounds__(256) void kmeans_count_kernel(const int32_t *__restrict__ assign, long long N, int k,
+                                                           int *__restrict__ counts)
 {
-    extern __shared__ unsigned long long acc_sh[];  // [k][ds], then k counters
-    unsigned *cnt_sh = (unsigned *)(acc_sh + (size_t)k * ds);
-    const int slice = blockIdx.y;
-    const long long p0 = (long long)blockIdx.x * chunk_points;
-    const int j0 = slice * ds;
-    for (int t = threadIdx.x; t < k * ds; t += 256) acc_sh[t] = 0ull;
-    if (slice == 0)
-        for (int t = threadIdx.x; t < k; t += 256) cnt_sh[t] = 0u;
+    extern __shared__ int hist[];  // k
+    for (int t = threadIdx.x; t < k; t += 256) hist[t] = 0;
     __syncthreads();
-    const int jj = threadIdx.x % ds;  // dimension within the slice
-    const int pp = threadIdx.x / ds;  // point within a step
-    const int step = 256 / ds;
-    if (j0 + jj < d) {
-        for (int q = pp; q < chunk_points; q += step) {
-            const long long p = p0 + q;
-            if (p >= N) break;
-            const int c = assign[p];
-            const long long v = __double2ll_rn((double)Z[p * d + j0 + jj] * 4294967296.0);
-            atomicAdd(&acc_sh[c * ds + jj], (unsigned long long)v);
-        }
-    }
-    if (slice == 0) {
-        for (int q = threadIdx.x; q < chunk_points; q += 256) {
-            const long long p = p0 + q;
-            if (p < N) atomicAdd(&cnt_sh[assign[p]], 1u);
+    const long long p0 = (long long)blockIdx.x * KM_POINTS;
+    for (int q = threadIdx.x; q < KM_POINTS; q += 256)
+        if (p0 + q < N) atomicAdd(&hist[assign[p0 + q]], 1);
+    __syncthreads();
+    for (int t = threadIdx.x; t < k; t += 256)
+        if (hist[t]) atomicAdd(&counts[t], hist[t]);
+}
+
+__global__ __launch_bounds__(256) void kmeans_scatter_kernel(const int32_t *__restrict__ assign, long long N, int k,
+                                                             const int *__restrict__ counts, int *__restrict__ cursor,
+                                                             int *__restrict__ order, int *__restrict__ offs)
+{
+    extern __shared__ int sh[];  // start[k] (where this workgroup's members of a cluster go), hist[k]
+    __shared__ int part[256];
+    int *start = sh, *hist = sh + k;
+    const int tid = threadIdx.x;
+    // exclusive scan of the counts: a contiguous run per thread, then the 256 run totals
+    const int seg = (k + 255) / 256;
+    const int lo = tid * seg, hi = lo + seg < k ? lo + seg : k;
+    int run = 0;
+    for (int t = lo; t < hi; ++t) run += counts[t];
+    part[tid] = run;
+    for (int t = tid; t < k; t += 256) hist[t] = 0;
+    __syncthreads();
+    if (tid == 0) {
+        int acc = 0;
+        for (int t = 0; t < 256; ++t) {
+            const int v = part[t];
+            part[t] = acc;
+            acc += v;
         }
     }
     __syncthreads();
-    long long *dst = psums + (long long)blockIdx.x * k * d;
-    for (int t = threadIdx.x; t < k * ds; t += 256) {
-        const int c = t / ds, j = j0 + t % ds;
-        if (j < d) dst[(long long)c * d + j] = (long long)acc_sh[t];
+    run = part[tid];
+    for (int t = lo; t < hi; ++t) {
+        start[t] = run;
+        if (blockIdx.x == 0) offs[t] = run;  // where each cluster's members begin, for the sum kernel
+        run += counts[t];
     }
-    if (slice == 0)
-        for (int t = threadIdx.x; t < k; t += 256) pcounts[blockIdx.x * k + t] = (int)cnt_sh[t];
+    __syncthreads();
+    const long long p0 = (long long)blockIdx.x * KM_POINTS;
+    int rank[KM_POINTS / 256], cl[KM_POINTS / 256];
+#pragma unroll
+    for (int u = 0; u < KM_POINTS / 256; ++u) {
+        const long long p = p0 + tid + 256 * u;
+        cl[u] = p < N ? assign[p] : -1;
+        rank[u] = cl[u] >= 0 ? atomicAdd(&hist[cl[u]], 1) : 0;
+    }
+    __syncthreads();
+    for (int t = tid; t < k; t += 256)
+        if (hist[t]) start[t] += atomicAdd(&cursor[t], hist[t]);
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < KM_POINTS / 256; ++u)
+        if (cl[u] >= 0) order[start[cl[u]] + rank[u]] = (int)(p0 + tid + 256 * u);
 }
 
-__global__ void kmeans_finalize_kernel(const long long *__restrict__ psums, const int *__restrict__ pcounts,
-                                       int chunks, int k, int d, float *cent, unsigned *reset_a, int *reset_b)
+// grid: (k, ceil(d / 64)); 1024 threads.
+__global__ __launch_bounds__(1024) void kmeans_sum_kernel(const float *__restrict__ Z, int d, int k,
+                                                          const int *__restrict__ counts, const int *__restrict__ offs,
+                                                          const int *__restrict__ order, float *__restrict__ cent,
+                                                          int *__restrict__ counts_next, int *__restrict__ cursor_next,
+                                                          unsigned *reset_a, int *reset_b)
 {
-    int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e == 0) {  // scratch of the next assignment step starts from zero
-        if (reset_a) *reset_a = 0u;
-        if (reset_b) {
-            reset_b[0] = 0;
-            reset_b[1] = 0;
+    __shared__ long long red[16][64];
+    const int c = blockIdx.x, slice = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (slice == 0 && threadIdx.x == 0) {  // scratch of the next assignment and update steps starts from zero
+        counts_next[c] = 0;
+        cursor_next[c] = 0;
+        if (c == 0) {
+            if (reset_a) *reset_a = 0u;
+            if (reset_b) {
+                reset_b[0] = 0;
+                reset_b[1] = 0;
+            }
         }
     }
-    if (e >= k * d) return;
-    int c = e / d;
-    long long cnt = 0, sum = 0;
-    for (int q = 0; q < chunks; ++q) {
-        cnt += pcounts[q * k + c];
-        sum += psums[(long long)q * k * d + e];
+    const int cnt = counts[c];
+    const int *__restrict__ mem = order + offs[c];
+    const int j = 64 * slice + lane;
+    const bool jin = j < d;
+    long long sum = 0;
+    // the 16 wavefronts share out the members in contiguous runs; a wave reads up to 64 member
+    // indices at once (one per lane) and then requests 16 rows before the first is added
+    const int per = (cnt + 15) / 16;
+    const int beg = wave * per;
+    const int end = beg + per < cnt ? beg + per : cnt;
+    for (int base = beg; base < end; base += 64) {
+        const int nloc = end - base < 64 ? end - base : 64;
+        const int myidx = lane < nloc ? mem[base + lane] : 0;
+        for (int u0 = 0; u0 < nloc; u0 += 16) {
+            float z[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int uu = u0 + u;
+                const long long row = __builtin_amdgcn_readlane(myidx, uu < 64 ? uu : 63);
+                z[u] = (uu < nloc && jin) ? Z[row * d + j] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) sum += __double2ll_rn((double)z[u] * 4294967296.0);
+        }
     }
-    if (cnt == 0) return;  // an empty cluster keeps its centroid
-    double mean = ((double)sum * (1.0 / 4294967296.0)) / (double)cnt;
-    cent[e] = (float)mean;
+    red[wave][lane] = sum;
+    __syncthreads();
+    if (wave == 0 && jin && cnt > 0) {  // an empty cluster keeps its centroid
+        long long tot = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) tot += red[w][lane];
+        const double mean = ((double)tot * (1.0 / 4294967296.0)) / (double)cnt;
+        cent[(long long)c * d + j] = (float)mean;
+    }
 }
 
-hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *psums,
-                                int *pcounts, float *cent, unsigned *reset_a, int *reset_b, hipStream_t s)
+// counts2 / cursor2: [2][k] each, zero on the first call of a k-means run; offs: [k]; `parity` alternates per call.
+// reset_a / reset_b (nullable) are cleared for the next assignment step.
+hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, int *counts2,
+                                int *cursor2, int *order, int *offs, int parity, float *cent, unsigned *reset_a,
+                                int *reset_b, hipStream_t s)
 {
-    int ds = 16;
-    while (ds > 1 && (size_t)k * ds * sizeof(unsigned long long) > 40 * 1024) ds >>= 1;
-    const int cp = kmeans_chunk_points(N);
-    const int chunks = (int)((N + cp - 1) / cp);
-    dim3 grid((unsigned)chunks, (unsigned)((d + ds - 1) / ds));
-    size_t lds = sizeof(unsigned long long) * (size_t)k * ds + sizeof(unsigned) * (size_t)k;
-    hipLaunchKernelGGL(kmeans_partial_kernel, grid, dim3(256), lds, s, Z, N, d, assign, k, ds, cp, psums, pcounts);
-    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((k * d + 255) / 256), dim3(256), 0, s, psums, pcounts, chunks, k, d,
-                       cent, reset_a, reset_b);
+    int *counts = counts2 + (size_t)(parity & 1) * k, *counts_next = counts2 + (size_t)((parity + 1) & 1) * k;
+    int *cursor = cursor2 + (size_t)(parity & 1) * k, *cursor_next = cursor2 + (size_t)((parity + 1) & 1) * k;
+    const unsigned blocks = (unsigned)((N + KM_POINTS - 1) / KM_POINTS);
+    hipLaunchKernelGGL(kmeans_count_kernel, dim3(blocks), dim3(256), sizeof(int) * (size_t)k, s, assign, N, k, counts);
+    hipLaunchKernelGGL(kmeans_scatter_kernel, dim3(blocks), dim3(256), 2 * sizeof(int) * (size_t)k, s, assign, N, k,
+                       counts, cursor, order, offs);
+    hipLaunchKernelGGL(kmeans_sum_kernel, dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(1024), 0, s, Z, d, k,
+                       counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
     return hipGetLastError();
 }
 

@@ -66,8 +66,7 @@ bool uses_lsh(int mode) { return mode == LCN_MODE_SPARSE || mode == LCN_MODE_LCN
 struct Scratch {  // build-only buffers
     long long *idx;
     float *cent;
-    long long *psums;
-    int *pcounts;
+    int *counts2, *cursor2, *order, *offs;  // k-means update: [2][kmax], [2][kmax], [N], [kmax]
     int32_t *assign;
     double *Vt64, *A64, *Lt, *Li, *Ainv, *ln, *Dinv, *Tm;
     int *fail_flag;
@@ -96,12 +95,10 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.L = bump.take<float>((size_t)(h.l > 0 ? h.l : 1) * h.d);
     sc.idx = bump.take<long long>((size_t)kmax);
     sc.cent = bump.take<float>((size_t)kmax * h.d);
-    {
-        const int cp = kmeans_chunk_points(N);
-        const size_t chunks = (size_t)((N + cp - 1) / cp);
-        sc.psums = bump.take<long long>(chunks * kmax * h.d);
-        sc.pcounts = bump.take<int>(chunks * kmax);
-    }
+    sc.counts2 = bump.take<int>(2 * (size_t)kmax);
+    sc.cursor2 = bump.take<int>(2 * (size_t)kmax);
+    sc.order = bump.take<int>((size_t)N);
+    sc.offs = bump.take<int>((size_t)kmax);
     sc.assign = bump.take<int32_t>((size_t)N);
     sc.cn = bump.take<float>((size_t)kmax);
     // bf16 planes for the assignment filter: points (one plane if the input was bf16), centroids
@@ -241,6 +238,8 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
     HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
     HIPCHK(hipMemsetAsync(sc.cmax_bits, 0, sizeof(unsigned), h.stream));
     HIPCHK(hipMemsetAsync(sc.nflagged, 0, 2 * sizeof(int), h.stream));
+    HIPCHK(hipMemsetAsync(sc.counts2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
+    HIPCHK(hipMemsetAsync(sc.cursor2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
     for (int it = 0; it < T; ++it) {
         if (h.exact_assign_only) {
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, h.stream));
@@ -252,7 +251,7 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, sc.flagged, sc.nflagged, h.stream));
         }
         // the last iteration leaves the count of undecided points in place for lcn_get_info
-        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.psums, sc.pcounts, cent, sc.cmax_bits,
+        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.counts2, sc.cursor2, sc.order, sc.offs, it, cent, sc.cmax_bits,
                                     it + 1 < T ? sc.nflagged : nullptr, h.stream));
     }
     return LCN_OK;

@@ -62,11 +62,12 @@ hipError_t launch_assign_pairs(const float *Z, int d, const float *cent, int32_t
                                const int *pair_count, hipStream_t s);
 hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
                                        hipStream_t s);
-// psums: [chunks][k][d] int64, pcounts: [chunks][k]; chunks = ceil(N / kmeans_chunk_points(N)) <= 32.
-// reset_a / reset_b (nullable) are cleared for the next assignment step.
-hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, long long *psums,
-                                int *pcounts, float *cent, unsigned *reset_a, int *reset_b, hipStream_t s);
-int kmeans_chunk_points(long long N);
+// counts2 / cursor2: [2][k] ints each, zero before the first update of a k-means run; order: [N], offs: [k] ints;
+// `parity` alternates from update to update.  reset_a / reset_b (nullable) are cleared for the next
+// assignment step.
+hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, int *counts2,
+                                int *cursor2, int *order, int *offs, int parity, float *cent, unsigned *reset_a,
+                                int *reset_b, hipStream_t s);
 
 struct SortBuffers {
     int R, b;
