@@ -198,6 +198,9 @@ def main():
     bytes_launch = bytes_iter / 2.0
     launch_us = run_mean * 1e3 / max(n_launch, 1)
     achieved = bytes_launch / (launch_us * 1e-6) / 1e9
+    # HBM bytes per pass_kernel launch from the rocprofv3 counter runs (FETCH_SIZE scaled by 2.000 plus
+    # WRITE_SIZE scaled by 1.000 against a 256 MiB device copy); see profiles/lcn_sinkhorn_c*.md
+    traffic = {3: 37.37e6 + 2.40e6, 5: 674.73e6 + 29.39e6}.get(args.config) if args.mode == "lcn" else None
     out = {
         "metric": "LCN-Sinkhorn iterations/s (n=20k,d=300); build ms; % HBM peak; cost rel.err",
         "value": its_per_s, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -207,7 +210,7 @@ def main():
                    "nnz_stored": nnz_stored},
         "build_ms": float(np.mean(build_ms)), "sinkhorn_ms": run_mean, "distance": dist,
         "roofline": {"bound": "hbm", "kernel": "pass_kernel (one half-iteration)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": bytes_launch, "launch_us": launch_us},
     }
     if args.copy_calibration:
