@@ -142,12 +142,13 @@ def nystrom(X, Y, L, cost, lam, ridge=0.0):
     return U, W
 
 
-def pattern_values(X, Y, cost, lam, rowptr, colidx, U=None, W=None):
-    """K^sp on the pattern, or the LCN correction K^sp - (U W) when U, W are given."""
+def pattern_values(X, Y, cost, lam, rowptr, colidx, U=None, W=None, nystrom_only=False):
+    """K^sp on the pattern, or the LCN correction K^sp - (U W) when U, W are given
+    (nystrom_only: (U W) on the pattern alone)."""
     X, Y = _f32(X), _f32(Y)
     n, m = X.shape[0], Y.shape[0]
     val = np.empty(max(colidx.shape[0], 1))
-    mode = 0 if U is None else 1
+    mode = 0 if U is None else (2 if nystrom_only else 1)
     l = 0 if U is None else U.shape[1]
     lib().orc_pattern_values(_p(X, F), _p(Y, F), X.shape[1], cost, D(lam), I64(n), I64(m), _p(rowptr, I64),
                              _p(colidx, I32), mode, _p(_f64(U), D), _p(_f64(W), D), l, _p(val, D))
@@ -211,6 +212,23 @@ def sinkhorn(op: Operator, a, b, iters, state: Optional[SinkhornState] = None) -
     state.empty_rows += int(counts[1])
     state.empty_cols += int(counts[2])
     return state
+
+
+def backward(op: Operator, lam, state: SinkhornState, ksp=None, knys=None):
+    """Derivatives of the distance at the (converged) scalings of `state` (Prop. 1):
+    returns (gU n x l, gW l x m, gsp, gnys), entries None where the part is absent.
+    ksp / knys: K^sp and K^sp_Nys on the pattern of `op`."""
+    l = op.l
+    gU = np.empty((op.n, l)) if l else None
+    gW = np.empty((l, op.m)) if l else None
+    nnz = 0 if op.colidx is None else op.colidx.shape[0]
+    ksp, knys = _f64(ksp), _f64(knys)
+    gsp = np.empty(max(nnz, 1)) if ksp is not None else None
+    gnys = np.empty(max(nnz, 1)) if knys is not None else None
+    lib().orc_backward(I64(op.n), I64(op.m), l, _p(op.U, D), _p(op.W, D), _p(op.rowptr, I64), _p(op.colidx, I32),
+                       _p(ksp, D), _p(knys, D), D(lam), _p(state.log_u, D), _p(state.log_v, D), _p(gU, D), _p(gW, D),
+                       _p(gsp, D), _p(gnys, D))
+    return gU, gW, None if gsp is None else gsp[:nnz], None if gnys is None else gnys[:nnz]
 
 
 def marginals(op: Operator, a, b, lam, state: SinkhornState):

@@ -342,7 +342,8 @@ int orc_nystrom(const float *X, int64_t n, const float *Y, int64_t m, int d, con
 
 /* mode 0: K^sp_ij = exp(-c(x_i, y_j) / lambda) on the pattern (Sec. 3).
  * mode 1: the LCN correction K^sp_ij - (U W)_ij on the pattern (Sec. 4,
- * K_LCN = K_Nys + K^sp_Delta). */
+ * K_LCN = K_Nys + K^sp_Delta).
+ * mode 2: the Nystrom value K^sp_Nys,ij = (U W)_ij on the pattern alone. */
 void orc_pattern_values(const float *X, const float *Y, int d, int cost, double lambda, int64_t n, int64_t m,
                         const int64_t *rowptr, const int32_t *colidx, int mode, const double *U, const double *W,
                         int l, double *val)
@@ -351,11 +352,11 @@ void orc_pattern_values(const float *X, const float *Y, int d, int cost, double 
     for (int64_t i = 0; i < n; ++i)
         for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
             int64_t j = colidx[e];
-            double kij = exp(-orc_cost(X + i * d, Y + j * d, d, cost) / lambda);
-            if (mode == 1) {
+            double kij = mode == 2 ? 0.0 : exp(-orc_cost(X + i * d, Y + j * d, d, cost) / lambda);
+            if (mode >= 1) {
                 double nys = 0.0;
                 for (int k = 0; k < l; ++k) nys += U[i * l + k] * W[(int64_t)k * m + j];
-                kij -= nys;
+                kij = mode == 1 ? kij - nys : nys;
             }
             val[e] = kij;
         }
@@ -625,6 +626,50 @@ void orc_marginals(int64_t n, int64_t m, int l, const double *Kd, const double *
     free(vl);
     *dist = lambda * D;
     *resid = E;
+}
+
+/* ------------------------------------------------- analytic derivatives -- */
+
+/* Derivatives of the distance at converged scalings (Prop. 1; App. "Proof of
+ * Prop. 1"), with the four parts of the decomposed kernel
+ *     K_LCN = U W + K^sp - K^sp_Nys   (last two on the pattern)
+ * taken as independent variables.  From d d / d C_ij = P_ij (Danskin) and
+ * C_ij = -lambda log K_ij:  d d / d K_ij = -lambda P_ij / K_ij = -lambda u_i v_j, so
+ *     gU_ik   = -lambda u_i (W v)_k                       (n x l)
+ *     gW_kj   = -lambda (U^T u)_k v_j                     (l x m)
+ *     gsp_e   = -lambda u_i K^sp_ij v_j      = -lambda P^sp_ij      (w.r.t. log K^sp)
+ *     gnys_e  = +lambda u_i K^sp_Nys,ij v_j                (w.r.t. log K^sp_Nys)
+ * K^sp_Nys enters K_LCN with a minus sign, hence the plus; the proposition prints a
+ * minus there as well, which the finite-difference pin contradicts.
+ * ksp / knys: kernel values on the pattern (NULL: that output is skipped).
+ * With l = 0 (dense or sparse Sinkhorn: K = K^sp) only gsp is produced, and
+ * d d / d C = -gsp / lambda = P is the first line of the proposition. */
+void orc_backward(int64_t n, int64_t m, int l, const double *U, const double *W, const int64_t *rowptr,
+                  const int32_t *colidx, const double *ksp, const double *knys, double lambda, const double *log_u,
+                  const double *log_v, double *gU, double *gW, double *gsp, double *gnys)
+{
+    if (l > 0) {
+        double *y = (double *)calloc((size_t)l, sizeof(double));
+        double *z = (double *)calloc((size_t)l, sizeof(double));
+        for (int k = 0; k < l; ++k)
+            for (int64_t j = 0; j < m; ++j) y[k] += W[(int64_t)k * m + j] * exp(log_v[j]);
+        for (int64_t i = 0; i < n; ++i)
+            for (int k = 0; k < l; ++k) z[k] += U[i * l + k] * exp(log_u[i]);
+        for (int64_t i = 0; i < n; ++i)
+            for (int k = 0; k < l; ++k) gU[i * l + k] = -lambda * exp(log_u[i]) * y[k];
+        for (int k = 0; k < l; ++k)
+            for (int64_t j = 0; j < m; ++j) gW[(int64_t)k * m + j] = -lambda * z[k] * exp(log_v[j]);
+        free(y);
+        free(z);
+    }
+    if (rowptr) {
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                const double uv = exp(log_u[i] + log_v[colidx[e]]);
+                if (ksp) gsp[e] = -lambda * uv * ksp[e];
+                if (knys) gnys[e] = lambda * uv * knys[e];
+            }
+    }
 }
 
 /* -------------------------------------- bipartite-matching augmentation -- */

@@ -624,3 +624,107 @@ def test_log_domain_path_survives_diverging_scalings_and_matches_library_logsume
     rr, cc, dist, resid = oracle.marginals(op, a, b, 1.0, st)
     assert np.isfinite(dist) and np.isfinite(resid)
     np.testing.assert_allclose(cc, b, atol=1e-12)   # columns were scaled last
+
+
+# ---- analytic derivatives (Prop. 1) ------------------------------------------
+
+def _small_lcn(seed=31):
+    """A small decomposed kernel with every entry positive, its four parts separate."""
+    r = rng(seed)
+    n, m, d, l = 9, 11, 3, 3
+    X = (0.4 * r.standard_normal((n, d))).astype(np.float32)
+    Y = (0.4 * r.standard_normal((m, d))).astype(np.float32)
+    lam = 1.5
+    L = np.concatenate([X, Y])[[0, 7, 15]]
+    U, W = oracle.nystrom(X, Y, L, COST_SQEUCLID, lam, 0.0)
+    bucket = np.concatenate([np.arange(n) % 2, np.arange(m) % 2]).astype(np.int32)[None, :]
+    rowptr, colidx = oracle.pattern(bucket, n, m)
+    ksp = oracle.pattern_values(X, Y, COST_SQEUCLID, lam, rowptr, colidx)
+    knys = oracle.pattern_values(X, Y, COST_SQEUCLID, lam, rowptr, colidx, U, W, nystrom_only=True)
+    a = r.random(n) + 0.5
+    b = r.random(m) + 0.5
+    return n, m, lam, U, W, rowptr, colidx, ksp, knys, a / a.sum(), b / b.sum()
+
+
+def _converged(n, m, lam, U, W, rowptr, colidx, ksp, knys, a, b, iters=3000):
+    op = Operator(n, m, U=U, W=W, rowptr=rowptr, colidx=colidx, val=ksp - knys)
+    assert op.dense().min() > 0
+    st = oracle.sinkhorn(op, a, b, iters)
+    _, _, dist, resid = oracle.marginals(op, a, b, lam, st)
+    assert resid < 1e-13
+    return op, st, dist
+
+
+def test_backward_matches_finite_differences_of_the_converged_distance():
+    """Prop. 1 with U, W, log K^sp and log K^sp_Nys as independent variables:
+    central differences of the converged distance reproduce every derivative,
+    including the sign of the K^sp_Nys term (which enters the kernel negatively)."""
+    n, m, lam, U, W, rowptr, colidx, ksp, knys, a, b = _small_lcn()
+    op, st, d0 = _converged(n, m, lam, U, W, rowptr, colidx, ksp, knys, a, b)
+    gU, gW, gsp, gnys = oracle.backward(op, lam, st, ksp, knys)
+    h = 1e-5
+
+    def dist(U_=U, W_=W, ksp_=ksp, knys_=knys):
+        return _converged(n, m, lam, U_, W_, rowptr, colidx, ksp_, knys_, a, b)[2]
+
+    for (i, k) in [(0, 0), (4, 2), (8, 1)]:
+        E = np.zeros_like(U)
+        E[i, k] = h
+        fd = (dist(U_=U + E) - dist(U_=U - E)) / (2 * h)
+        np.testing.assert_allclose(gU[i, k], fd, rtol=2e-5)
+    for (k, j) in [(0, 0), (2, 10), (1, 5)]:      # n != m: a transposed result would not even fit
+        E = np.zeros_like(W)
+        E[k, j] = h
+        fd = (dist(W_=W + E) - dist(W_=W - E)) / (2 * h)
+        np.testing.assert_allclose(gW[k, j], fd, rtol=2e-5)
+    for e in [0, 17, len(colidx) - 1]:
+        f = np.ones_like(ksp)
+        f[e] = math.exp(h)
+        fd = (dist(ksp_=ksp * f) - dist(ksp_=ksp / f)) / (2 * h)
+        np.testing.assert_allclose(gsp[e], fd, rtol=2e-5)
+        fd = (dist(knys_=knys * f) - dist(knys_=knys / f)) / (2 * h)
+        np.testing.assert_allclose(gnys[e], fd, rtol=2e-5)
+        assert gsp[e] < 0 < gnys[e]
+
+
+def test_backward_mass_identity():
+    """sum U o gU = sum W o gW = -lambda (mass of the Nystrom part), sum gsp = -lambda (mass of
+    the K^sp part), sum gnys = +lambda (mass of the K^sp_Nys part); the plan's mass is 1, so
+    sum U o gU + sum gsp + sum gnys = -lambda."""
+    n, m, lam, U, W, rowptr, colidx, ksp, knys, a, b = _small_lcn(32)
+    op, st, _ = _converged(n, m, lam, U, W, rowptr, colidx, ksp, knys, a, b)
+    gU, gW, gsp, gnys = oracle.backward(op, lam, st, ksp, knys)
+    u, v = np.exp(st.log_u), np.exp(st.log_v)
+    mass_nys = u @ (U @ W) @ v
+    np.testing.assert_allclose((U * gU).sum(), -lam * mass_nys, rtol=1e-12)
+    np.testing.assert_allclose((W * gW).sum(), -lam * mass_nys, rtol=1e-12)
+    np.testing.assert_allclose((U * gU).sum() + gsp.sum() + gnys.sum(), -lam, rtol=1e-11)
+
+
+def test_backward_dense_gives_the_plan():
+    """First line of Prop. 1: d d / d C = P for plain entropic OT (K = K^sp on the full pattern),
+    against the materialised plan and against a central difference in one cost entry."""
+    r = rng(33)
+    n, m = 6, 8
+    C = r.random((n, m))
+    lam = 0.7
+    a = np.full(n, 1 / n)
+    b = np.full(m, 1 / m)
+    rowptr = (np.arange(n + 1) * m).astype(np.int64)
+    colidx = np.tile(np.arange(m), n).astype(np.int32)
+
+    def solve(Cm):
+        K = np.exp(-Cm / lam)
+        op = Operator(n, m, rowptr=rowptr, colidx=colidx, val=K.ravel())
+        st = oracle.sinkhorn(op, a, b, 3000)
+        return op, st, K, oracle.marginals(op, a, b, lam, st)[2]
+
+    op, st, K, d0 = solve(C)
+    _, _, gsp, _ = oracle.backward(op, lam, st, ksp=K.ravel())
+    P = plan(K, st)
+    np.testing.assert_allclose(-gsp.reshape(n, m) / lam, P, rtol=1e-12)
+    h = 1e-5
+    E = np.zeros_like(C)
+    E[2, 5] = h
+    fd = (solve(C + E)[3] - solve(C - E)[3]) / (2 * h)
+    np.testing.assert_allclose(P[2, 5], fd, rtol=2e-5)
