@@ -233,6 +233,17 @@ def main():
         except lcn.LcnError as e:
             out["cost_rel_err_vs_dense"] = None
             out["accuracy_note"] = str(e)
+    if args.mode in ("lcn", "nystrom") and not args.no_accuracy:
+        # analytic derivatives (Prop. 1) of the converged state, outside the timed region
+        hb = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh, workspace=ws)
+        lcn.sinkhorn_run(hb, p.iters)
+        nnz_b = int(lcn.lcn_get_csr(hb)[1].numel()) if args.mode == "lcn" else 0
+        lcn.lcn_backward(hb, nnz_b)          # allocates its outputs; the second call is the timed one
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        lcn.lcn_backward(hb, nnz_b)
+        out["backward_ms"] = 1e3 * (time.perf_counter() - tb)
+        lcn.lcn_destroy(hb)
     if not args.no_cpu_baseline:
         base, (st, dist_o, resid_o) = cpu_baseline(p, args.cpu_iters)
         out["cpu_baseline"] = base

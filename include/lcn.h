@@ -190,6 +190,24 @@ lcn_status lcn_get_csr(lcn_handle h, int64_t *nnz_host, int64_t *rowptr_dev, int
 /* Nystrom factors as stored: U (n x l) and W^T (m x l), fp32 device. */
 lcn_status lcn_get_factors(lcn_handle h, float *U_dev, float *Wt_dev);
 
+/* Analytic derivatives of the distance with respect to the parts of the
+ * decomposed kernel K_LCN = U W + K^sp - K^sp_Nys, taken as independent
+ * variables, at the current scalings (Prop. 1; exact at convergence):
+ *   gU_dev   (n x l)   -lambda u_i (W v)_k
+ *   gWt_dev  (m x l)   -lambda (U^T u)_k v_j   (the l x m derivative, transposed like W^T in lcn_get_factors)
+ *   gsp_dev            -lambda u_i K^sp_ij v_j      w.r.t. log K^sp      (= -lambda P^sp)
+ *   gnys_dev           +lambda u_i K^sp_Nys,ij v_j  w.r.t. log K^sp_Nys  (the term enters the kernel negatively)
+ * gsp_dev / gnys_dev hold one value per entry of the pattern in the order of
+ * lcn_get_csr.  Which outputs exist depends on the mode: lcn all four, nystrom
+ * gU and gWt, sparse and dense gsp (for those d d / d C = -gsp / lambda is the
+ * plan itself); asking for one that does not exist is LCN_ERR_STATE.  Outputs
+ * are device fp32, any may be NULL.  scratch_dev: device memory of at least
+ * lcn_backward_scratch_bytes() bytes (0 if no pattern output is requested),
+ * 256-byte aligned; too small is LCN_ERR_ALLOC.  Synchronises the stream. */
+lcn_status lcn_backward_scratch_bytes(lcn_handle h, size_t *bytes);
+lcn_status lcn_backward(lcn_handle h, float *gU_dev, float *gWt_dev, float *gsp_dev, float *gnys_dev,
+                        void *scratch_dev, size_t scratch_bytes);
+
 /* Sizes and counters: stored sparse entries (tiles, including pairs that a
  * later round repeats and that are stored as zero), unique pairs, and the
  * numeric-fault counters accumulated since the build. */

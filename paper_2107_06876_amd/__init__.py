@@ -10,4 +10,5 @@ from .binding import (  # noqa: F401
     MODE_SPARSE, LcnError, LcnHandle, library_path, load_library, lcn_build, lcn_destroy, lcn_get_buckets,
     lcn_get_csr, lcn_get_factors, lcn_get_info, lcn_get_landmarks, lcn_get_scalings, lcn_last_run_timing,
     lcn_set_scalings, lcn_status_string, lcn_workspace_bytes, plan_marginals, sinkhorn_run, transport_cost,
-    LcnBatchHandle, lcn_batched_get, lcn_batched_results, lcn_build_batched)
+    LcnBatchHandle, lcn_batched_get, lcn_batched_results, lcn_build_batched, lcn_backward,
+    lcn_backward_scratch_bytes)

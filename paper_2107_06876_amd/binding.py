@@ -83,6 +83,8 @@ def load_library():
         lib.lcn_get_buckets.argtypes = [vp, vp]
         lib.lcn_get_csr.argtypes = [vp, ctypes.POINTER(i64), vp, vp, vp]
         lib.lcn_get_factors.argtypes = [vp, vp, vp]
+        lib.lcn_backward_scratch_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.lcn_backward.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_size_t]
         lib.lcn_get_info.argtypes = [vp, ctypes.POINTER(Info)]
         lib.lcn_last_run_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         lib.lcn_destroy.argtypes = [vp]
@@ -276,6 +278,34 @@ def lcn_get_factors(h: LcnHandle):
     if st != OK:
         raise LcnError(st, "lcn_get_factors")
     return U, Wt
+
+
+def lcn_backward_scratch_bytes(h: LcnHandle) -> int:
+    nbytes = ctypes.c_size_t(0)
+    st = load_library().lcn_backward_scratch_bytes(h.raw, ctypes.byref(nbytes))
+    if st != OK:
+        raise LcnError(st, "lcn_backward_scratch_bytes")
+    return int(nbytes.value)
+
+
+def lcn_backward(h: LcnHandle, nnz: int = 0, factors: bool = True, pattern: bool = True):
+    """Derivatives of the distance (Prop. 1): returns (gU, gWt, gsp, gnys), None for the
+    parts the mode does not have.  nnz: entries of the pattern (from lcn_get_csr)."""
+    has_f = factors and h.l > 0
+    has_p = pattern and nnz > 0
+    gU = torch.empty((h.n, h.l), dtype=torch.float32, device=h.device) if has_f else None
+    gWt = torch.empty((h.m, h.l), dtype=torch.float32, device=h.device) if has_f else None
+    gsp = torch.empty(nnz, dtype=torch.float32, device=h.device) if has_p else None
+    gnys = torch.empty(nnz, dtype=torch.float32, device=h.device) if has_p and h.l > 0 else None
+    scratch = None
+    if has_p:
+        scratch = torch.empty(lcn_backward_scratch_bytes(h) + 256, dtype=torch.uint8, device=h.device)
+    sp = 0 if scratch is None else (scratch.data_ptr() + 255) // 256 * 256
+    st = load_library().lcn_backward(h.raw, _ptr(gU), _ptr(gWt), _ptr(gsp), _ptr(gnys), ctypes.c_void_p(sp),
+                                     0 if scratch is None else scratch.numel() - 256)
+    if st != OK:
+        raise LcnError(st, "lcn_backward")
+    return gU, gWt, gsp, gnys
 
 
 def lcn_get_info(h: LcnHandle) -> Info:

@@ -399,7 +399,7 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
                                                          double inv_lambda, const double *__restrict__ zn,
                                                          const float *__restrict__ U, const float *__restrict__ Wt,
                                                          int lp, int log_values, float *vals_x, float *vals_y,
-                                                         unsigned long long *unique_counter)
+                                                         unsigned long long *unique_counter, BackwardArgs bw)
 {
     __shared__ float Ps[KCH][LDT];
     __shared__ float Cs[KCH][LDT];
@@ -499,10 +499,42 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
             __syncthreads();
             tile_fma<false>(acc, Ps, Cs);
         }
+        if (!bw.lin_u) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) kv[i][j] -= acc.v[i][j];
+                for (int j = 0; j < 4; ++j) kv[i][j] -= acc.v[i][j];
+        }
+    }
+    if (bw.lin_u) {
+        // derivatives instead of kernel values (Prop. 1): -lambda u_i K^sp_ij v_j and, from the
+        // Nystrom value still in `acc`, +lambda u_i K^sp_Nys,ij v_j, into the records of X only
+        const double scale = bw.lambda * exp(bw.acc_y[lp] + bw.acc_z[lp]);  // exponents taken out of v and u
+        for (int which = 0; which < (U ? 2 : 1); ++which) {
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int li = ty * 4 + i, lj = tx * 4 + j;
+                    const long long gi = xi[li], gj = yj[lj];
+                    double g = 0.0;
+                    if (gi >= 0 && gj >= 0) {
+                        const double uv = bw.lin_u[gi] * bw.lin_v[U ? gj : gj - B.n] * scale;
+                        g = which == 0 ? -uv * kv[i][j] : uv * acc.v[i][j];
+                    }
+                    vals[li][lj] = (float)g;
+                }
+            __syncthreads();
+            float *dst = which == 0 ? bw.rec_sp : bw.rec_nys;
+            const int lane = tid & 63, w = tid >> 6;
+            if (dst)
+                for (int rr = w; rr < TILE; rr += 4) {
+                    const int lj = tj * 64 + lane;
+                    if (xdst[rr] >= 0 && lj < ny) dst[xdst[rr] + lj] = vals[rr][lane];
+                }
+        }
+        return;
     }
     // drop pairs an earlier round owns, count the rest
     unsigned mine = 0;
@@ -538,7 +570,80 @@ hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s)
     hipLaunchKernelGGL(correction_kernel, dim3(ntiles), dim3(256), 0, s, h.sort, h.Z, h.d, h.cost, 1.0 / h.lambda,
                        h.cost == LCN_COST_COSINE ? h.zn : (const double *)nullptr,
                        lcn_mode ? h.U : (const float *)nullptr, lcn_mode ? h.Wt : (const float *)nullptr, h.lp,
-                       h.log_domain, h.vals_x, h.vals_y, h.counters + 3);
+                       h.log_domain, h.vals_x, h.vals_y, h.counters + 3, BackwardArgs{});
+    return hipGetLastError();
+}
+
+// Derivatives on the pattern for the lcn mode, in the layout of the row records of X
+// (rec_sp, rec_nys: nnz_stored floats each, either may be null).
+hipError_t launch_backward_pattern(const Handle &h, float *rec_sp, float *rec_nys, hipStream_t s)
+{
+    if (h.ntiles <= 0) return hipSuccess;
+    BackwardArgs bw;
+    bw.lin_u = h.lin_u;
+    bw.lin_v = h.lin_v;
+    bw.acc_y = h.acc[0];
+    bw.acc_z = h.acc[1];
+    bw.lambda = h.lambda;
+    bw.rec_sp = rec_sp;
+    bw.rec_nys = rec_nys;
+    hipLaunchKernelGGL(correction_kernel, dim3(h.ntiles), dim3(256), 0, s, h.sort, h.Z, h.d, h.cost, 1.0 / h.lambda,
+                       h.cost == LCN_COST_COSINE ? h.zn : (const double *)nullptr, h.U, h.Wt, h.lp, 0,
+                       (float *)nullptr, (float *)nullptr, (unsigned long long *)nullptr, bw);
+    return hipGetLastError();
+}
+
+// out[i][k] = -lambda x_i acc_k for i < rows, k < l (Prop. 1: x = u, acc = W v for dU; x = v,
+// acc = U^T u for dW^T); x and acc are held with exponents taken out, which `acc_a[lp] + acc_b[lp]` restores
+__global__ void outer_kernel(const double *__restrict__ lin, long long rows, const double *__restrict__ acc,
+                             const double *__restrict__ acc_a, const double *__restrict__ acc_b, int l, int lp,
+                             double lambda, float *__restrict__ out)
+{
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= rows * l) return;
+    const long long i = e / l;
+    const int k = (int)(e - i * l);
+    const double scale = -lambda * exp(acc_a[lp] + acc_b[lp]);
+    out[e] = (float)(scale * lin[i] * acc[k]);
+}
+
+hipError_t launch_backward_factors(const Handle &h, float *gU, float *gWt, hipStream_t s)
+{
+    if (gU)
+        hipLaunchKernelGGL(outer_kernel, dim3((unsigned)((h.n * h.l + 255) / 256)), dim3(256), 0, s, h.lin_u, h.n,
+                           h.acc[0], h.acc[0], h.acc[1], h.l, h.lp, h.lambda, gU);
+    if (gWt)
+        hipLaunchKernelGGL(outer_kernel, dim3((unsigned)((h.m * h.l + 255) / 256)), dim3(256), 0, s, h.lin_v, h.m,
+                           h.acc[1], h.acc[0], h.acc[1], h.l, h.lp, h.lambda, gWt);
+    return hipGetLastError();
+}
+
+// Kernels held as logs (sparse, dense): -lambda exp(log u_i + log K_ij + log v_j) for every stored
+// entry, in the layout of the row records of X; one wavefront per row.
+__global__ __launch_bounds__(256) void backward_log_kernel(SortBuffers B, const float *__restrict__ vals_x,
+                                                           const double *__restrict__ log_u,
+                                                           const double *__restrict__ perm_log_v, double lambda,
+                                                           float *__restrict__ rec_sp)
+{
+    const long long i = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= B.n) return;
+    const int lane = threadIdx.x & 63;
+    const double lu = log_u[i];
+    long long at = B.rowbase_x[i];
+    for (int r = 0; r < B.R; ++r) {
+        const Seg sg = B.seg_x[(long long)r * B.n + i];
+        for (int e = lane; e < sg.len; e += 64) {
+            const double t = (double)vals_x[at + e] + lu + perm_log_v[sg.vstart + e];
+            rec_sp[at + e] = t > -INFINITY ? (float)(-lambda * exp(t)) : 0.f;
+        }
+        at += sg.len;
+    }
+}
+
+hipError_t launch_backward_log(const Handle &h, float *rec_sp, hipStream_t s)
+{
+    hipLaunchKernelGGL(backward_log_kernel, dim3((unsigned)((h.n + 3) / 4)), dim3(256), 0, s, h.sort, h.vals_x, h.lin_u,
+                       h.perm_v, h.lambda, rec_sp);
     return hipGetLastError();
 }
 

@@ -818,7 +818,7 @@ __global__ void csr_kernel(SortBuffers B, const float *vals, int log_values, lon
         }
         if (bestr < 0) break;
         if (FILL) {
-            colidx[outp] = bestj;
+            if (colidx) colidx[outp] = bestj;
             if (val) {
                 const float v = vals[base + segstart[bestr] + head[bestr]];
                 val[outp] = log_values ? expf(v) : v;
@@ -842,6 +842,13 @@ hipError_t launch_csr_fill(const Handle &h, const long long *rowptr, int32_t *co
 {
     hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.vals_x,
                        h.log_domain, (long long *)nullptr, rowptr, colidx, val);
+    return hipGetLastError();
+}
+
+hipError_t launch_csr_values(const Handle &h, const float *rec, const long long *rowptr, float *val, hipStream_t s)
+{
+    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, rec, 0,
+                       (long long *)nullptr, rowptr, (int32_t *)nullptr, val);
     return hipGetLastError();
 }
 

@@ -593,6 +593,52 @@ lcn_status lcn_get_factors(lcn_handle hh, float *U_dev, float *Wt_dev)
     return LCN_OK;
 }
 
+static size_t backward_scratch(const Handle &h)
+{
+    const size_t rowptr = ((sizeof(long long) * (size_t)(h.n + 1)) + 255) / 256 * 256;
+    const size_t rec = ((sizeof(float) * (size_t)(h.nnz_stored + 64)) + 255) / 256 * 256;
+    return rowptr + 2 * rec;
+}
+
+lcn_status lcn_backward_scratch_bytes(lcn_handle hh, size_t *bytes)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    if (!bytes) return LCN_ERR_INVALID_ARG;
+    const Handle &h = *(Handle *)hh;
+    *bytes = h.R > 0 ? backward_scratch(h) : 0;
+    return LCN_OK;
+}
+
+lcn_status lcn_backward(lcn_handle hh, float *gU_dev, float *gWt_dev, float *gsp_dev, float *gnys_dev,
+                        void *scratch_dev, size_t scratch_bytes)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if ((gU_dev || gWt_dev) && h.l == 0) return LCN_ERR_STATE;
+    if (gsp_dev && h.R == 0) return LCN_ERR_STATE;
+    if (gnys_dev && (h.R == 0 || h.l == 0)) return LCN_ERR_STATE;
+    if (gU_dev || gWt_dev) HIPCHK(launch_backward_factors(h, gU_dev, gWt_dev, h.stream));
+    if (gsp_dev || gnys_dev) {
+        if (!scratch_dev || ((uintptr_t)scratch_dev & 255)) return LCN_ERR_INVALID_ARG;
+        if (scratch_bytes < backward_scratch(h)) return LCN_ERR_ALLOC;
+        const size_t rowptr_bytes = ((sizeof(long long) * (size_t)(h.n + 1)) + 255) / 256 * 256;
+        const size_t rec_bytes = ((sizeof(float) * (size_t)(h.nnz_stored + 64)) + 255) / 256 * 256;
+        long long *rowptr = (long long *)scratch_dev;
+        float *rec_sp = (float *)((char *)scratch_dev + rowptr_bytes);
+        float *rec_nys = (float *)((char *)scratch_dev + rowptr_bytes + rec_bytes);
+        HIPCHK(launch_csr_count(h, rowptr, h.stream));
+        HIPCHK(launch_scan_i64(rowptr, h.n, h.stream));
+        if (h.log_domain)
+            HIPCHK(launch_backward_log(h, rec_sp, h.stream));
+        else
+            HIPCHK(launch_backward_pattern(h, gsp_dev ? rec_sp : nullptr, gnys_dev ? rec_nys : nullptr, h.stream));
+        if (gsp_dev) HIPCHK(launch_csr_values(h, rec_sp, rowptr, gsp_dev, h.stream));
+        if (gnys_dev) HIPCHK(launch_csr_values(h, rec_nys, rowptr, gnys_dev, h.stream));
+    }
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
 lcn_status lcn_get_info(lcn_handle hh, lcn_info *info)
 {
     if (!valid(hh)) return LCN_ERR_STATE;

@@ -39,6 +39,14 @@ struct PassSide {
 
 enum PassMode { PASS_UPDATE = 0, PASS_QUERY = 1, PASS_INIT = 2 };
 
+// What the tile kernel of the sparse values needs to produce derivatives instead (lin_u == nullptr: values).
+struct BackwardArgs {
+    const double *lin_u = nullptr, *lin_v = nullptr;  // scalings with their exponents taken out
+    const double *acc_y = nullptr, *acc_z = nullptr;  // accumulators; entry lp holds the exponent of v resp. u
+    double lambda = 0.0;
+    float *rec_sp = nullptr, *rec_nys = nullptr;      // outputs, layout of the row records of X
+};
+
 struct Handle;
 
 // ---- structure build (kernels_structure.hip) -------------------------------
@@ -110,6 +118,12 @@ hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lm, double
 hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N, int K, float *C32, int ldc,
                            hipStream_t s);
 hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s);
+// derivatives of the distance (Prop. 1): factor parts, and pattern parts in the layout of X's row records
+hipError_t launch_backward_factors(const Handle &h, float *gU, float *gWt, hipStream_t s);
+hipError_t launch_backward_pattern(const Handle &h, float *rec_sp, float *rec_nys, hipStream_t s);
+hipError_t launch_backward_log(const Handle &h, float *rec_sp, hipStream_t s);
+// row records of X -> canonical CSR order (rowptr from launch_csr_count + launch_scan_i64)
+hipError_t launch_csr_values(const Handle &h, const float *rec, const long long *rowptr, float *val, hipStream_t s);
 
 // ---- iteration (kernels_iter.hip) ------------------------------------------
 hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s);
