@@ -121,6 +121,38 @@ struct FRow {
     }
 };
 
+// Per-row metadata, read from the packed record (see meta_kernel): wave-uniform,
+// so it lives in scalar registers.
+template <int RR>
+struct RowMeta {
+    long long base;
+    float marg;
+    double log_marg;
+    int vstart[RR];
+    int len[RR];
+    int pos;     // lane r < R: position of the row in round r's bucket order
+    double lin;  // query mode: the row's current scaling
+};
+
+template <int RR, int MODE>
+__device__ inline void load_meta(RowMeta<RR> &M, const PassSide &S, int R, long long row, int lane)
+{
+    // the records are written once at build time: reading them through the constant
+    // address space lets the compiler use scalar loads although the kernel also stores
+    typedef const __attribute__((address_space(4))) int *const_int_ptr;
+    const_int_ptr rec = (const_int_ptr)(S.meta + row * S.meta_stride);
+    M.base = ((long long)rec[1] << 32) | (unsigned)rec[0];
+    M.marg = __int_as_float(rec[2]);
+    M.log_marg = __hiloint2double(rec[5], rec[4]);
+#pragma unroll
+    for (int r = 0; r < RR; ++r) {
+        M.vstart[r] = r < R ? rec[6 + 2 * r] : 0;
+        M.len[r] = r < R ? rec[7 + 2 * r] : 0;
+    }
+    M.pos = (MODE != PASS_QUERY && lane < R) ? rec[6 + 2 * R + lane] : 0;
+    M.lin = MODE == PASS_QUERY ? S.lin_out[row] : 0.0;
+}
+
 // A sweep that finishes the previous sweep's reduction itself passes the totals
 // from the reducing workgroups to all others through the accumulator itself:
 // the sweep before filled the accumulator with ACC_PENDING (a NaN bit pattern no

@@ -100,12 +100,17 @@ def test_fused_reduction_matches_separate_launches(monkeypatch):
     """A sweep that adds up its predecessor's partial sums itself gives the
     same bits as a sweep followed by the separate reduction launch, also when
     the iterations are split into runs of 1, 2 and 3 (first, inner and last
-    sweep of a run take different paths)."""
+    sweep of a run take different paths) and with unequal sides."""
     import torch
     import paper_2107_06876_amd as lcn
     from parity import gpu_build
-    for p in (workloads.config1(), workloads.config3(n=3000, d=48, landmarks=96, buckets=12, rounds=3, iters=6,
-                                                      name="C3 reduced")):
+    r = np.random.default_rng(5)
+    pu = workloads.config1()
+    pu.X = np.ascontiguousarray(pu.X[:700])
+    pu.a = (r.random(700) + 0.5).astype(np.float32)
+    pu.a /= pu.a.sum()
+    for p in (workloads.config1(), pu,
+              workloads.config3(n=3000, d=48, landmarks=96, buckets=12, rounds=3, iters=6, name="C3 reduced")):
         res = {}
         for fused in ("1", "0"):
             monkeypatch.setenv("LCN_FUSED_REDUCE", fused)
