@@ -233,6 +233,27 @@ def main():
         except lcn.LcnError as e:
             out["cost_rel_err_vs_dense"] = None
             out["accuracy_note"] = str(e)
+    if args.config == 3 and args.mode == "lcn" and not args.no_accuracy:
+        # The same comparison on the pre-aligned variant (Y rotated back, matched rows close, as after
+        # the Procrustes step of the paper's embedding runs): there the dense distance is not a
+        # near-cancellation of transport cost and entropy, and the relative error means something.
+        pa = workloads.config3(prealigned=True, name="C3 prealigned")
+        Ya = torch.from_numpy(pa.Y).to(dev)
+        try:
+            hl = lcn.lcn_build(X, Ya, a, b, pa.lam, pa.cost, mode, landmarks=lm, lsh=lsh)
+            lcn.sinkhorn_run(hl, pa.iters)
+            d_l = lcn.transport_cost(hl)
+            lcn.lcn_destroy(hl)
+            del hl
+            hd = lcn.lcn_build(X, Ya, a, b, pa.lam, pa.cost, lcn.MODE_DENSE)
+            lcn.sinkhorn_run(hd, pa.iters)
+            d_d = lcn.transport_cost(hd)
+            lcn.lcn_destroy(hd)
+            del hd
+            out["prealigned"] = {"distance_lcn": d_l, "distance_dense": d_d,
+                                 "cost_rel_err_vs_dense": abs(d_l - d_d) / abs(d_d)}
+        except lcn.LcnError as e:
+            out["prealigned"] = {"note": str(e)}
     if args.mode in ("lcn", "nystrom") and not args.no_accuracy:
         # analytic derivatives (Prop. 1) of the converged state, outside the timed region
         hb = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh, workspace=ws)
