@@ -208,6 +208,13 @@ lcn_status lcn_backward_scratch_bytes(lcn_handle h, size_t *bytes);
 lcn_status lcn_backward(lcn_handle h, float *gU_dev, float *gWt_dev, float *gsp_dev, float *gnys_dev,
                         void *scratch_dev, size_t scratch_bytes);
 
+/* Rows i0 .. i0 + nrows - 1 of the current transport plan P = diag(u) K~ diag(v)
+ * (Sec. 2; for the lcn mode the decomposed plan of Sec. 4 eq. 4 written out),
+ * as a dense nrows x m block, row-major, device fp32.  For inspection and for
+ * plan-quality measures (Sec. 8: correlation and overlap of the largest entries
+ * with the exact plan); costs O(nrows m l).  Synchronises the stream. */
+lcn_status lcn_plan_rows(lcn_handle h, int64_t i0, int64_t nrows, float *out_dev);
+
 /* Sizes and counters: stored sparse entries (tiles, including pairs that a
  * later round repeats and that are stored as zero), unique pairs, and the
  * numeric-fault counters accumulated since the build. */

@@ -85,6 +85,7 @@ def load_library():
         lib.lcn_get_factors.argtypes = [vp, vp, vp]
         lib.lcn_backward_scratch_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         lib.lcn_backward.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_size_t]
+        lib.lcn_plan_rows.argtypes = [vp, i64, i64, vp]
         lib.lcn_get_info.argtypes = [vp, ctypes.POINTER(Info)]
         lib.lcn_last_run_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         lib.lcn_destroy.argtypes = [vp]
@@ -306,6 +307,16 @@ def lcn_backward(h: LcnHandle, nnz: int = 0, factors: bool = True, pattern: bool
     if st != OK:
         raise LcnError(st, "lcn_backward")
     return gU, gWt, gsp, gnys
+
+
+def lcn_plan_rows(h: LcnHandle, i0: int, nrows: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Rows i0 .. i0 + nrows - 1 of the current transport plan as a dense (nrows, m) block."""
+    if out is None:
+        out = torch.empty((nrows, h.m), dtype=torch.float32, device=h.device)
+    st = load_library().lcn_plan_rows(h.raw, i0, nrows, _ptr(_dev(out, torch.float32)))
+    if st != OK:
+        raise LcnError(st, "lcn_plan_rows")
+    return out
 
 
 def lcn_get_info(h: LcnHandle) -> Info:

@@ -618,6 +618,53 @@ hipError_t launch_backward_factors(const Handle &h, float *gU, float *gWt, hipSt
     return hipGetLastError();
 }
 
+// Nystrom part of the plan for a block of rows: out[i - i0][j] = u_i (U_i . W_:j) v_j, 64 x 64 per workgroup.
+__global__ __launch_bounds__(256) void plan_nystrom_kernel(const float *__restrict__ U, const float *__restrict__ Wt,
+                                                           int lp, long long i0, long long nrows, long long m,
+                                                           const double *__restrict__ lin_u,
+                                                           const double *__restrict__ lin_v,
+                                                           const double *__restrict__ acc_y,
+                                                           const double *__restrict__ acc_z, float *__restrict__ out)
+{
+    __shared__ float Ps[KCH][LDT];
+    __shared__ float Cs[KCH][LDT];
+    __shared__ long long xi[TILE], yj[TILE];
+    const int tid = threadIdx.x;
+    if (tid < TILE) {
+        const long long i = (long long)blockIdx.y * TILE + tid;
+        xi[tid] = i < nrows ? i0 + i : -1;
+    } else if (tid < 2 * TILE) {
+        const long long j = (long long)blockIdx.x * TILE + tid - TILE;
+        yj[tid - TILE] = j < m ? j : -1;
+    }
+    TileAcc acc;
+    tile_zero(acc);
+    for (int k0 = 0; k0 < lp; k0 += KCH) {
+        __syncthreads();
+        stage_rows(Ps, U, lp, xi, k0, lp);
+        stage_rows(Cs, Wt, lp, yj, k0, lp);
+        __syncthreads();
+        tile_fma<false>(acc, Ps, Cs);
+    }
+    const double scale = exp(acc_y[lp] + acc_z[lp]);  // exponents taken out of v and u
+    const int tx = tid & 15, ty = tid >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const long long gi = xi[ty * 4 + i], gj = yj[tx * 4 + j];
+            if (gi >= 0 && gj >= 0) out[(gi - i0) * m + gj] = (float)(acc.v[i][j] * lin_u[gi] * lin_v[gj] * scale);
+        }
+}
+
+hipError_t launch_plan_nystrom(const Handle &h, long long i0, long long nrows, float *out, hipStream_t s)
+{
+    dim3 grid((unsigned)((h.m + TILE - 1) / TILE), (unsigned)((nrows + TILE - 1) / TILE));
+    hipLaunchKernelGGL(plan_nystrom_kernel, grid, dim3(256), 0, s, h.U, h.Wt, h.lp, i0, nrows, h.m, h.lin_u, h.lin_v,
+                       h.acc[0], h.acc[1], out);
+    return hipGetLastError();
+}
+
 // Kernels held as logs (sparse, dense): -lambda exp(log u_i + log K_ij + log v_j) for every stored
 // entry, in the layout of the row records of X; one wavefront per row.
 __global__ __launch_bounds__(256) void backward_log_kernel(SortBuffers B, const float *__restrict__ vals_x,

@@ -845,6 +845,52 @@ hipError_t launch_csr_fill(const Handle &h, const long long *rowptr, int32_t *co
     return hipGetLastError();
 }
 
+// Sparse part of the plan for a block of rows, one wavefront per row: every stored pair of the
+// row that no earlier round owns adds u_i val_ij v_j to out[i - i0][j] (values held as logs:
+// sets exp(log u_i + val_ij + log v_j)).  Each (i, j) is touched by one lane only.
+__global__ __launch_bounds__(256) void plan_sparse_kernel(SortBuffers B, const float *__restrict__ vals_x,
+                                                          int log_values, long long i0, long long nrows,
+                                                          const double *__restrict__ lin_u,
+                                                          const double *__restrict__ lin_v,
+                                                          const double *__restrict__ acc_y,
+                                                          const double *__restrict__ acc_z, int lp,
+                                                          float *__restrict__ out)
+{
+    const long long li = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (li >= nrows) return;
+    const long long i = i0 + li;
+    const int lane = threadIdx.x & 63;
+    const long long N = B.n + B.m;
+    const double ui = lin_u[i];
+    const double scale = log_values ? 0.0 : exp(acc_y[lp] + acc_z[lp]);
+    long long at = B.rowbase_x[i];
+    for (int r = 0; r < B.R; ++r) {
+        const Seg sg = B.seg_x[(long long)r * B.n + i];
+        const int *yperm = B.perm + (long long)B.R * B.n + (long long)r * B.m;
+        const int seg0 = sg.vstart - (int)((long long)r * B.m);
+        for (int e = lane; e < sg.len; e += 64) {
+            const int j = yperm[seg0 + e];
+            if (owned_by_earlier_round(B.bucket, N, B.n, r, i, j)) continue;
+            const double v = (double)vals_x[at + e];
+            float *dst = out + li * B.m + j;
+            if (log_values) {
+                const double t = v + ui + lin_v[j];
+                *dst = t > -INFINITY ? (float)exp(t) : 0.f;
+            } else {
+                *dst += (float)(v * ui * lin_v[j] * scale);
+            }
+        }
+        at += sg.len;
+    }
+}
+
+hipError_t launch_plan_sparse(const Handle &h, long long i0, long long nrows, float *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(plan_sparse_kernel, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, s, h.sort, h.vals_x,
+                       h.log_domain, i0, nrows, h.lin_u, h.lin_v, h.acc[0], h.acc[1], h.lp, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_csr_values(const Handle &h, const float *rec, const long long *rowptr, float *val, hipStream_t s)
 {
     hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, rec, 0,

@@ -639,6 +639,21 @@ lcn_status lcn_backward(lcn_handle hh, float *gU_dev, float *gWt_dev, float *gsp
     return LCN_OK;
 }
 
+lcn_status lcn_plan_rows(lcn_handle hh, int64_t i0, int64_t nrows, float *out_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    Handle &h = *(Handle *)hh;
+    if (!out_dev || i0 < 0 || nrows < 0 || i0 + nrows > h.n) return LCN_ERR_INVALID_ARG;
+    if (nrows == 0) return LCN_OK;
+    if (h.l > 0)
+        HIPCHK(launch_plan_nystrom(h, i0, nrows, out_dev, h.stream));
+    else
+        HIPCHK(hipMemsetAsync(out_dev, 0, sizeof(float) * (size_t)nrows * (size_t)h.m, h.stream));
+    if (h.R > 0) HIPCHK(launch_plan_sparse(h, i0, nrows, out_dev, h.stream));
+    HIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
 lcn_status lcn_get_info(lcn_handle hh, lcn_info *info)
 {
     if (!valid(hh)) return LCN_ERR_STATE;

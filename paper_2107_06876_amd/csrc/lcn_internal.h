@@ -122,6 +122,9 @@ hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s);
 hipError_t launch_backward_factors(const Handle &h, float *gU, float *gWt, hipStream_t s);
 hipError_t launch_backward_pattern(const Handle &h, float *rec_sp, float *rec_nys, hipStream_t s);
 hipError_t launch_backward_log(const Handle &h, float *rec_sp, hipStream_t s);
+// rows of the plan as a dense block: Nystrom part (sets), then sparse part (adds; sets for kernels held as logs)
+hipError_t launch_plan_nystrom(const Handle &h, long long i0, long long nrows, float *out, hipStream_t s);
+hipError_t launch_plan_sparse(const Handle &h, long long i0, long long nrows, float *out, hipStream_t s);
 // row records of X -> canonical CSR order (rowptr from launch_csr_count + launch_scan_i64)
 hipError_t launch_csr_values(const Handle &h, const float *rec, const long long *rowptr, float *val, hipStream_t s);
 

@@ -24,7 +24,7 @@ def test_header_declares_the_expected_entry_points():
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
                      "lcn_get_factors", "lcn_get_info", "lcn_destroy", "lcn_status_string", "lcn_build_batched",
                      "lcn_batched_results", "lcn_batched_get", "lcn_last_run_timing", "lcn_backward",
-                     "lcn_backward_scratch_bytes"):
+                     "lcn_backward_scratch_bytes", "lcn_plan_rows"):
         assert required in names
 
 

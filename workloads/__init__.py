@@ -173,6 +173,25 @@ def config3(n: int = 20000, d: int = 300, landmarks: int = 256, buckets: int = 1
                    projections=projections(config_index, rounds, d, buckets))
 
 
+def dball(n: int = 10000, d: int = 16, landmarks: int = 20, buckets: int = 500, iters: int = 300,
+          stream: int = 1) -> Problem:
+    """Two independent samples, uniform in the unit d-ball, Euclidean cost,
+    lambda = 0.05: the one synthetic workload of the paper's accuracy table
+    (Sec. 8, Table 1, last column group: 20 landmarks and on average 20
+    neighbours for LCN).  Not a benchmark configuration."""
+    rng = _rng(7, stream)
+
+    def sample():
+        g = rng.standard_normal((n, d))
+        g /= np.linalg.norm(g, axis=1, keepdims=True)
+        return g * rng.random((n, 1)) ** (1.0 / d)
+
+    X, Y = _f32(sample()), _f32(sample())
+    a = _f32(np.full(n, 1.0 / n))
+    return Problem("d-ball", X, Y, a, a.copy(), float(np.float32(0.05)), COST_EUCLID,
+                   num_landmarks=landmarks, num_buckets=buckets, num_rounds=1, iters=iters)
+
+
 def config5(n: int = 200000, d: int = 300, landmarks: int = 512, buckets: int = 1024) -> Problem:
     """Large log-linear-only problem; inputs are stored in bfloat16."""
     return config3(n=n, d=d, landmarks=landmarks, buckets=buckets, rounds=3, iters=200,
