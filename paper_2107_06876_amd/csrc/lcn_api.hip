@@ -165,7 +165,7 @@ lcn_status check_params(long long n, long long m, int d, int dtype, float lambda
                         const lcn_landmark_params *lm, const lcn_lsh_params *lsh)
 {
     if (n < 1 || m < 1 || d < 1) return LCN_ERR_INVALID_ARG;
-    if (n > (1ll << 30) || m > (1ll << 30) || d > 65536) return LCN_ERR_INVALID_ARG;
+    if (n > (1ll << 30) || m > (1ll << 30) || d > 8192) return LCN_ERR_INVALID_ARG;  // a row of d floats must fit LDS
     if (dtype != LCN_F32 && dtype != LCN_BF16) return LCN_ERR_INVALID_ARG;
     if (!(lambda > 0.f) || !(lambda < INFINITY)) return LCN_ERR_INVALID_ARG;
     if (cost < LCN_COST_SQEUCLID || cost > LCN_COST_COSINE) return LCN_ERR_INVALID_ARG;
