@@ -100,7 +100,7 @@ lcn_status lcn_workspace_bytes(int64_t n, int64_t m, int32_t d, int32_t mode, co
                                const lcn_lsh_params *lsh, int64_t nnz_guess, size_t *bytes);
 
 /* Build the approximate kernel for one problem (Secs. 2-4).
- *   X, Y       device, n x d and m x d, of type `dtype` (bf16 is widened to fp32 on load)
+ *   X, Y       device, n x d and m x d (d <= 8192), of type `dtype` (bf16 is widened to fp32 on load)
  *   a, b       device, fp32 marginals of length n and m (positive)
  *   lambda     entropic regularisation (> 0); K = exp(-c / lambda)
  *   cost       lcn_cost; k-means always uses the Euclidean rule on the vectors as given

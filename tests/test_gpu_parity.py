@@ -129,6 +129,30 @@ def test_fused_reduction_matches_separate_launches(monkeypatch):
         lcn.lcn_destroy(h)
 
 
+def test_filter_plus_exact_rule_equals_exact_rule_everywhere(monkeypatch):
+    """Buckets and landmarks decided by the matrix-core filter plus the exact
+    rule on the undecided points (over two candidates or over all centroids)
+    are those of the exact rule applied to every point; 300 buckets exercise
+    the two-candidate path (more than 256 centroids), bf16 input the two-product
+    filter."""
+    import torch
+    import paper_2107_06876_amd as lcn
+    from parity import gpu_build
+    cases = (workloads.config1(),
+             workloads.config3(n=3000, d=48, landmarks=96, buckets=300, rounds=2, iters=2, name="C3 reduced"),
+             workloads.config3(n=2500, d=70, landmarks=64, buckets=24, rounds=2, iters=2, bf16=True,
+                               name="C5 reduced"))
+    for p in cases:
+        got = {}
+        for exact in ("0", "1"):
+            monkeypatch.setenv("LCN_EXACT_ASSIGN_ONLY", exact)
+            h = gpu_build(p, "lcn")
+            got[exact] = (lcn.lcn_get_landmarks(h), lcn.lcn_get_buckets(h), lcn.lcn_get_info(h).undecided_last)
+            lcn.lcn_destroy(h)
+        assert torch.equal(got["0"][0], got["1"][0]) and torch.equal(got["0"][1], got["1"][1]), p.name
+        assert got["1"][2] == 0
+
+
 def test_config3_full_size():
     """The benchmark configuration itself (n = m = 20 000, d = 300, l = 256,
     128 buckets x 3 rounds, 200 iterations), in the launch configuration
