@@ -781,12 +781,13 @@ __device__ inline bool owned_by_earlier_round(const int32_t *bucket, long long N
     return false;
 }
 
+// One row by one thread: the R-way merge written out.  Used for rows too long for the
+// wavefront version below.
 template <bool FILL>
-__global__ void csr_kernel(SortBuffers B, const float *vals, int log_values, long long *rowcount,
-                           const long long *rowptr, int32_t *colidx, float *val)
+__device__ inline void csr_row_serial(const SortBuffers &B, long long i, const float *vals, const float *vals2,
+                                      int log_values, long long *rowcount, const long long *rowptr, int32_t *colidx,
+                                      float *val, float *val2)
 {
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= B.n) return;
     const long long N = B.n + B.m;
     int head[8], segstart[8];
     int run = 0;
@@ -819,10 +820,9 @@ __global__ void csr_kernel(SortBuffers B, const float *vals, int log_values, lon
         if (bestr < 0) break;
         if (FILL) {
             if (colidx) colidx[outp] = bestj;
-            if (val) {
-                const float v = vals[base + segstart[bestr] + head[bestr]];
-                val[outp] = log_values ? expf(v) : v;
-            }
+            const long long at = base + segstart[bestr] + head[bestr];
+            if (val) val[outp] = log_values ? expf(vals[at]) : vals[at];
+            if (val2) val2[outp] = vals2[at];
             ++outp;
         }
         ++cnt;
@@ -831,17 +831,86 @@ __global__ void csr_kernel(SortBuffers B, const float *vals, int log_values, lon
     if (!FILL) rowcount[i] = cnt;
 }
 
+// One wavefront per row.  The row's stored columns (all rounds, T of them) go into LDS, a dropped
+// pair as INT_MAX; the place of a kept pair in the row is the number of kept columns below its own,
+// counted by brute force over the T entries (T^2 / 64 LDS reads per lane, T ~ 100).  With one round
+// the record already is the CSR row.  FILL = false only counts the kept pairs.
+constexpr int CSR_ROW_MAX = 2048;  // entries of a row the wavefront version holds
+
+template <bool FILL>
+__global__ __launch_bounds__(256) void csr_kernel(SortBuffers B, const float *vals, const float *vals2,
+                                                  int log_values, long long *rowcount, const long long *rowptr,
+                                                  int32_t *colidx, float *val, float *val2)
+{
+    __shared__ int cols_sh[4][CSR_ROW_MAX];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const long long i = (long long)blockIdx.x * 4 + w;
+    const bool live = i < B.n;
+    const long long N = B.n + B.m;
+    int T = 0;
+    if (live)
+        for (int r = 0; r < B.R; ++r) T += B.seg_x[(long long)r * B.n + i].len;
+    const long long base = live ? B.rowbase_x[i] : 0;
+    const bool serial = live && B.R > 1 && T > CSR_ROW_MAX;
+    const bool wide = live && B.R > 1 && !serial;
+    int *cols = cols_sh[w];
+    if (wide) {
+        int off = 0;
+        for (int r = 0; r < B.R; ++r) {
+            const Seg sg = B.seg_x[(long long)r * B.n + i];
+            const int *yperm = B.perm + (long long)B.R * B.n + (long long)r * B.m;
+            const int seg0 = sg.vstart - (int)((long long)r * B.m);
+            for (int e = lane; e < sg.len; e += 64) {
+                const int j = yperm[seg0 + e];
+                cols[off + e] = owned_by_earlier_round(B.bucket, N, B.n, r, i, j) ? 0x7fffffff : j;
+            }
+            off += sg.len;
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+    if (serial) {
+        if (lane == 0) csr_row_serial<FILL>(B, i, vals, vals2, log_values, rowcount, rowptr, colidx, val, val2);
+        return;
+    }
+    const long long outp = FILL ? rowptr[i] : 0;
+    long long kept = 0;
+    for (int t0 = 0; t0 < T; t0 += 64) {
+        const int t = t0 + lane;
+        int j = 0x7fffffff;
+        if (t < T) j = B.R > 1 ? cols[t] : B.perm[(long long)B.R * B.n + B.seg_x[i].vstart + t];
+        const bool keep = j != 0x7fffffff;
+        if (!FILL) {
+            kept += __popcll(__ballot(keep));
+            continue;
+        }
+        if (!keep) continue;
+        int rank = t;  // one round: the record is in column order and nothing is dropped
+        if (B.R > 1) {
+            rank = 0;
+#pragma unroll 8
+            for (int q = 0; q < T; ++q) rank += cols[q] < j ? 1 : 0;
+        }
+        if (colidx) colidx[outp + rank] = j;
+        if (val) val[outp + rank] = log_values ? expf(vals[base + t]) : vals[base + t];
+        if (val2) val2[outp + rank] = vals2[base + t];
+    }
+    if (!FILL && lane == 0) rowcount[i] = kept;
+}
+
 hipError_t launch_csr_count(const Handle &h, long long *rowcount, hipStream_t s)
 {
-    hipLaunchKernelGGL(csr_kernel<false>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.vals_x,
-                       h.log_domain, rowcount, (const long long *)nullptr, (int32_t *)nullptr, (float *)nullptr);
+    hipLaunchKernelGGL(csr_kernel<false>, dim3((unsigned)((h.n + 3) / 4)), dim3(256), 0, s, h.sort, h.vals_x,
+                       (const float *)nullptr, h.log_domain, rowcount, (const long long *)nullptr, (int32_t *)nullptr,
+                       (float *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_csr_fill(const Handle &h, const long long *rowptr, int32_t *colidx, float *val, hipStream_t s)
 {
-    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, h.vals_x,
-                       h.log_domain, (long long *)nullptr, rowptr, colidx, val);
+    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 3) / 4)), dim3(256), 0, s, h.sort, h.vals_x,
+                       (const float *)nullptr, h.log_domain, (long long *)nullptr, rowptr, colidx, val,
+                       (float *)nullptr);
     return hipGetLastError();
 }
 
@@ -891,10 +960,12 @@ hipError_t launch_plan_sparse(const Handle &h, long long i0, long long nrows, fl
     return hipGetLastError();
 }
 
-hipError_t launch_csr_values(const Handle &h, const float *rec, const long long *rowptr, float *val, hipStream_t s)
+// rec / rec2 (nullable): values in the layout of X's row records; val / val2: the same in CSR order
+hipError_t launch_csr_values(const Handle &h, const float *rec, const float *rec2, const long long *rowptr, float *val,
+                             float *val2, hipStream_t s)
 {
-    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 127) / 128)), dim3(128), 0, s, h.sort, rec, 0,
-                       (long long *)nullptr, rowptr, (int32_t *)nullptr, val);
+    hipLaunchKernelGGL(csr_kernel<true>, dim3((unsigned)((h.n + 3) / 4)), dim3(256), 0, s, h.sort, rec, rec2, 0,
+                       (long long *)nullptr, rowptr, (int32_t *)nullptr, val, val2);
     return hipGetLastError();
 }
 

@@ -632,8 +632,8 @@ lcn_status lcn_backward(lcn_handle hh, float *gU_dev, float *gWt_dev, float *gsp
             HIPCHK(launch_backward_log(h, rec_sp, h.stream));
         else
             HIPCHK(launch_backward_pattern(h, gsp_dev ? rec_sp : nullptr, gnys_dev ? rec_nys : nullptr, h.stream));
-        if (gsp_dev) HIPCHK(launch_csr_values(h, rec_sp, rowptr, gsp_dev, h.stream));
-        if (gnys_dev) HIPCHK(launch_csr_values(h, rec_nys, rowptr, gnys_dev, h.stream));
+        HIPCHK(launch_csr_values(h, gsp_dev ? rec_sp : nullptr, gnys_dev ? rec_nys : nullptr, rowptr, gsp_dev, gnys_dev,
+                                 h.stream));
     }
     HIPCHK(hipStreamSynchronize(h.stream));
     return LCN_OK;

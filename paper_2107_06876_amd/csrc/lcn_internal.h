@@ -126,7 +126,8 @@ hipError_t launch_backward_log(const Handle &h, float *rec_sp, hipStream_t s);
 hipError_t launch_plan_nystrom(const Handle &h, long long i0, long long nrows, float *out, hipStream_t s);
 hipError_t launch_plan_sparse(const Handle &h, long long i0, long long nrows, float *out, hipStream_t s);
 // row records of X -> canonical CSR order (rowptr from launch_csr_count + launch_scan_i64)
-hipError_t launch_csr_values(const Handle &h, const float *rec, const long long *rowptr, float *val, hipStream_t s);
+hipError_t launch_csr_values(const Handle &h, const float *rec, const float *rec2, const long long *rowptr, float *val,
+                             float *val2, hipStream_t s);
 
 // ---- iteration (kernels_iter.hip) ------------------------------------------
 hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_out, float *marg_out, hipStream_t s);
