@@ -127,7 +127,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 256 MiB device-to-device copy so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "can be scaled by what the same counter reads for a copy of known size")
-    ap.add_argument("--cpu-iters", type=int, default=5)
+    ap.add_argument("--cpu-iters", type=int, default=1000,
+                    help="Sinkhorn iterations of the oracle sample (with its build: about 10 s of CPU work at C3)")
     ap.add_argument("--mode", default="lcn", choices=["lcn", "sparse", "nystrom", "dense"])
     args = ap.parse_args()
     if args.gpus != 1:
