@@ -155,6 +155,23 @@ lcn_status lcn_batched_results(lcn_handle h, double *dist_host, double *resid_ho
 lcn_status lcn_batched_get(lcn_handle h, double *log_u_dev, double *log_v_dev, float *landmarks_dev,
                            int32_t *buckets_dev, float *kernel_dev);
 
+/* Deletion costs of learnable unbalanced OT (Sec. 6): out[i] = || alpha .* x_i ||_2
+ * for the `total` rows of X (device fp32, total x d, d >= 1), alpha a device
+ * fp32 vector of d weights, out device fp32 of `total` entries (the arrays
+ * lcn_batch_desc takes as del_cost_x / del_cost_y).  The squares are added in
+ * fp64 in the order of the dimensions, the root is taken in fp64 and rounded
+ * to fp32.  Asynchronous on hip_stream; nothing is allocated.  total == 0 is a
+ * no-op that reads no pointer; INVALID_ARG for null pointers, total < 0 or d < 1. */
+lcn_status lcn_deletion_costs(const float *X, int64_t total, int32_t d, const float *alpha, float *out,
+                              void *hip_stream);
+/* Regularisation parameters of multi-head OT (Sec. 6): K heads solve the same
+ * pair, each on its own embeddings, with lambda_k = 2^(k - K/2) * lambda.
+ * Writes out_host[k-1] for k = 1 .. K (host array of K floats).  The heads of a
+ * batch are ordinary problems of lcn_build_batched: pair p, head k is problem
+ * p*K + (k-1) with its own rows of X and Y, its own lambda and deletion costs.
+ * INVALID_ARG unless lambda > 0, 1 <= K <= 64 and every lambda_k is finite and > 0. */
+lcn_status lcn_head_lambdas(float lambda, int32_t num_heads, float *out_host);
+
 /* Run `iters` Sinkhorn iterations u = a ./ (K~ v), v = b ./ (K~^T u) (eq. 2),
  * continuing from the current scalings: N then M iterations equal N + M.
  * Returns after the work has finished.  NONPOSITIVE is reported if any sum

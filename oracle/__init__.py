@@ -263,6 +263,26 @@ def marginals_bp(op: Operator, kpe, keq, a, b, lam, state: SinkhornState):
     return r, c, dist.value, resid.value
 
 
+def deletion_costs(X, alpha):
+    """Deletion cost of every point for learnable unbalanced OT (Sec. 6):
+    c_i = || alpha .* x_i ||_2, as float32.  The squares are added in fp64 in
+    the order of the dimensions."""
+    X, alpha = _f32(X), _f32(alpha)
+    s = np.zeros(X.shape[0])
+    for k in range(X.shape[1]):
+        t = X[:, k].astype(np.float64) * np.float64(alpha[k])
+        s = s + t * t
+    return np.sqrt(s).astype(np.float32)
+
+
+def head_lambdas(lam, num_heads):
+    """Regularisation of the K heads of multi-head OT (Sec. 6):
+    lambda_k = 2^(k - K/2) * lambda for k = 1 .. K, as float32."""
+    K = int(num_heads)
+    return np.array([np.float32(2.0 ** (k - K / 2.0) * float(np.float32(lam))) for k in range(1, K + 1)],
+                    dtype=np.float32)
+
+
 # ------------------------------------------------------------ whole paths --
 
 @dataclass

@@ -74,6 +74,8 @@ def load_library():
                                           vp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(vp)]
         lib.lcn_batched_results.argtypes = [vp, vp, vp, vp, vp]
         lib.lcn_batched_get.argtypes = [vp, vp, vp, vp, vp, vp]
+        lib.lcn_deletion_costs.argtypes = [vp, i64, i32, vp, vp, vp]
+        lib.lcn_head_lambdas.argtypes = [ctypes.c_float, i32, vp]
         lib.sinkhorn_run.argtypes = [vp, i32]
         lib.transport_cost.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
         lib.plan_marginals.argtypes = [vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
@@ -92,7 +94,8 @@ def load_library():
         lib.lcn_destroy.restype = None
         lib.lcn_status_string.argtypes = [i32]
         lib.lcn_status_string.restype = ctypes.c_char_p
-        for name in ("lcn_build_batched", "lcn_batched_results", "lcn_batched_get", "lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
+        for name in ("lcn_build_batched", "lcn_batched_results", "lcn_batched_get", "lcn_deletion_costs",
+                     "lcn_head_lambdas", "lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
                      "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing"):
             getattr(lib, name).restype = i32
@@ -421,4 +424,31 @@ def lcn_batched_get(h: LcnBatchHandle):
                                         _ptr(out["buckets"]), _ptr(out["kernel"]))
     if st != OK:
         raise LcnError(st, "lcn_batched_get")
+    return out
+
+
+def lcn_deletion_costs(X, alpha, out=None, stream=None):
+    """c_i = || alpha .* x_i ||_2 for every row of X (float32 device tensors); returns the float32
+    device tensor of costs."""
+    X, alpha = _dev(X, torch.float32), _dev(alpha, torch.float32)
+    if X.dim() != 2 or alpha.numel() != X.shape[1]:
+        raise ValueError("X must be (total, d) and alpha (d,)")
+    if out is None:
+        out = torch.empty(X.shape[0], dtype=torch.float32, device=X.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+    st = load_library().lcn_deletion_costs(_ptr(X), X.shape[0], X.shape[1], _ptr(alpha), _ptr(out),
+                                           ctypes.c_void_p(stream))
+    if st != OK:
+        raise LcnError(st, "lcn_deletion_costs")
+    return out
+
+
+def lcn_head_lambdas(lam: float, num_heads: int):
+    """lambda_k = 2^(k - K/2) * lambda for k = 1 .. K as a float32 numpy array."""
+    import numpy as np
+    out = np.empty(max(int(num_heads), 1), dtype=np.float32)
+    st = load_library().lcn_head_lambdas(float(lam), int(num_heads), out.ctypes.data)
+    if st != OK:
+        raise LcnError(st, "lcn_head_lambdas")
     return out

@@ -15,6 +15,7 @@
 // Without deletion costs it is plain Sinkhorn on K~.
 //
 // Compiled with -ffp-contract=off: the bucket rule needs separate multiply and add.
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -382,6 +383,22 @@ __global__ __launch_bounds__(256) void batched_run_kernel(BatchDev B, int iters,
     }
 }
 
+// c_i = || alpha .* x_i ||_2 (Sec. 6, learnable deletion cost); one thread per
+// point, squares added in fp64 in the order of the dimensions.
+__global__ __launch_bounds__(256) void deletion_cost_kernel(const float *X, long long total, int d, const float *alpha,
+                                                            float *out)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const float *x = X + i * d;
+    double s = 0.0;
+    for (int k = 0; k < d; ++k) {
+        const double t = (double)x[k] * (double)alpha[k];
+        s += t * t;
+    }
+    out[i] = (float)sqrt(s);
+}
+
 struct BatchHandle {
     uint32_t magic;
     BatchDev dev;
@@ -598,6 +615,31 @@ lcn_status lcn_batched_get(lcn_handle hh, double *log_u_dev, double *log_v_dev, 
         BHIPCHK(hipMemcpyAsync(kernel_dev, D.Kt, sizeof(float) * (size_t)D.P * BMAX * BMAX, hipMemcpyDeviceToDevice,
                                h.stream));
     BHIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status lcn_deletion_costs(const float *X, int64_t total, int32_t d, const float *alpha, float *out,
+                              void *hip_stream)
+{
+    if (total < 0 || d < 1) return LCN_ERR_INVALID_ARG;
+    if (total == 0) return LCN_OK;
+    if (!X || !alpha || !out) return LCN_ERR_INVALID_ARG;
+    const long long groups = (total + 255) / 256;
+    if (groups > 0x7FFFFFFFLL) return LCN_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(deletion_cost_kernel, dim3((unsigned)groups), dim3(256), 0, (hipStream_t)hip_stream, X,
+                       (long long)total, d, alpha, out);
+    BHIPCHK(hipGetLastError());
+    return LCN_OK;
+}
+
+lcn_status lcn_head_lambdas(float lambda, int32_t num_heads, float *out_host)
+{
+    if (!out_host || !(lambda > 0.f) || num_heads < 1 || num_heads > 64) return LCN_ERR_INVALID_ARG;
+    for (int k = 1; k <= num_heads; ++k) {
+        const float v = (float)(std::exp2((double)k - 0.5 * (double)num_heads) * (double)lambda);
+        if (!(v > 0.f) || !std::isfinite(v)) return LCN_ERR_INVALID_ARG;
+        out_host[k - 1] = v;
+    }
     return LCN_OK;
 }
 

@@ -24,7 +24,7 @@ def test_header_declares_the_expected_entry_points():
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
                      "lcn_get_factors", "lcn_get_info", "lcn_destroy", "lcn_status_string", "lcn_build_batched",
                      "lcn_batched_results", "lcn_batched_get", "lcn_last_run_timing", "lcn_backward",
-                     "lcn_backward_scratch_bytes", "lcn_plan_rows"):
+                     "lcn_backward_scratch_bytes", "lcn_plan_rows", "lcn_deletion_costs", "lcn_head_lambdas"):
         assert required in names
 
 
@@ -132,6 +132,27 @@ def test_batched_arguments():
     assert call([0, 20], [0, 20], [0.1], d=100) == ERR_INVALID_ARG
     assert call([0, 3], [0, 3], [0.1]) == ERR_INVALID_ARG         # fewer points than landmarks
     assert call([1, 20], [0, 20], [0.1]) == ERR_INVALID_ARG       # offsets must start at 0
+
+
+def test_head_lambdas_host_call():
+    """lcn_head_lambdas runs on the host: lambda_k = 2^(k - K/2) lambda, k = 1 .. K (Sec. 6)."""
+    import oracle
+    import paper_2107_06876_amd as lcn
+    from paper_2107_06876_amd.binding import ERR_INVALID_ARG
+    for lam, K in ((0.05, 1), (0.25, 2), (0.1, 8), (3.0, 5)):
+        np.testing.assert_array_equal(lcn.lcn_head_lambdas(lam, K), oracle.head_lambdas(lam, K))
+    lib = lcn.load_library()
+    buf = np.zeros(64, dtype=np.float32)
+    assert lib.lcn_head_lambdas(0.0, 4, buf.ctypes.data) == ERR_INVALID_ARG
+    assert lib.lcn_head_lambdas(0.1, 0, buf.ctypes.data) == ERR_INVALID_ARG
+    assert lib.lcn_head_lambdas(0.1, 65, buf.ctypes.data) == ERR_INVALID_ARG
+    assert lib.lcn_head_lambdas(0.1, 4, None) == ERR_INVALID_ARG
+    assert lib.lcn_head_lambdas(1e38, 64, buf.ctypes.data) == ERR_INVALID_ARG   # overflows fp32
+    assert lib.lcn_deletion_costs(None, 4, 4, None, None, None) == ERR_INVALID_ARG
+    assert lib.lcn_deletion_costs(ctypes.c_void_p(256), -1, 4, ctypes.c_void_p(256), ctypes.c_void_p(256),
+                                  None) == ERR_INVALID_ARG
+    assert lib.lcn_deletion_costs(ctypes.c_void_p(256), 4, 0, ctypes.c_void_p(256), ctypes.c_void_p(256),
+                                  None) == ERR_INVALID_ARG
 
 
 def test_gpu_entry_points_fail_loudly_without_the_library(monkeypatch, tmp_path):

@@ -73,3 +73,71 @@ def test_config4(mode, bp):
         worst["resid"] = max(worst["resid"], abs(resid[p] - resid_o))
     print("C4", mode, bp, worst, flush=True)
     assert worst["log"] <= 1e-4 and worst["cost"] <= 1e-4 and worst["resid"] <= 1e-5, worst
+
+
+def test_deletion_costs_bitwise():
+    """c_i = || alpha .* x_i ||_2 (Sec. 6): same fp64 operations in the same order on both sides."""
+    import paper_2107_06876_amd as lcn
+    rng = np.random.default_rng(11)
+    for total, d in ((1, 1), (257, 32), (5000, 64), (300, 301)):
+        X = rng.standard_normal((total, d)).astype(np.float32)
+        alpha = rng.uniform(0.5, 1.5, d).astype(np.float32)
+        got = lcn.lcn_deletion_costs(torch.from_numpy(X).cuda(), torch.from_numpy(alpha).cuda()).cpu().numpy()
+        np.testing.assert_array_equal(got, oracle.deletion_costs(X, alpha))
+    empty = lcn.lcn_deletion_costs(torch.empty((0, 8), device="cuda"), torch.ones(8, device="cuda"))
+    assert empty.numel() == 0
+
+
+def test_multi_head_unbalanced():
+    """Multi-head OT with learnable deletion costs (Sec. 6): every (pair, head) is a problem of
+    the batch with lambda_k = 2^(k - K/2) lambda and c = || alpha_k .* x ||_2; the K distances
+    of every pair against the oracle's."""
+    import paper_2107_06876_amd as lcn
+    H = workloads.config4_heads(pairs=40, heads=4)
+    B, K = H.batch, H.heads
+    P = B.num_problems
+    dev = "cuda:0"
+    X = torch.from_numpy(B.X).to(dev)
+    Y = torch.from_numpy(B.Y).to(dev)
+    lam = np.concatenate([lcn.lcn_head_lambdas(float(l0), K) for l0 in H.base_lam])
+    dx = torch.empty(X.shape[0], dtype=torch.float32, device=dev)
+    dy = torch.empty(Y.shape[0], dtype=torch.float32, device=dev)
+    for q in range(P):                                    # one head's rows at a time
+        a = torch.from_numpy(H.alpha[H.head_of[q]]).to(dev)
+        lcn.lcn_deletion_costs(X[B.x_off[q]:B.x_off[q + 1]], a, out=dx[B.x_off[q]:B.x_off[q + 1]])
+        lcn.lcn_deletion_costs(Y[B.y_off[q]:B.y_off[q + 1]], a, out=dy[B.y_off[q]:B.y_off[q + 1]])
+    lm = dict(num_landmarks=B.num_landmarks, kmeans_iters=B.kmeans_iters, seed=B.landmark_seed, ridge=B.ridge)
+    lsh = dict(num_buckets=B.num_buckets, num_rounds=1, kmeans_iters=B.kmeans_iters, seed=B.lsh_seed)
+    h = lcn.lcn_build_batched(X, Y, B.x_off, B.y_off, lam, B.cost, lcn.MODE_LCN, dx, dy, landmarks=lm, lsh=lsh)
+    lcn.sinkhorn_run(h, B.iters)
+    dist, resid = lcn.lcn_batched_results(h)
+    st = {k: v.cpu().numpy() for k, v in lcn.lcn_batched_get(h).items()}
+
+    # the oracle's side: its own lambdas and deletion costs
+    B.lam = np.concatenate([oracle.head_lambdas(float(l0), K) for l0 in H.base_lam])
+    np.testing.assert_array_equal(lam, B.lam)
+    B.del_x = np.concatenate([oracle.deletion_costs(B.X[B.x_off[q]:B.x_off[q + 1]], H.alpha[H.head_of[q]])
+                              for q in range(P)])
+    B.del_y = np.concatenate([oracle.deletion_costs(B.Y[B.y_off[q]:B.y_off[q + 1]], H.alpha[H.head_of[q]])
+                              for q in range(P)])
+    np.testing.assert_array_equal(dx.cpu().numpy(), B.del_x)
+    np.testing.assert_array_equal(dy.cpu().numpy(), B.del_y)
+    worst = dict(log=0.0, cost=0.0, resid=0.0)
+    dist_o = np.empty(P)
+    for q in range(P):
+        Bl, so, dist_o[q], resid_o = _oracle_pair(B, q, "lcn", True)
+        n = int(B.x_off[q + 1] - B.x_off[q])
+        m = int(B.y_off[q + 1] - B.y_off[q])
+        z0 = int(B.x_off[q] + B.y_off[q])
+        assert so.nonpositive == 0
+        np.testing.assert_array_equal(st["landmarks"][q], Bl.landmarks)
+        np.testing.assert_array_equal(st["buckets"][z0:z0 + n + m], Bl.buckets[0])
+        worst["log"] = max(worst["log"], np.abs(st["log_u"][z0:z0 + n + m] - so.log_u).max(),
+                           np.abs(st["log_v"][z0:z0 + n + m] - so.log_v).max())
+        worst["cost"] = max(worst["cost"], abs(dist[q] - dist_o[q]) / abs(dist_o[q]))
+        worst["resid"] = max(worst["resid"], abs(resid[q] - resid_o))
+    print("C4 heads", worst, flush=True)
+    assert worst["log"] <= 1e-4 and worst["cost"] <= 1e-4 and worst["resid"] <= 1e-5, worst
+    # d in R^K per pair: heads of a pair differ (their lambdas do)
+    d_pk = dist.reshape(-1, K)
+    assert np.all(np.ptp(d_pk, axis=1) > 0)

@@ -728,3 +728,36 @@ def test_backward_dense_gives_the_plan():
     E[2, 5] = h
     fd = (solve(C + E)[3] - solve(C - E)[3]) / (2 * h)
     np.testing.assert_allclose(P[2, 5], fd, rtol=2e-5)
+
+
+# ---------------------------------------------------- multi-head / deletion costs --
+
+def test_deletion_costs_special_cases():
+    """Sec. 6, learnable deletion cost: alpha = 1 is the Euclidean norm, a unit
+    alpha picks |x_j|, and the 3-4-5 triangle."""
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((37, 19)).astype(np.float32)
+    alpha = rng.uniform(0.5, 1.5, 19).astype(np.float32)
+    c = oracle.deletion_costs(X, alpha)
+    assert c.dtype == np.float32
+    ref = np.linalg.norm(X.astype(np.float64) * alpha.astype(np.float64), axis=1)
+    np.testing.assert_allclose(c, ref, rtol=1e-7)
+    np.testing.assert_allclose(oracle.deletion_costs(X, np.ones(19, np.float32)),
+                               np.linalg.norm(X.astype(np.float64), axis=1), rtol=1e-7)
+    e = np.zeros(19, np.float32)
+    e[7] = 2.0
+    np.testing.assert_array_equal(oracle.deletion_costs(X, e), np.abs(2.0 * X[:, 7]))
+    np.testing.assert_array_equal(oracle.deletion_costs(np.array([[3.0, 4.0]], np.float32),
+                                                        np.ones(2, np.float32)), [5.0])
+    # homogeneous of degree one in alpha
+    np.testing.assert_allclose(oracle.deletion_costs(X, 2 * alpha), 2 * c, rtol=1e-7)
+
+
+def test_head_lambdas_closed_form():
+    """Sec. 6, multi-head OT: consecutive heads differ by a factor of two and
+    K = 2 gives (lambda, 2 lambda); the geometric mean is sqrt(2) lambda."""
+    np.testing.assert_array_equal(oracle.head_lambdas(0.25, 2), np.array([0.25, 0.5], np.float32))
+    lam8 = oracle.head_lambdas(0.1, 8).astype(np.float64)
+    np.testing.assert_allclose(lam8[1:] / lam8[:-1], 2.0, rtol=1e-6)
+    np.testing.assert_allclose(np.exp(np.log(lam8).mean()), np.sqrt(2.0) * np.float32(0.1), rtol=1e-6)
+    np.testing.assert_allclose(lam8[3], np.float32(0.1), rtol=1e-7)   # k = K/2

@@ -252,5 +252,44 @@ def config4(pairs: int = 1024, d: int = 32, lo: int = 16, hi: int = 64) -> Batch
                  COST_EUCLID, num_landmarks=8, num_buckets=4, iters=50)
 
 
+@dataclasses.dataclass
+class HeadBatch:
+    """Multi-head OT over a ragged batch (Sec. 6): every pair is solved by K
+    heads, each on its own linear map of the pair's node embeddings.  Pair p,
+    head k (k = 0 .. K-1) is problem p*K + k of `batch`, whose lam, del_x and
+    del_y are left for the caller to fill (they are part of the method: the
+    head's lambda_k and the learnable deletion costs)."""
+    batch: Batch
+    heads: int
+    base_lam: np.ndarray     # (pairs,) float32
+    alpha: np.ndarray        # (K, d) float32 deletion weights of each head
+    head_of: np.ndarray      # (P*K,) int32 head index of every problem
+
+
+def config4_heads(pairs: int = 48, heads: int = 4, d: int = 32) -> HeadBatch:
+    """config4's pairs seen through `heads` seeded random linear layers."""
+    base = config4(pairs=pairs, d=d)
+    rng = _rng(4, 2)
+    Wk = rng.standard_normal((heads, d, d)) / np.sqrt(d)
+    alpha = _f32(rng.uniform(0.5, 1.5, size=(heads, d)))
+    Xs, Ys, xo, yo, head_of = [], [], [0], [0], []
+    for p in range(pairs):
+        Xp = base.X[base.x_off[p]:base.x_off[p + 1]].astype(np.float64)
+        Yp = base.Y[base.y_off[p]:base.y_off[p + 1]].astype(np.float64)
+        for k in range(heads):
+            Xs.append(_f32(Xp @ Wk[k]))
+            Ys.append(_f32(Yp @ Wk[k]))
+            xo.append(xo[-1] + len(Xp))
+            yo.append(yo[-1] + len(Yp))
+            head_of.append(k)
+    X, Y = np.concatenate(Xs), np.concatenate(Ys)
+    batch = Batch("C4-heads", X, Y, np.asarray(xo, dtype=np.int64), np.asarray(yo, dtype=np.int64),
+                  np.zeros(pairs * heads, dtype=np.float32), None, None, COST_EUCLID,
+                  num_landmarks=8, num_buckets=4, iters=50)
+    # base lambda chosen so that the sharpest head (k = 1) has config4's lambda
+    base_lam = _f32(base.lam.astype(np.float64) * 2.0 ** (heads / 2.0 - 1.0))
+    return HeadBatch(batch, heads, base_lam, alpha, np.asarray(head_of, dtype=np.int32))
+
+
 def get(index: int, **kw):
     return {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}[index](**kw)
