@@ -90,12 +90,33 @@ def assign(Z, cent):
     return out
 
 
-def kmeans(Z, k, T, seed):
-    """Returns (centroids float32 (k, d), assignment int32 (N,))."""
+def kmeanspp(Z, k, seed):
+    """Indices (int64, k) of the points k-means++ seeding picks (D^2 sampling)."""
+    Z = _f32(Z)
+    idx = np.empty(k, dtype=np.int64)
+    rc = lib().orc_kmeanspp(_p(Z, F), I64(Z.shape[0]), Z.shape[1], k, ctypes.c_uint64(seed), _p(idx, I64))
+    if rc:
+        raise ValueError("kmeanspp: bad arguments")
+    return idx
+
+
+def kmeans(Z, k, T, seed, init="sample"):
+    """Returns (centroids float32 (k, d), assignment int32 (N,)).  init: "sample"
+    (k seeded distinct points), "kmeans++" (D^2 sampling; T may be 0: the sampled
+    points themselves) or an array of k start centroids."""
     Z = _f32(Z)
     cent = np.empty((k, Z.shape[1]), dtype=np.float32)
     asg = np.empty(Z.shape[0], dtype=np.int32)
-    rc = lib().orc_kmeans(_p(Z, F), I64(Z.shape[0]), Z.shape[1], k, T, ctypes.c_uint64(seed), _p(cent, F), _p(asg, I32))
+    if isinstance(init, str) and init == "sample" and T >= 1:
+        rc = lib().orc_kmeans(_p(Z, F), I64(Z.shape[0]), Z.shape[1], k, T, ctypes.c_uint64(seed), _p(cent, F),
+                              _p(asg, I32))
+    else:
+        if isinstance(init, str):
+            idx = {"sample": seeded_indices, "kmeans++": lambda s, N, kk: kmeanspp(Z, kk, s)}[init](seed, Z.shape[0], k)
+            cent[:] = Z[idx]
+        else:
+            cent[:] = _f32(init).reshape(k, Z.shape[1])
+        rc = lib().orc_lloyd(_p(Z, F), I64(Z.shape[0]), Z.shape[1], k, T, _p(cent, F), _p(asg, I32))
     if rc:
         raise ValueError("kmeans: bad arguments")
     return cent, asg
@@ -309,7 +330,8 @@ def hash_rounds(Z, hash_kind, num_buckets, num_rounds, kmeans_iters, seed, proje
 
 
 def build_problem(X, Y, cost, lam, mode, num_landmarks=0, landmark_seed=1, kmeans_iters=10, ridge=0.0,
-                  hash_kind=0, num_buckets=0, num_rounds=0, lsh_seed=101, projections=None) -> Built:
+                  hash_kind=0, num_buckets=0, num_rounds=0, lsh_seed=101, projections=None,
+                  landmark_init="sample", landmark_iters=None) -> Built:
     """The build stage of one path: mode in {"dense", "sparse", "nystrom", "lcn"}."""
     X, Y = _f32(X), _f32(Y)
     n, m = X.shape[0], Y.shape[0]
@@ -319,7 +341,8 @@ def build_problem(X, Y, cost, lam, mode, num_landmarks=0, landmark_seed=1, kmean
     L = U = W = None
     buckets = rowptr = colidx = val = None
     if mode in ("nystrom", "lcn"):
-        L, _ = kmeans(Z, num_landmarks, kmeans_iters, landmark_seed)
+        L, _ = kmeans(Z, num_landmarks, kmeans_iters if landmark_iters is None else landmark_iters, landmark_seed,
+                      init=landmark_init)
         U, W = nystrom(X, Y, L, cost, lam, ridge)
     if mode in ("sparse", "lcn"):
         buckets = hash_rounds(Z, hash_kind, num_buckets, num_rounds, kmeans_iters, lsh_seed, projections)

@@ -146,16 +146,29 @@ void orc_assign(const float *Z, int64_t N, int d, const float *cent, int k, int3
  * it does not depend on summation order.  Outputs: the centroids after T
  * iterations and the assignment made in iteration T (the clusters whose means
  * those centroids are).  Requires |z| < 2^10, N <= 2^20, T >= 1. */
+int orc_lloyd(const float *Z, int64_t N, int d, int k, int T, float *cent, int32_t *assign);
+
 int orc_kmeans(const float *Z, int64_t N, int d, int k, int T, uint64_t seed, float *cent, int32_t *assign)
 {
     if (T < 1 || k < 1 || k > N) return 1;
     int64_t *idx = (int64_t *)malloc(sizeof(int64_t) * (size_t)k);
-    int64_t *sums = (int64_t *)malloc(sizeof(int64_t) * (size_t)k * (size_t)d);
-    int64_t *counts = (int64_t *)malloc(sizeof(int64_t) * (size_t)k);
-    if (!idx || !sums || !counts) return 2;
+    if (!idx) return 2;
     if (orc_seeded_indices(seed, N, k, idx)) return 1;
     for (int c = 0; c < k; ++c)
         memcpy(cent + (int64_t)c * d, Z + idx[c] * d, sizeof(float) * (size_t)d);
+    free(idx);
+    return orc_lloyd(Z, N, d, k, T, cent, assign);
+}
+
+/* T Lloyd iterations from the centroids `cent` holds on entry (T = 0 leaves
+ * them as they are and only makes the assignment). */
+int orc_lloyd(const float *Z, int64_t N, int d, int k, int T, float *cent, int32_t *assign)
+{
+    if (T < 0 || k < 1) return 1;
+    int64_t *sums = (int64_t *)malloc(sizeof(int64_t) * (size_t)k * (size_t)d);
+    int64_t *counts = (int64_t *)malloc(sizeof(int64_t) * (size_t)k);
+    if (!sums || !counts) return 2;
+    if (T == 0) orc_assign(Z, N, d, cent, k, assign);
     for (int it = 0; it < T; ++it) {
         orc_assign(Z, N, d, cent, k, assign);
         memset(sums, 0, sizeof(int64_t) * (size_t)k * (size_t)d);
@@ -173,9 +186,73 @@ int orc_kmeans(const float *Z, int64_t N, int d, int k, int T, uint64_t seed, fl
                     (float)(ldexp((double)sums[(int64_t)c * d + j], -32) / (double)counts[c]);
         }
     }
-    free(idx);
     free(sums);
     free(counts);
+    return 0;
+}
+
+/* k-means++ seeding ("sampling via k-means++", Sec. 4): the first point is
+ * uniform, every further point is drawn with probability proportional to its
+ * squared distance w_i to the nearest point chosen so far.  The paper names the
+ * method only; this build's reading makes the draw exact integer work so that
+ * both sides agree on every index:
+ *   - distances by the fp64 bucket rule (left to right, separate multiply and add);
+ *   - weights q_i = floor(w_i * 2^(38 - e)), with 4 * max_i |z_i|^2 = f * 2^e,
+ *     1/2 <= f < 1 (no distance exceeds that bound, so q_i < 2^39 and the total
+ *     of 2^20 points fits 64 bits); a chosen point has weight 0;
+ *   - step t takes the t-th output r_t of splitmix64(seed): the first index is
+ *     r_0 mod N, later ones the lowest i whose running total q_0 + .. + q_i
+ *     exceeds r_t mod (total);
+ *   - if the total is 0 (every remaining point coincides with a chosen one) the
+ *     lowest index not chosen yet is taken. */
+int orc_kmeanspp(const float *Z, int64_t N, int d, int k, uint64_t seed, int64_t *idx)
+{
+    if (k < 1 || k > N) return 1;
+    double *w = (double *)malloc(sizeof(double) * (size_t)N);
+    char *chosen = (char *)calloc((size_t)N, 1);
+    float *zero = (float *)calloc((size_t)d, sizeof(float));
+    if (!w || !chosen || !zero) return 2;
+    double m2 = 0.0;
+    for (int64_t i = 0; i < N; ++i) {
+        double s = bucket_sqdist(Z + i * d, zero, d);
+        if (s > m2) m2 = s;
+    }
+    int e = 0;
+    (void)frexp(4.0 * m2, &e);
+    const int shift = 38 - e;
+    uint64_t st = seed;
+    for (int t = 0; t < k; ++t) {
+        const uint64_t r = splitmix64(&st);
+        int64_t pick = -1;
+        if (t == 0) {
+            pick = (int64_t)(r % (uint64_t)N);
+        } else {
+            uint64_t total = 0;
+            for (int64_t i = 0; i < N; ++i)
+                if (!chosen[i]) total += (uint64_t)floor(ldexp(w[i], shift));
+            if (total == 0) {
+                for (int64_t i = 0; i < N && pick < 0; ++i)
+                    if (!chosen[i]) pick = i;
+            } else {
+                const uint64_t target = r % total;
+                uint64_t run = 0;
+                for (int64_t i = 0; i < N && pick < 0; ++i) {
+                    if (chosen[i]) continue;
+                    run += (uint64_t)floor(ldexp(w[i], shift));
+                    if (run > target) pick = i;
+                }
+            }
+        }
+        idx[t] = pick;
+        chosen[pick] = 1;
+        for (int64_t i = 0; i < N; ++i) {
+            double s = bucket_sqdist(Z + i * d, Z + pick * d, d);
+            if (t == 0 || s < w[i]) w[i] = s;
+        }
+    }
+    free(w);
+    free(chosen);
+    free(zero);
     return 0;
 }
 

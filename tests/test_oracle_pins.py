@@ -761,3 +761,88 @@ def test_head_lambdas_closed_form():
     np.testing.assert_allclose(lam8[1:] / lam8[:-1], 2.0, rtol=1e-6)
     np.testing.assert_allclose(np.exp(np.log(lam8).mean()), np.sqrt(2.0) * np.float32(0.1), rtol=1e-6)
     np.testing.assert_allclose(lam8[3], np.float32(0.1), rtol=1e-7)   # k = K/2
+
+
+# ------------------------------------------------------------ k-means++ sampling --
+
+def test_kmeanspp_second_pick_follows_squared_distances():
+    """Sec. 4, landmarks sampled via k-means++: given the first point, the second is
+    drawn with probability D^2 / sum D^2.  Four points on a line, 40 000 seeds: the
+    empirical law of (first, second) against the closed form (first uniform)."""
+    Z = np.array([[0.0], [1.0], [3.0], [7.0]], dtype=np.float32)
+    N, S = 4, 40000
+    counts = np.zeros((N, N))
+    for seed in range(S):
+        i, j = oracle.kmeanspp(Z, 2, seed)
+        counts[i, j] += 1
+    D2 = (Z - Z.T) ** 2
+    expect = (D2 / D2.sum(axis=1, keepdims=True)) / N
+    assert np.all(np.diag(counts) == 0)
+    sigma = np.sqrt(expect * (1 - expect) / S)
+    assert np.all(np.abs(counts / S - expect) <= 4.5 * sigma + 1e-12), (counts / S, expect)
+
+
+def test_kmeanspp_structure():
+    """Distinct picks; a copy of a chosen point is never drawn while other points are left;
+    far-apart tight clusters each receive one of k = (number of clusters) picks; scaling
+    the points by a power of two changes nothing (the weights are relative to the largest norm);
+    more picks than distinct points falls back to the lowest unused index."""
+    rng = np.random.default_rng(3)
+    Z = rng.standard_normal((400, 5)).astype(np.float32)
+    for seed in range(5):
+        idx = oracle.kmeanspp(Z, 50, seed)
+        assert len(set(idx.tolist())) == 50 and idx.min() >= 0 and idx.max() < 400
+        np.testing.assert_array_equal(oracle.kmeanspp(4.0 * Z, 50, seed), idx)
+        np.testing.assert_array_equal(oracle.kmeanspp(Z, 20, seed), idx[:20])        # a prefix of the longer run
+    centres = 100.0 * np.eye(6, 5)
+    label = np.arange(300) % 6
+    C = (centres[label] + 0.01 * rng.standard_normal((300, 5))).astype(np.float32)
+    for seed in range(20):
+        assert sorted(label[oracle.kmeanspp(C, 6, seed)].tolist()) == list(range(6))
+    Zd = np.concatenate([Z[:7], Z[:7], Z[:7]])                                       # 7 distinct points, 3 copies each
+    for seed in range(10):
+        idx = oracle.kmeanspp(Zd, 10, seed)
+        assert sorted((idx[:7] % 7).tolist()) == list(range(7))                      # first the 7 distinct ones
+        left = sorted(set(range(21)) - set(idx[:7].tolist()))
+        np.testing.assert_array_equal(idx[7:], left[:3])                             # then lowest unused indices
+    idx = oracle.kmeanspp(np.zeros((5, 3), np.float32), 3, 1)                       # all points equal
+    np.testing.assert_array_equal(idx[1:], sorted(set(range(5)) - {int(idx[0])})[:2])
+
+
+def test_kmeanspp_first_pick_uniform_and_potential():
+    """First pick uniform over the points; the D^2 potential after k-means++ seeding is, on
+    clustered data, far below that of a uniform sample (the reason the paper prefers it)."""
+    Z = np.arange(10, dtype=np.float32).reshape(10, 1)
+    first = np.bincount([int(oracle.kmeanspp(Z, 1, s)[0]) for s in range(20000)], minlength=10) / 20000.0
+    assert np.all(np.abs(first - 0.1) < 4.5 * np.sqrt(0.09 / 20000))
+    rng = np.random.default_rng(8)
+    centres = 10.0 * rng.standard_normal((12, 4))
+    sizes = (2000 * np.arange(1, 13) / 78).astype(int)                               # unbalanced clusters
+    P = np.concatenate([c + 0.1 * rng.standard_normal((s, 4)) for c, s in zip(centres, sizes)]).astype(np.float32)
+
+    def potential(idx):
+        return ((P[:, None, :].astype(np.float64) - P[idx][None].astype(np.float64)) ** 2).sum(-1).min(1).sum()
+
+    pp = np.median([potential(oracle.kmeanspp(P, 12, s)) for s in range(15)])
+    un = np.median([potential(oracle.seeded_indices(s, len(P), 12)) for s in range(15)])
+    assert pp < 0.2 * un, (pp, un)
+
+
+def test_lloyd_from_given_start():
+    """k-means from caller-supplied centroids: the true means of well separated clusters are a
+    fixed point, and the seeded start passed in by hand reproduces the seeded run."""
+    rng = np.random.default_rng(4)
+    centres = 20.0 * np.eye(4, 3)
+    label = np.arange(200) % 4
+    Z = (centres[label] + rng.standard_normal((200, 3))).astype(np.float32)
+    means = np.stack([Z[label == c].astype(np.float64).mean(0) for c in range(4)])
+    cent, asg = oracle.kmeans(Z, 4, 3, 0, init=means.astype(np.float32))
+    np.testing.assert_array_equal(asg, label)
+    np.testing.assert_allclose(cent, means, rtol=0, atol=1e-6)
+    a = oracle.kmeans(Z, 4, 5, 9)
+    b = oracle.kmeans(Z, 4, 5, 9, init=Z[oracle.seeded_indices(9, 200, 4)])
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[1], b[1])
+    c0, a0 = oracle.kmeans(Z, 4, 0, 9, init="kmeans++")
+    np.testing.assert_array_equal(c0, Z[oracle.kmeanspp(Z, 4, 9)])
+    np.testing.assert_array_equal(a0, oracle.assign(Z, c0))
