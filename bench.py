@@ -44,7 +44,8 @@ def cpu_baseline(p, sample_iters: int):
     threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or os.cpu_count()
     t0 = time.perf_counter()
     B = oracle.build_problem(p.X, p.Y, p.cost, p.lam, "lcn", p.num_landmarks, p.landmark_seed, p.kmeans_iters,
-                             p.ridge, 0, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections)
+                             p.ridge, 0, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections,
+                             landmark_init=p.landmark_init, landmark_iters=p.landmark_iters)
     t1 = time.perf_counter()
     st = oracle.sinkhorn(B.op, p.a, p.b, sample_iters)
     t2 = time.perf_counter()
@@ -130,6 +131,9 @@ def main():
     ap.add_argument("--cpu-iters", type=int, default=1000,
                     help="Sinkhorn iterations of the oracle sample (with its build: about 10 s of CPU work at C3)")
     ap.add_argument("--mode", default="lcn", choices=["lcn", "sparse", "nystrom", "dense"])
+    ap.add_argument("--landmarks", default="kmeans", choices=["kmeans", "kmeans++"],
+                    help="kmeans: the configuration's k-means landmarks; kmeans++: landmarks sampled by "
+                         "k-means++ seeding, no Lloyd iterations")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -154,6 +158,10 @@ def main():
     b = torch.from_numpy(p.b).to(dev)
     mode = {"lcn": lcn.MODE_LCN, "sparse": lcn.MODE_SPARSE, "nystrom": lcn.MODE_NYSTROM, "dense": lcn.MODE_DENSE}[args.mode]
     lm = dict(num_landmarks=p.num_landmarks, kmeans_iters=p.kmeans_iters, seed=p.landmark_seed, ridge=p.ridge)
+    if args.landmarks == "kmeans++":
+        p.landmark_init, p.landmark_iters = "kmeans++", 0
+        lm.update(init=lcn.INIT_KMEANSPP, kmeans_iters=0)
+        wl += " landmarks=kmeans++ sampling"
     lsh = dict(hash=lcn.HASH_KMEANS, num_buckets=p.num_buckets, num_rounds=p.num_rounds,
                kmeans_iters=p.kmeans_iters, seed=p.lsh_seed)
     lm = lm if args.mode in ("lcn", "nystrom") else None

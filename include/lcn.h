@@ -59,16 +59,31 @@ typedef enum { LCN_MODE_DENSE = 0, LCN_MODE_SPARSE = 1, LCN_MODE_NYSTROM = 2, LC
 typedef enum { LCN_HASH_KMEANS = 0, LCN_HASH_CROSSPOLYTOPE = 1 } lcn_hash;
 typedef enum { LCN_F32 = 0, LCN_BF16 = 1 } lcn_dtype; /* storage type of X and Y only */
 
-/* Landmarks of the Nystrom part: centroids of Lloyd's k-means on X u Y
- * ("k-means Nystrom", Sec. 4; fixed iteration count, App. "Complexity
- * analysis").  The start is num_landmarks distinct points chosen by a
- * splitmix64-driven partial Fisher-Yates shuffle from `seed`.
- * ridge: A + ridge*I is inverted; 0 is the paper's plain inverse. */
+typedef enum {
+    LCN_INIT_SAMPLE = 0,   /* num_landmarks distinct points by a splitmix64-driven partial Fisher-Yates shuffle */
+    LCN_INIT_KMEANSPP = 1, /* k-means++ seeding: D^2 sampling, see below */
+    LCN_INIT_GIVEN = 2     /* the caller's init_centroids */
+} lcn_landmark_init;
+
+/* Landmarks of the Nystrom part (Sec. 4): Lloyd's k-means on X u Y with a fixed
+ * iteration count (App. "Complexity analysis") from the start `init` names;
+ * kmeans_iters = 0 takes the start itself -- with LCN_INIT_KMEANSPP that is
+ * the paper's "sampling via k-means++" (Sec. 4; App. "Choosing LSH neighbors
+ * and Nystrom landmarks"), with LCN_INIT_SAMPLE uniform sampling.
+ * LCN_INIT_KMEANSPP: first point r_0 mod (n+m); then, with w_i the squared
+ * distance (fp64, dimensions left to right) of point i to the nearest chosen
+ * point and q_i = floor(w_i 2^(38-e)) where 4 max|z|^2 = f 2^e, 1/2 <= f < 1,
+ * the lowest i with q_0 + .. + q_i > r_t mod (sum q); r_t is the t-th output of
+ * splitmix64 from `seed`; if all q are 0 the lowest index not yet chosen.
+ * ridge: A + ridge*I is inverted; 0 is the paper's plain inverse.
+ * lcn_build_batched supports LCN_INIT_SAMPLE with kmeans_iters >= 1 only. */
 typedef struct {
     int32_t num_landmarks; /* l, 1 .. 512, <= n + m */
-    int32_t kmeans_iters;  /* >= 1 */
+    int32_t kmeans_iters;  /* >= 0 */
     uint64_t seed;
     double ridge;          /* >= 0 */
+    int32_t init;          /* lcn_landmark_init */
+    const float *init_centroids; /* device, l x d fp32, read during lcn_build; LCN_INIT_GIVEN only, else NULL */
 } lcn_landmark_params;
 
 /* Locality-sensitive hashing of X u Y (Sec. 3; App. "Choosing LSH neighbors

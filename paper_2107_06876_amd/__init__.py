@@ -6,7 +6,8 @@ package does not load the library; the first call does, and fails loudly if it
 has not been built (python -m paper_2107_06876_amd.build).
 """
 from .binding import (  # noqa: F401
-    COST_COSINE, COST_EUCLID, COST_SQEUCLID, HASH_CROSSPOLYTOPE, HASH_KMEANS, MODE_DENSE, MODE_LCN, MODE_NYSTROM,
+    COST_COSINE, COST_EUCLID, COST_SQEUCLID, HASH_CROSSPOLYTOPE, HASH_KMEANS, INIT_GIVEN, INIT_KMEANSPP, INIT_SAMPLE,
+    MODE_DENSE, MODE_LCN, MODE_NYSTROM,
     MODE_SPARSE, LcnError, LcnHandle, library_path, load_library, lcn_build, lcn_destroy, lcn_get_buckets,
     lcn_get_csr, lcn_get_factors, lcn_get_info, lcn_get_landmarks, lcn_get_scalings, lcn_last_run_timing,
     lcn_set_scalings, lcn_status_string, lcn_workspace_bytes, plan_marginals, sinkhorn_run, transport_cost,

@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "liblcn_hip.so")
 COST_SQEUCLID, COST_EUCLID, COST_COSINE = 0, 1, 2
 MODE_DENSE, MODE_SPARSE, MODE_NYSTROM, MODE_LCN = 0, 1, 2, 3
 HASH_KMEANS, HASH_CROSSPOLYTOPE = 0, 1
+INIT_SAMPLE, INIT_KMEANSPP, INIT_GIVEN = 0, 1, 2
 F32, BF16 = 0, 1
 
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_DEVICE, ERR_STATE, ERR_SINGULAR, ERR_NONPOSITIVE, WARN_NO_SUPPORT = range(8)
@@ -21,7 +22,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_DEVICE, ERR_STATE, ERR_SINGULAR, ERR_NONPOSI
 
 class LandmarkParams(ctypes.Structure):
     _fields_ = [("num_landmarks", ctypes.c_int32), ("kmeans_iters", ctypes.c_int32), ("seed", ctypes.c_uint64),
-                ("ridge", ctypes.c_double)]
+                ("ridge", ctypes.c_double), ("init", ctypes.c_int32), ("init_centroids", ctypes.c_void_p)]
 
 
 class LshParams(ctypes.Structure):
@@ -135,8 +136,14 @@ class LcnHandle:
 def _params(landmarks, lsh, keep):
     lm = None
     if landmarks is not None:
+        given = landmarks.get("init_centroids")
+        if given is not None:
+            given = _dev(given, torch.float32)
+            keep.append(given)
         lm = LandmarkParams(int(landmarks["num_landmarks"]), int(landmarks.get("kmeans_iters", 10)),
-                            int(landmarks.get("seed", 1)), float(landmarks.get("ridge", 0.0)))
+                            int(landmarks.get("seed", 1)), float(landmarks.get("ridge", 0.0)),
+                            int(landmarks.get("init", INIT_GIVEN if given is not None else INIT_SAMPLE)),
+                            None if given is None else given.data_ptr())
     ls = None
     if lsh is not None:
         proj = lsh.get("projections")
@@ -161,7 +168,7 @@ def lcn_workspace_bytes(n, m, d, mode, landmarks=None, lsh=None, nnz_guess=0) ->
 
 
 def lcn_build(X, Y, a, b, lam, cost, mode, landmarks=None, lsh=None, workspace=None, stream=None) -> LcnHandle:
-    """landmarks: dict(num_landmarks, kmeans_iters, seed, ridge); lsh: dict(hash,
+    """landmarks: dict(num_landmarks, kmeans_iters, seed, ridge, init, init_centroids); lsh: dict(hash,
     num_buckets, num_rounds, kmeans_iters, seed, projections).  X, Y: float32 or
     bfloat16 device tensors.  If the workspace (a uint8 device tensor) is
     missing or too small a new one of the size the library asks for is

@@ -489,7 +489,7 @@ lcn_status lcn_build_batched(const float *X, const float *Y, int32_t d, const lc
         return LCN_ERR_INVALID_ARG;
     const bool low_rank = mode == LCN_MODE_NYSTROM || mode == LCN_MODE_LCN;
     const bool hashed = mode == LCN_MODE_SPARSE || mode == LCN_MODE_LCN;
-    if (low_rank && (!lm || lm->num_landmarks < 1 || lm->num_landmarks > BL || lm->kmeans_iters < 1 ||
+    if (low_rank && (!lm || lm->num_landmarks < 1 || lm->num_landmarks > BL || lm->kmeans_iters < 1 || lm->init != LCN_INIT_SAMPLE ||
                      !(lm->ridge >= 0.0)))
         return LCN_ERR_INVALID_ARG;
     if (hashed && (!lsh || lsh->hash != LCN_HASH_KMEANS || lsh->num_buckets < 1 || lsh->num_buckets > BL ||

@@ -56,6 +56,230 @@ hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k
     return hipGetLastError();
 }
 
+// ---------------------------------------------------- k-means++ seeding --
+//
+// Landmarks "sampled via k-means++" (Sec. 4): the first point uniformly, each
+// further one with probability proportional to its squared distance w_i to
+// the nearest point chosen so far.  The draw is integer work so that it has
+// one answer: w_i by the fp64 bucket rule, weight q_i = floor(w_i 2^(38-e))
+// where 4 max|z|^2 = f 2^e (1/2 <= f < 1) bounds every distance, pick = lowest
+// i with q_0 + .. + q_i > r_t mod (sum q), r_t the t-th splitmix64 output.  A
+// chosen point carries w = -1 (weight 0).  If the weights sum to 0 the lowest
+// index not chosen yet is taken.
+//
+// One step = one sweep over the points (distance to the newest landmark,
+// minimum, weights, per-workgroup totals) and one single-workgroup pick.
+
+constexpr int PP_POINTS = 64;   // points per workgroup of the sweep: one wavefront, one point per lane
+constexpr int PP_MAX_GROUPS = 16384;
+
+__device__ inline int kmeanspp_shift(unsigned long long m2_bits)
+{
+    // 4 * m2 = f * 2^e with 1/2 <= f < 1: e = biased exponent - 1020 (m2 is 0 or a normal double)
+    return 38 - ((int)((m2_bits >> 52) & 0x7FF) - 1020);
+}
+
+__device__ inline unsigned long long kmeanspp_weight(double w, int shift)
+{
+    return w > 0.0 ? (unsigned long long)floor(ldexp(w, shift)) : 0ull;
+}
+
+// MODE 0: largest squared norm of a point -> state[0] (bits of a non-negative double order like integers)
+// MODE 1: w = D(z, c);  MODE 2: w = min(w, D(z, c));  both: partial[workgroup] = sum of the weights
+// The wavefront reads its 64 rows in tiles of 32 dimensions (two rows per load instruction, all 32
+// loads of a tile in flight together, the next tile's while this one is summed), turns the tile
+// through LDS, and every lane adds up its own point's terms in dimension order.
+template <int MODE>
+__global__ __launch_bounds__(64) void kmeanspp_sweep_kernel(const float *Z, long long N, int d, const float *c,
+                                                            const int *picks, int t, double *w,
+                                                            unsigned long long *state, unsigned long long *partial)
+{
+    __shared__ float tile[64][33];
+    __shared__ float csh[32];
+    const int lane = threadIdx.x;
+    const int half = lane >> 5, col = lane & 31;
+    const long long i0 = (long long)blockIdx.x * PP_POINTS;
+    // rows past the end repeat the last row (their lanes are dropped at the end)
+    long long rowoff[32];
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+        const long long row = i0 + 2 * q + half;
+        rowoff[q] = (row < N ? row : N - 1) * d;
+    }
+    float v[32];
+    float cv = 0.f;
+    auto fetch = [&](int k0) {
+        const int kc = k0 + col < d ? k0 + col : d - 1;   // columns past the end repeat the last one (not summed)
+#pragma unroll
+        for (int q = 0; q < 32; ++q) v[q] = Z[rowoff[q] + kc];
+        if (MODE != 0) cv = c[k0 + (lane & 31) < d ? k0 + (lane & 31) : d - 1];
+    };
+    fetch(0);
+    double s = 0.0;
+    for (int k0 = 0; k0 < d; k0 += 32) {
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 32; ++q) tile[2 * q + half][col] = v[q];
+        if (lane < 32) csh[lane] = cv;
+        __syncthreads();
+        if (k0 + 32 < d) fetch(k0 + 32);
+        const int kend = d - k0 < 32 ? d - k0 : 32;
+        if (kend == 32) {
+#pragma unroll
+            for (int kk = 0; kk < 32; ++kk) {
+                const double df = (double)tile[lane][kk] - (double)csh[kk];
+                const double sq = df * df;
+                s = s + sq;
+            }
+        } else {
+            for (int kk = 0; kk < kend; ++kk) {
+                const double df = (double)tile[lane][kk] - (double)csh[kk];
+                const double sq = df * df;
+                s = s + sq;
+            }
+        }
+    }
+    const long long i = i0 + lane;
+    unsigned long long r = 0;
+    if (MODE == 0) {
+        r = i < N ? (unsigned long long)__double_as_longlong(s) : 0ull;
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long other = __shfl_xor(r, o, 64);
+            r = other > r ? other : r;
+        }
+        if (lane == 0) atomicMax(&state[0], r);
+    } else {
+        if (i < N) {
+            double wn = s;
+            if (MODE == 2) wn = fmin(w[i], s);
+            if (i == (long long)picks[t]) wn = -1.0;
+            w[i] = wn;
+            r = kmeanspp_weight(wn, kmeanspp_shift(state[0]));
+        }
+        for (int o = 32; o > 0; o >>= 1) r += __shfl_xor(r, o, 64);
+        if (lane == 0) partial[blockIdx.x] = r;
+    }
+}
+
+// One workgroup of 1024 threads: the t-th pick from the per-workgroup totals of the sweep, its
+// index into picks[t], its row into cent[t].  nb <= 16384 totals, sixteen per thread.
+__global__ __launch_bounds__(1024) void kmeanspp_pick_kernel(const float *Z, long long N, int d, const double *w,
+                                                             const unsigned long long *state,
+                                                             const unsigned long long *partial, int nb,
+                                                             const unsigned long long *rnd, int t, int *picks,
+                                                             float *cent)
+{
+    __shared__ unsigned long long scan[1024];
+    __shared__ long long found;     // index of the pick
+    __shared__ long long blk;       // workgroup of the sweep that holds it
+    __shared__ unsigned long long rem_sh;
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        found = -1;
+        blk = -1;
+    }
+    if (t == 0) {
+        __syncthreads();
+        if (tid == 0) found = (long long)(rnd[0] % (unsigned long long)N);
+        __syncthreads();
+    } else {
+        unsigned long long v[16], local = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int b = tid * 16 + q;
+            v[q] = b < nb ? partial[b] : 0ull;
+            local += v[q];
+        }
+        scan[tid] = local;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {   // inclusive scan
+            const unsigned long long add = tid >= o ? scan[tid - o] : 0ull;
+            __syncthreads();
+            scan[tid] += add;
+            __syncthreads();
+        }
+        const unsigned long long total = scan[1023];
+        if (total == 0) {
+            // every point left coincides with a chosen one: lowest index not chosen yet
+            long long best = N;
+            for (long long i = tid; i < N; i += 1024)
+                if (w[i] >= 0.0 && i < best) best = i;
+            __syncthreads();
+            scan[tid] = (unsigned long long)best;
+            __syncthreads();
+            for (int o = 512; o > 0; o >>= 1) {
+                if (tid < o && scan[tid + o] < scan[tid]) scan[tid] = scan[tid + o];
+                __syncthreads();
+            }
+            if (tid == 0) found = (long long)scan[0];
+            __syncthreads();
+        } else {
+            const unsigned long long target = rnd[t] % total;
+            unsigned long long run = scan[tid] - local;   // total of the workgroups before this thread's sixteen
+            if (local > 0 && run <= target && target < scan[tid]) {
+                bool done = false;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    if (!done && target < run + v[q]) {
+                        blk = tid * 16 + q;
+                        rem_sh = target - run;
+                        done = true;
+                    }
+                    run += v[q];
+                }
+            }
+            __syncthreads();
+            const long long base = blk * PP_POINTS;
+            const unsigned long long rem = rem_sh;
+            const int shift = kmeanspp_shift(state[0]);
+            unsigned long long q = 0;
+            if (tid < PP_POINTS && base + tid < N) q = kmeanspp_weight(w[base + tid], shift);
+            __syncthreads();
+            scan[tid] = q;
+            __syncthreads();
+            for (int o = 1; o < PP_POINTS; o <<= 1) {
+                const unsigned long long add = (tid >= o && tid < PP_POINTS) ? scan[tid - o] : 0ull;
+                __syncthreads();
+                if (tid < PP_POINTS) scan[tid] += add;
+                __syncthreads();
+            }
+            if (tid < PP_POINTS && q > 0 && scan[tid] - q <= rem && rem < scan[tid]) found = base + tid;
+            __syncthreads();
+        }
+    }
+    const long long pick = found;
+    if (pick < 0 || pick >= N) return;   // cannot happen; leaves picks[t] untouched rather than reading out of range
+    if (tid == 0) picks[t] = (int)pick;
+    for (int j = tid; j < d; j += 1024) cent[(long long)t * d + j] = Z[pick * d + j];
+}
+
+// k points of Z by k-means++ seeding into cent (k x d); rnd: k splitmix64 outputs (device);
+// w: N doubles, partial: ceil(N / 64) totals, picks: k ints, state: one 64-bit word.
+hipError_t launch_kmeanspp(const float *Z, long long N, int d, int k, const unsigned long long *rnd, double *w,
+                           unsigned long long *partial, int *picks, unsigned long long *state, float *cent,
+                           hipStream_t s)
+{
+    const int nb = (int)((N + PP_POINTS - 1) / PP_POINTS);
+    if (nb > PP_MAX_GROUPS || k > N) return hipErrorInvalidValue;
+    hipError_t e = hipMemsetAsync(state, 0, sizeof(unsigned long long), s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kmeanspp_sweep_kernel<0>, dim3(nb), dim3(64), 0, s, Z, N, d, (const float *)nullptr,
+                       (const int *)nullptr, 0, (double *)nullptr, state, (unsigned long long *)nullptr);
+    for (int t = 0; t < k; ++t) {
+        hipLaunchKernelGGL(kmeanspp_pick_kernel, dim3(1), dim3(1024), 0, s, Z, N, d, (const double *)w,
+                           (const unsigned long long *)state, (const unsigned long long *)partial, nb, rnd, t, picks,
+                           cent);
+        if (t + 1 == k) break;
+        if (t == 0)
+            hipLaunchKernelGGL(kmeanspp_sweep_kernel<1>, dim3(nb), dim3(64), 0, s, Z, N, d,
+                               (const float *)(cent + (long long)t * d), (const int *)picks, t, w, state, partial);
+        else
+            hipLaunchKernelGGL(kmeanspp_sweep_kernel<2>, dim3(nb), dim3(64), 0, s, Z, N, d,
+                               (const float *)(cent + (long long)t * d), (const int *)picks, t, w, state, partial);
+    }
+    return hipGetLastError();
+}
+
 // ------------------------------------------------- exact-rule assignment --
 //
 // A block takes 64 points and walks over all candidates (centroids, or

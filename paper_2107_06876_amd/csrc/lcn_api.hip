@@ -74,6 +74,7 @@ struct Scratch {  // build-only buffers
     float *cn;
     unsigned *cmax_bits;
     int *flagged, *nflagged, *pairs;
+    unsigned long long *pp_state;  // k-means++: bits of the largest squared norm
     char *zt, *ct;  // bf16 planes of the points and of the centroids (assignment filter)
     int zplanes;
 };
@@ -107,7 +108,8 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.ct = bump.take<char>(2 * split_plane_bytes(kmax, h.d));
     sc.cmax_bits = bump.take<unsigned>(4);
     sc.nflagged = bump.take<int>(4);
-    sc.flagged = bump.take<int>((size_t)N);
+    sc.pp_state = bump.take<unsigned long long>(4);
+    sc.flagged = bump.take<int>((size_t)N + 8);  // also the k-means++ sweep's 64-bit totals, one per 64 points
     sc.pairs = bump.take<int>(3 * (size_t)N);
     h.bucket = bump.take<int32_t>((size_t)(h.R > 0 ? h.R : 1) * N);
 
@@ -174,8 +176,10 @@ lcn_status check_params(long long n, long long m, int d, int dtype, float lambda
     if (uses_landmarks(mode)) {
         if (!lm) return LCN_ERR_INVALID_ARG;
         if (lm->num_landmarks < 1 || lm->num_landmarks > 512 || lm->num_landmarks > n + m) return LCN_ERR_INVALID_ARG;
-        if (lm->kmeans_iters < 1) return LCN_ERR_INVALID_ARG;
+        if (lm->kmeans_iters < 0) return LCN_ERR_INVALID_ARG;
         if (!(lm->ridge >= 0.0)) return LCN_ERR_INVALID_ARG;
+        if (lm->init < LCN_INIT_SAMPLE || lm->init > LCN_INIT_GIVEN) return LCN_ERR_INVALID_ARG;
+        if ((lm->init == LCN_INIT_GIVEN) != (lm->init_centroids != nullptr)) return LCN_ERR_INVALID_ARG;
         kmeans = true;
     }
     if (uses_lsh(mode)) {
@@ -229,13 +233,30 @@ void fill_shape(Handle &h, long long n, long long m, int d, int mode, const lcn_
         }                                    \
     } while (0)
 
-lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float *cent, int32_t *assign)
+// T Lloyd iterations on Z from the start `init` names (LCN_INIT_*): centroids into cent, the last
+// iteration's assignment into assign (untouched if T == 0).
+lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float *cent, int32_t *assign,
+                      int init = LCN_INIT_SAMPLE, const float *given = nullptr)
 {
     const long long N = h.n + h.m;
-    std::vector<long long> idx = seeded_indices(seed, N, k);
-    HIPCHK(hipMemcpyAsync(sc.idx, idx.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
-    HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
-    HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
+    if (init == LCN_INIT_GIVEN) {
+        HIPCHK(hipMemcpyAsync(cent, given, sizeof(float) * (size_t)k * h.d, hipMemcpyDeviceToDevice, h.stream));
+    } else if (init == LCN_INIT_KMEANSPP) {
+        std::vector<unsigned long long> rnd((size_t)k);
+        uint64_t st = seed;
+        for (int t = 0; t < k; ++t) rnd[(size_t)t] = splitmix64(st);
+        HIPCHK(hipMemcpyAsync(sc.idx, rnd.data(), sizeof(unsigned long long) * (size_t)k, hipMemcpyHostToDevice,
+                              h.stream));
+        HIPCHK(hipStreamSynchronize(h.stream));  // rnd is a local host vector
+        // the assignment's buffers are free until the first Lloyd iteration
+        HIPCHK(launch_kmeanspp(h.Z, N, h.d, k, (const unsigned long long *)sc.idx, (double *)sc.pairs,
+                               (unsigned long long *)sc.flagged, sc.order, sc.pp_state, cent, h.stream));
+    } else {
+        std::vector<long long> idx = seeded_indices(seed, N, k);
+        HIPCHK(hipMemcpyAsync(sc.idx, idx.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
+        HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
+        HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
+    }
     HIPCHK(hipMemsetAsync(sc.cmax_bits, 0, sizeof(unsigned), h.stream));
     HIPCHK(hipMemsetAsync(sc.nflagged, 0, 2 * sizeof(int), h.stream));
     HIPCHK(hipMemsetAsync(sc.counts2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
@@ -381,7 +402,7 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
 
     // landmarks: centroids of k-means on X u Y (Sec. 4)
     if (h.l > 0) {
-        st = run_kmeans(h, sc, h.l, lm->kmeans_iters, lm->seed, h.L, sc.assign);
+        st = run_kmeans(h, sc, h.l, lm->kmeans_iters, lm->seed, h.L, sc.assign, lm->init, lm->init_centroids);
         if (st != LCN_OK) return st;
     }
     // hash rounds (Sec. 3)

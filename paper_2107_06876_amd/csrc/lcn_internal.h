@@ -53,6 +53,9 @@ struct Handle;
 hipError_t launch_convert(const void *X, long long n, const void *Y, long long m, int d, int dtype, float *Z,
                           unsigned *range_flag, hipStream_t s);
 hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k, float *out, hipStream_t s);
+hipError_t launch_kmeanspp(const float *Z, long long N, int d, int k, const unsigned long long *rnd, double *w,
+                           unsigned long long *partial, int *picks, unsigned long long *state, float *cent,
+                           hipStream_t s);
 // exact rule for all points (list == nullptr) or for the listed ones
 hipError_t launch_assign_kmeans(const float *Z, long long N, int d, const float *cent, int k, int32_t *out,
                                 const int *list, const int *list_count, hipStream_t s);

@@ -28,7 +28,8 @@ TOL_RESID = 1e-5
 
 def oracle_run(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, iters=None):
     B = oracle.build_problem(p.X, p.Y, p.cost, p.lam, mode, p.num_landmarks, p.landmark_seed, p.kmeans_iters, p.ridge,
-                             hash_kind, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections)
+                             hash_kind, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections,
+                             landmark_init=p.landmark_init, landmark_iters=p.landmark_iters)
     st = oracle.sinkhorn(B.op, p.a, p.b, p.iters if iters is None else iters)
     r, c, dist, resid = oracle.marginals(B.op, p.a, p.b, p.lam, st)
     return B, st, r, c, dist, resid
@@ -40,7 +41,12 @@ def gpu_build(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, 
     Y = torch.from_numpy(p.Y).to(device).to(dt)
     a = torch.from_numpy(p.a).to(device)
     b = torch.from_numpy(p.b).to(device)
-    lm = dict(num_landmarks=p.num_landmarks, kmeans_iters=p.kmeans_iters, seed=p.landmark_seed, ridge=p.ridge)
+    lm = dict(num_landmarks=p.num_landmarks, seed=p.landmark_seed, ridge=p.ridge,
+              kmeans_iters=p.kmeans_iters if p.landmark_iters is None else p.landmark_iters)
+    if isinstance(p.landmark_init, str):
+        lm["init"] = {"sample": lcn.INIT_SAMPLE, "kmeans++": lcn.INIT_KMEANSPP}[p.landmark_init]
+    else:
+        lm["init_centroids"] = torch.from_numpy(np.ascontiguousarray(p.landmark_init, dtype=np.float32)).to(device)
     lsh = dict(hash=hash_kind, num_buckets=p.num_buckets, num_rounds=p.num_rounds, kmeans_iters=p.kmeans_iters,
                seed=p.lsh_seed)
     if hash_kind == workloads.HASH_CROSSPOLYTOPE:

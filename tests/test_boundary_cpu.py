@@ -79,7 +79,13 @@ def test_invalid_arguments_are_rejected_before_any_device_work():
     assert build(n=1 << 20, m=1 << 20) == ERR_INVALID_ARG  # k-means needs n + m <= 2^20
     lm_bad = LandmarkParams(1000, 10, 1, 0.0)
     assert build(lm=ctypes.byref(lm_bad)) == ERR_INVALID_ARG
-    lm_bad = LandmarkParams(8, 0, 1, 0.0)
+    lm_bad = LandmarkParams(8, -1, 1, 0.0)
+    assert build(lm=ctypes.byref(lm_bad)) == ERR_INVALID_ARG
+    lm_bad = LandmarkParams(8, 10, 1, 0.0, 3, None)         # unknown start
+    assert build(lm=ctypes.byref(lm_bad)) == ERR_INVALID_ARG
+    lm_bad = LandmarkParams(8, 10, 1, 0.0, 2, None)         # LCN_INIT_GIVEN without centroids
+    assert build(lm=ctypes.byref(lm_bad)) == ERR_INVALID_ARG
+    lm_bad = LandmarkParams(8, 10, 1, 0.0, 1, 256 * 1024)   # centroids given although the start is not GIVEN
     assert build(lm=ctypes.byref(lm_bad)) == ERR_INVALID_ARG
     lm_bad = LandmarkParams(8, 10, 1, -1.0)
     assert build(lm=ctypes.byref(lm_bad)) == ERR_INVALID_ARG

@@ -177,3 +177,55 @@ def test_config2_full_size_dense_and_sparse():
     print("C2 full lcn", out, flush=True)
     out = compare(p, "dense", iters=4)
     print("C2 full dense", out, flush=True)
+
+
+@pytest.mark.parametrize("iters_l", [0, 3])
+def test_landmarks_by_kmeanspp_sampling(iters_l):
+    """Landmarks sampled via k-means++ (Sec. 4; the paper's choice for word embeddings), alone
+    (0 Lloyd iterations) and as the start of k-means: same points picked on both sides, then
+    the usual parity.  Sizes leave ragged tails in the sweep (N = 6000 = 23.4 workgroups of
+    256 points, d = 300 = 9.4 chunks of 32)."""
+    from parity import compare
+    p = workloads.config3(n=3000, landmarks=96, buckets=20, iters=40)
+    p.landmark_init, p.landmark_iters = "kmeans++", iters_l
+    out = compare(p, "lcn")
+    print("C3r kmeans++", iters_l, out, flush=True)
+    p = workloads.config1(n=700, d=9)
+    p.landmark_init, p.landmark_iters = "kmeans++", iters_l
+    out = compare(p, "nystrom")
+    print("C1 kmeans++", iters_l, out, flush=True)
+
+
+def test_kmeanspp_with_repeated_points():
+    """More landmarks than distinct points on one side of the draw: once every remaining
+    point coincides with a chosen one the lowest unused index is taken.  Checked on the
+    picked landmarks only (A is singular by construction, so the build reports that)."""
+    import torch
+    import oracle
+    import paper_2107_06876_amd as lcn
+    rng = np.random.default_rng(2)
+    base = rng.standard_normal((9, 7)).astype(np.float32)
+    X = np.concatenate([base, base, base[:4]])             # 22 points, 9 distinct
+    Y = np.concatenate([base[::-1], base[:3]])             # 12 points
+    Z = np.concatenate([X, Y])
+    for seed in (1, 2, 3):
+        want = Z[oracle.kmeanspp(Z, 12, seed)]
+        a = torch.full((len(X),), 1.0 / len(X), device="cuda")
+        b = torch.full((len(Y),), 1.0 / len(Y), device="cuda")
+        lm = dict(num_landmarks=12, kmeans_iters=0, seed=seed, init=lcn.INIT_KMEANSPP, ridge=1e-3)
+        h = lcn.lcn_build(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda(), a, b, 1.0, lcn.COST_SQEUCLID,
+                          lcn.MODE_NYSTROM, landmarks=lm)
+        np.testing.assert_array_equal(lcn.lcn_get_landmarks(h).cpu().numpy(), want)
+        lcn.lcn_destroy(h)
+
+
+def test_landmarks_from_given_start():
+    """Caller-supplied start centroids for the landmark k-means."""
+    from parity import compare
+    p = workloads.config1(n=900, d=16)
+    rng = np.random.default_rng(9)
+    half = p.num_landmarks // 2
+    start = np.concatenate([p.X[:half], p.Y[:p.num_landmarks - half]])
+    p.landmark_init = (start + 0.05 * rng.standard_normal(start.shape)).astype(np.float32)
+    out = compare(p, "lcn")
+    print("C1 given start", out, flush=True)

@@ -49,6 +49,10 @@ class Problem:
     bf16_inputs: bool = False
     # cross-polytope projections, (rounds, d, buckets/2) float32
     projections: Optional[np.ndarray] = None
+    # start of the landmark k-means: "sample", "kmeans++" or an (l, d) float32 array; its
+    # iteration count if it differs from kmeans_iters (0: the start itself is the landmark set)
+    landmark_init: object = "sample"
+    landmark_iters: Optional[int] = None
 
     @property
     def n(self):
