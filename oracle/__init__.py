@@ -316,14 +316,60 @@ class Built:
     extras: dict = field(default_factory=dict)
 
 
-def hash_rounds(Z, hash_kind, num_buckets, num_rounds, kmeans_iters, seed, projections=None):
+def hierarchical_kmeans(Z, branching, T, seed):
+    """Hierarchical k-means hashing (App. "Choosing LSH neighbors and Nystrom
+    landmarks": used instead of flat k-means for large inputs).  Level 0 is
+    k-means with branching[0] clusters on all points; level j >= 1 runs a
+    separate k-means with branching[j] clusters inside every cluster of level
+    j-1 (on its members in index order; with fewer members than branching[j],
+    one cluster per member).  bucket = parent * branching[j] + child.  Seeds
+    (this build's reading): level 0 uses `seed`, cluster `parent` of level j uses
+    seed + j * 2^32 + parent.  Returns int32 bucket ids < prod(branching)."""
+    Z = _f32(Z)
+    ids = np.zeros(Z.shape[0], dtype=np.int64)
+    parents = 1
+    for level, b in enumerate(branching):
+        new = np.empty_like(ids)
+        for parent in range(parents):
+            members = np.flatnonzero(ids == parent)
+            if members.size == 0:
+                continue
+            k = min(int(b), members.size)
+            s = seed if level == 0 else seed + (level << 32) + parent
+            _, asg = kmeans(Z[members], k, T, s)
+            new[members] = parent * int(b) + asg
+        ids = new
+        parents *= int(b)
+    return ids.astype(np.int32)
+
+
+def crosspolytope_and(Z, projections, b):
+    """AND construction (App. "Choosing LSH neighbors and Nystrom landmarks"):
+    a band of r cross-polytope hashes matches only if all r do, i.e. the band's
+    bucket is the tuple (h_1 .. h_r), numbered h_1 * b^(r-1) + .. + h_r.
+    projections: (r, d, b/2)."""
+    out = np.zeros(Z.shape[0], dtype=np.int64)
+    for j in range(projections.shape[0]):
+        out = out * b + crosspolytope(Z, projections[j], b)
+    return out.astype(np.int32)
+
+
+def hash_rounds(Z, hash_kind, num_buckets, num_rounds, kmeans_iters, seed, projections=None, branching=None,
+                and_width=1):
     """Bucket ids of every point of Z = [X; Y] for each hash round (Sec. 3).
-    Round r of k-means LSH is a fresh k-means run seeded with seed + r; round
-    r of cross-polytope LSH uses projections[r]."""
+    Round r of k-means LSH is a fresh (hierarchical, if `branching` is given)
+    k-means run seeded with seed + r; round r of cross-polytope LSH uses
+    projections[r] (with the AND construction projections[r*w : (r+1)*w] and
+    num_buckets is the bucket count of ONE hash)."""
     out = np.empty((num_rounds, Z.shape[0]), dtype=np.int32)
     for r in range(num_rounds):
         if hash_kind == 0:
-            _, out[r] = kmeans(Z, num_buckets, kmeans_iters, seed + r)
+            if branching:
+                out[r] = hierarchical_kmeans(Z, branching, kmeans_iters, seed + r)
+            else:
+                _, out[r] = kmeans(Z, num_buckets, kmeans_iters, seed + r)
+        elif and_width > 1:
+            out[r] = crosspolytope_and(Z, projections[r * and_width:(r + 1) * and_width], num_buckets)
         else:
             out[r] = crosspolytope(Z, projections[r], num_buckets)
     return out
@@ -331,7 +377,7 @@ def hash_rounds(Z, hash_kind, num_buckets, num_rounds, kmeans_iters, seed, proje
 
 def build_problem(X, Y, cost, lam, mode, num_landmarks=0, landmark_seed=1, kmeans_iters=10, ridge=0.0,
                   hash_kind=0, num_buckets=0, num_rounds=0, lsh_seed=101, projections=None,
-                  landmark_init="sample", landmark_iters=None) -> Built:
+                  landmark_init="sample", landmark_iters=None, branching=None, and_width=1) -> Built:
     """The build stage of one path: mode in {"dense", "sparse", "nystrom", "lcn"}."""
     X, Y = _f32(X), _f32(Y)
     n, m = X.shape[0], Y.shape[0]
@@ -345,7 +391,8 @@ def build_problem(X, Y, cost, lam, mode, num_landmarks=0, landmark_seed=1, kmean
                       init=landmark_init)
         U, W = nystrom(X, Y, L, cost, lam, ridge)
     if mode in ("sparse", "lcn"):
-        buckets = hash_rounds(Z, hash_kind, num_buckets, num_rounds, kmeans_iters, lsh_seed, projections)
+        buckets = hash_rounds(Z, hash_kind, num_buckets, num_rounds, kmeans_iters, lsh_seed, projections,
+                              branching=branching, and_width=and_width)
         rowptr, colidx = pattern(buckets, n, m)
         val = pattern_values(X, Y, cost, lam, rowptr, colidx, U, W)
     return Built(mode, Operator(n, m, U=U, W=W, rowptr=rowptr, colidx=colidx, val=val), L, buckets)

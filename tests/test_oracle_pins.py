@@ -846,3 +846,72 @@ def test_lloyd_from_given_start():
     c0, a0 = oracle.kmeans(Z, 4, 0, 9, init="kmeans++")
     np.testing.assert_array_equal(c0, Z[oracle.kmeanspp(Z, 4, 9)])
     np.testing.assert_array_equal(a0, oracle.assign(Z, c0))
+
+
+# ----------------------------------------- hierarchical k-means, AND construction --
+
+def test_hierarchical_kmeans_structure():
+    """App. "Choosing LSH neighbors and Nystrom landmarks" (hierarchical k-means): one level is flat
+    k-means; a trailing branching factor 1 changes nothing; the upper level of a two-level hash IS
+    the flat hash with the same seed; every lower-level run only sees its parent's members."""
+    rng = np.random.default_rng(12)
+    Z = rng.standard_normal((600, 6)).astype(np.float32)
+    _, flat = oracle.kmeans(Z, 7, 5, 33)
+    np.testing.assert_array_equal(oracle.hierarchical_kmeans(Z, [7], 5, 33), flat)
+    np.testing.assert_array_equal(oracle.hierarchical_kmeans(Z, [7, 1], 5, 33), flat)
+    two = oracle.hierarchical_kmeans(Z, [7, 4], 5, 33)
+    np.testing.assert_array_equal(two // 4, flat)
+    assert two.min() >= 0 and two.max() < 28
+    three = oracle.hierarchical_kmeans(Z, [3, 2, 4], 5, 33)
+    np.testing.assert_array_equal(three // 4, oracle.hierarchical_kmeans(Z, [3, 2], 5, 33))
+    # a parent with fewer members than children: one bucket per member, ids below the branching factor
+    tiny = np.concatenate([[[0, 0], [1, 0], [0, 1]], 100 + rng.standard_normal((50, 2))]).astype(np.float32)
+    h = oracle.hierarchical_kmeans(tiny, [2, 5], 10, 1)
+    lone = h[:3]
+    assert len(set(lone.tolist())) == 3 and len(set((lone // 5).tolist())) == 1
+    assert set((h[3:] // 5).tolist()) == {1 - int(lone[0] // 5)}
+
+
+def test_hierarchical_kmeans_fixed_point():
+    """Run to convergence, every point is nearer (or as near) to the mean of its own bucket than to
+    the mean of any sibling bucket -- Lloyd's fixed point, inside every parent."""
+    rng = np.random.default_rng(13)
+    centres = 6.0 * rng.standard_normal((12, 3))
+    Z = (centres[rng.integers(0, 12, 900)] + 0.5 * rng.standard_normal((900, 3))).astype(np.float32)
+    b1, b2 = 4, 3
+    h = oracle.hierarchical_kmeans(Z, [b1, b2], 200, 5)
+    Zd = Z.astype(np.float64)
+    for parent in range(b1):
+        kids = [c for c in range(parent * b2, (parent + 1) * b2) if np.any(h == c)]
+        means = np.stack([Zd[h == c].mean(0) for c in kids])
+        mem = np.flatnonzero(h // b2 == parent)
+        D = ((Zd[mem][:, None, :] - means[None]) ** 2).sum(-1)
+        own = np.array([kids.index(c) for c in h[mem]])
+        assert np.all(D[np.arange(len(mem)), own] <= D.min(1) + 1e-9)
+
+
+def test_crosspolytope_and_construction():
+    """AND construction: two points share a band's bucket iff all r hashes of the band agree; one
+    hash is the plain cross-polytope hash."""
+    rng = np.random.default_rng(14)
+    Z = rng.standard_normal((500, 10)).astype(np.float32)
+    P = rng.standard_normal((3, 10, 4)).astype(np.float32)
+    b = 8
+    hs = [oracle.crosspolytope(Z, P[j], b) for j in range(3)]
+    np.testing.assert_array_equal(oracle.crosspolytope_and(Z, P[:1], b), hs[0])
+    band = oracle.crosspolytope_and(Z, P, b)
+    assert band.max() < b ** 3
+    same = band[:, None] == band[None, :]
+    allsame = np.ones_like(same)
+    for hj in hs:
+        allsame &= hj[:, None] == hj[None, :]
+    np.testing.assert_array_equal(same, allsame)
+    # fewer neighbours than a single hash: the pattern of the band is the intersection
+    n = 250
+    B1 = oracle.hash_rounds(Z, 1, b, 1, 0, 0, projections=P[:1])
+    B3 = oracle.hash_rounds(Z, 1, b, 1, 0, 0, projections=P, and_width=3)
+    r1, c1 = oracle.pattern(B1, n, n)
+    r3, c3 = oracle.pattern(B3, n, n)
+    s1 = {(i, j) for i in range(n) for j in c1[r1[i]:r1[i + 1]]}
+    s3 = {(i, j) for i in range(n) for j in c3[r3[i]:r3[i + 1]]}
+    assert s3 <= s1 and len(s3) < len(s1)
