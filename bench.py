@@ -45,7 +45,7 @@ def cpu_baseline(p, sample_iters: int):
     t0 = time.perf_counter()
     B = oracle.build_problem(p.X, p.Y, p.cost, p.lam, "lcn", p.num_landmarks, p.landmark_seed, p.kmeans_iters,
                              p.ridge, 0, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections,
-                             landmark_init=p.landmark_init, landmark_iters=p.landmark_iters)
+                             landmark_init=p.landmark_init, landmark_iters=p.landmark_iters, branching=p.branching)
     t1 = time.perf_counter()
     st = oracle.sinkhorn(B.op, p.a, p.b, sample_iters)
     t2 = time.perf_counter()
@@ -134,6 +134,9 @@ def main():
     ap.add_argument("--landmarks", default="kmeans", choices=["kmeans", "kmeans++"],
                     help="kmeans: the configuration's k-means landmarks; kmeans++: landmarks sampled by "
                          "k-means++ seeding, no Lloyd iterations")
+    ap.add_argument("--branching", default="",
+                    help="hierarchical k-means hashing: comma-separated factors whose product is the "
+                         "configuration's bucket count, e.g. 32,32 (default: flat k-means)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -164,6 +167,10 @@ def main():
         wl += " landmarks=kmeans++ sampling"
     lsh = dict(hash=lcn.HASH_KMEANS, num_buckets=p.num_buckets, num_rounds=p.num_rounds,
                kmeans_iters=p.kmeans_iters, seed=p.lsh_seed)
+    if args.branching:
+        p.branching = tuple(int(x) for x in args.branching.split(","))
+        lsh["branching"] = p.branching
+        wl += " hierarchical k-means " + "x".join(str(x) for x in p.branching)
     lm = lm if args.mode in ("lcn", "nystrom") else None
     lsh = lsh if args.mode in ("lcn", "sparse") else None
 

@@ -91,18 +91,31 @@ typedef struct {
  * in at least one of num_rounds independent hash rounds (OR construction with
  * one hash per band, App. "Complexity analysis").
  *   LCN_HASH_KMEANS: round r = a k-means run with num_buckets clusters and
- *     seed + r; bucket = cluster.
+ *     seed + r; bucket = cluster.  With branching[0] > 0 the run is hierarchical
+ *     (used for large inputs): up to three levels whose factors multiply to
+ *     num_buckets; level 0 is a k-means with branching[0] clusters on all points,
+ *     level j >= 1 runs inside every cluster of level j-1 its own k-means with
+ *     branching[j] <= 32 clusters on that cluster's members (in index order;
+ *     with fewer members, one cluster per member) seeded with
+ *     seed + r + j * 2^32 + parent; bucket = parent * branching[j] + child.
  *   LCN_HASH_CROSSPOLYTOPE: round r = argmax([x^T R_r || -x^T R_r]) with
  *     R_r = projections + r*d*(num_buckets/2), a d x num_buckets/2 row-major
  *     device matrix supplied by the caller; num_buckets must be even.
+ *     AND construction (and_width = w > 1): a round is a band of w hashes that
+ *     matches only if all w do; hash j of round r uses matrix r*w + j, the
+ *     band's bucket is h_0 * b^(w-1) + .. + h_(w-1) with b = num_buckets, and
+ *     b^w <= 4096.  The paper advises against it for k-means hashing; it is
+ *     rejected there.
  * Ties go to the lowest bucket index. */
 typedef struct {
     int32_t hash;         /* lcn_hash */
-    int32_t num_buckets;  /* b, 1 .. 4096 */
+    int32_t num_buckets;  /* b, 1 .. 4096 (cross-polytope with and_width w: b^w <= 4096) */
     int32_t num_rounds;   /* R, 1 .. 8 */
     int32_t kmeans_iters; /* >= 1 (k-means hashing only) */
     uint64_t seed;
     const float *projections; /* device; cross-polytope only, else NULL */
+    int32_t branching[3];     /* hierarchical k-means: factors per level, unused levels 0; all 0: flat */
+    int32_t and_width;        /* cross-polytope: hashes per band; 0 or 1: one */
 } lcn_lsh_params;
 
 /* Size of a workspace that is certainly enough for everything except the
@@ -150,7 +163,7 @@ typedef struct {
 
 /* Build all problems of a batch.  X, Y: device fp32, (sum n_p) x d and
  * (sum m_p) x d, d <= 64; they must stay valid until the build returns.
- * landmarks: l <= 16, problem p uses seed + p; lsh: k-means hashing only,
+ * landmarks: l <= 16, problem p uses seed + p; lsh: flat k-means hashing only,
  * buckets <= 16, rounds <= 4, problem p round r uses seed + p*rounds + r.
  * The handle works with sinkhorn_run, transport_cost (writes num_problems
  * doubles), lcn_last_run_timing and lcn_destroy; results per problem come from

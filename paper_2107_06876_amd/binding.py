@@ -27,7 +27,8 @@ class LandmarkParams(ctypes.Structure):
 
 class LshParams(ctypes.Structure):
     _fields_ = [("hash", ctypes.c_int32), ("num_buckets", ctypes.c_int32), ("num_rounds", ctypes.c_int32),
-                ("kmeans_iters", ctypes.c_int32), ("seed", ctypes.c_uint64), ("projections", ctypes.c_void_p)]
+                ("kmeans_iters", ctypes.c_int32), ("seed", ctypes.c_uint64), ("projections", ctypes.c_void_p),
+                ("branching", ctypes.c_int32 * 3), ("and_width", ctypes.c_int32)]
 
 
 class Info(ctypes.Structure):
@@ -153,6 +154,11 @@ def _params(landmarks, lsh, keep):
         ls = LshParams(int(lsh.get("hash", HASH_KMEANS)), int(lsh["num_buckets"]), int(lsh["num_rounds"]),
                        int(lsh.get("kmeans_iters", 10)), int(lsh.get("seed", 101)),
                        None if proj is None else proj.data_ptr())
+        branching = [int(x) for x in (lsh.get("branching") or [])]
+        if len(branching) > 3:
+            raise ValueError("at most three levels of hierarchical k-means")
+        ls.branching = (ctypes.c_int32 * 3)(*(branching + [0] * (3 - len(branching))))
+        ls.and_width = int(lsh.get("and_width", 1))
     return lm, ls
 
 
@@ -169,7 +175,7 @@ def lcn_workspace_bytes(n, m, d, mode, landmarks=None, lsh=None, nnz_guess=0) ->
 
 def lcn_build(X, Y, a, b, lam, cost, mode, landmarks=None, lsh=None, workspace=None, stream=None) -> LcnHandle:
     """landmarks: dict(num_landmarks, kmeans_iters, seed, ridge, init, init_centroids); lsh: dict(hash,
-    num_buckets, num_rounds, kmeans_iters, seed, projections).  X, Y: float32 or
+    num_buckets, num_rounds, kmeans_iters, seed, projections, branching, and_width).  X, Y: float32 or
     bfloat16 device tensors.  If the workspace (a uint8 device tensor) is
     missing or too small a new one of the size the library asks for is
     allocated and the build is repeated."""

@@ -493,7 +493,8 @@ lcn_status lcn_build_batched(const float *X, const float *Y, int32_t d, const lc
                      !(lm->ridge >= 0.0)))
         return LCN_ERR_INVALID_ARG;
     if (hashed && (!lsh || lsh->hash != LCN_HASH_KMEANS || lsh->num_buckets < 1 || lsh->num_buckets > BL ||
-                   lsh->num_rounds < 1 || lsh->num_rounds > BR || lsh->kmeans_iters < 1))
+                   lsh->num_rounds < 1 || lsh->num_rounds > BR || lsh->kmeans_iters < 1 || lsh->branching[0] != 0 ||
+                   lsh->and_width > 1))
         return LCN_ERR_INVALID_ARG;
     if ((desc->del_cost_x == nullptr) != (desc->del_cost_y == nullptr)) return LCN_ERR_INVALID_ARG;
     for (int p = 0; p < P; ++p) {

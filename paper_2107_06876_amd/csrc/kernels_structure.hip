@@ -47,7 +47,8 @@ hipError_t launch_convert(const void *X, long long n, const void *Y, long long m
 __global__ void gather_rows_kernel(const float *Z, int d, const long long *idx, int k, float *out)
 {
     int c = blockIdx.x;
-    for (int j = threadIdx.x; j < d; j += blockDim.x) out[(long long)c * d + j] = Z[idx[c] * d + j];
+    const long long src = idx[c];   // negative: no such row, the slot is filled with zeros
+    for (int j = threadIdx.x; j < d; j += blockDim.x) out[(long long)c * d + j] = src < 0 ? 0.f : Z[src * d + j];
 }
 
 hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k, float *out, hipStream_t s)
@@ -581,6 +582,130 @@ hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const
     return hipGetLastError();
 }
 
+// ------------------------------------------- hierarchical k-means, AND hash --
+//
+// Lower levels of hierarchical k-means hashing (App. "Choosing LSH neighbors and
+// Nystrom landmarks"): inside every cluster of the level above, a k-means of its
+// own.  The points arrive grouped by parent (`order`), cut into chunks of at most
+// 64 members of ONE parent: chunk = {parent, first position in order, members}.
+// A wavefront takes a chunk, one member per lane, and adds up the squared
+// distances to all children of that parent at once (children's centroids in
+// LDS, read as broadcasts) -- the bucket rule: fp64, dimensions in order,
+// multiply and add separately, lowest index among the minima.  bucket =
+// parent * branch + child.
+constexpr int HK_MAX_BRANCH = 32;
+
+// Children's centroids as fp64, laid out [parent][dimension][child] with the children padded to
+// `brp` (4, 8, 16 or 32): the sweep below reads one dimension of all children of a parent as one
+// run of wave-uniform (scalar) loads.  A child that does not exist gets +infinity, which no
+// minimum picks.
+__global__ void children_layout_kernel(const float *cent, int d, int branch, int brp, const int *nchild,
+                                       long long total, double *out)
+{
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    const int j = (int)(e % brp);
+    const long long pk = e / brp;
+    const int k = (int)(pk % d);
+    const long long parent = pk / d;
+    out[e] = j < nchild[parent] ? (double)cent[(parent * branch + j) * d + k] : INFINITY;
+}
+
+template <int BRP>
+__global__ __launch_bounds__(64) void assign_children_kernel(const float *Z, int d, const double *centT, int branch,
+                                                             const int *order, const int *chunks, int32_t *out)
+{
+    __shared__ float tile[64][33];
+    __shared__ int mem_sh[64];
+    const int lane = threadIdx.x;
+    const int half = lane >> 5, col = lane & 31;
+    const int parent = __builtin_amdgcn_readfirstlane(chunks[3 * blockIdx.x]);
+    const int first = chunks[3 * blockIdx.x + 1], cnt = chunks[3 * blockIdx.x + 2];
+    const int me = order[first + (lane < cnt ? lane : cnt - 1)];   // lanes past the end repeat the last member
+    mem_sh[lane] = me;
+    __syncthreads();
+    long long rowoff[32];
+#pragma unroll
+    for (int q = 0; q < 32; ++q) rowoff[q] = (long long)mem_sh[2 * q + half] * d;
+    // wave-uniform address in the constant address space: read through the scalar unit
+    typedef const __attribute__((address_space(4))) double *cptr;
+    cptr ct = (cptr)(unsigned long long)(centT + (long long)parent * d * BRP);
+    double acc[BRP];
+#pragma unroll
+    for (int j = 0; j < BRP; ++j) acc[j] = 0.0;
+    float v[32];
+    auto fetch = [&](int k0) {
+        const int kc = k0 + col < d ? k0 + col : d - 1;
+#pragma unroll
+        for (int q = 0; q < 32; ++q) v[q] = Z[rowoff[q] + kc];
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < d; k0 += 32) {
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 32; ++q) tile[2 * q + half][col] = v[q];
+        __syncthreads();
+        if (k0 + 32 < d) fetch(k0 + 32);
+        const int kend = d - k0 < 32 ? d - k0 : 32;
+        for (int kk = 0; kk < kend; ++kk) {
+            const double zv = (double)tile[lane][kk];
+            cptr crow = ct + (long long)(k0 + kk) * BRP;
+#pragma unroll
+            for (int j = 0; j < BRP; ++j) {
+                const double df = zv - crow[j];
+                const double sq = df * df;
+                acc[j] = acc[j] + sq;
+            }
+        }
+    }
+    int best = 0;
+    double bestD = acc[0];
+#pragma unroll
+    for (int j = 1; j < BRP; ++j) {
+        if (acc[j] < bestD) {
+            bestD = acc[j];
+            best = j;
+        }
+    }
+    if (lane < cnt) out[me] = parent * branch + best;
+}
+
+// centT: scratch of parents * d * 32 doubles at most
+hipError_t launch_assign_children(const float *Z, int d, const float *cent, long long parents, int branch,
+                                  const int *nchild, const int *order, const int *chunks, int nchunks, double *centT,
+                                  int32_t *out, hipStream_t s)
+{
+    if (branch < 1 || branch > HK_MAX_BRANCH) return hipErrorInvalidValue;
+    if (nchunks < 1) return hipSuccess;
+    const int brp = branch <= 4 ? 4 : branch <= 8 ? 8 : branch <= 16 ? 16 : 32;
+    const long long total = parents * d * brp;
+    hipLaunchKernelGGL(children_layout_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, cent, d, branch,
+                       brp, nchild, total, centT);
+#define LCN_CHILDREN(B)                                                                                          \
+    hipLaunchKernelGGL(assign_children_kernel<B>, dim3(nchunks), dim3(64), 0, s, Z, d, (const double *)centT, branch, \
+                       order, chunks, out)
+    if (brp == 4) LCN_CHILDREN(4);
+    else if (brp == 8) LCN_CHILDREN(8);
+    else if (brp == 16) LCN_CHILDREN(16);
+    else LCN_CHILDREN(32);
+#undef LCN_CHILDREN
+    return hipGetLastError();
+}
+
+// AND construction: the bucket of a band of hashes is the tuple of their values,
+// numbered acc * b + h, one hash at a time.
+__global__ void combine_hash_kernel(int32_t *acc, const int32_t *h, int b, int first, long long N)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) acc[i] = (first ? 0 : acc[i] * b) + h[i];
+}
+
+hipError_t launch_combine_hash(int32_t *acc, const int32_t *h, int b, int first, long long N, hipStream_t s)
+{
+    hipLaunchKernelGGL(combine_hash_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, acc, h, b, first, N);
+    return hipGetLastError();
+}
+
 // -------------------------------------------------------- k-means update --
 //
 // Member sums in 2^-32 fixed point: integer addition is associative, so the
@@ -663,16 +788,20 @@ __global__ __launch_bounds__(256) void kmeans_scatter_kernel(const int32_t *__re
         if (cl[u] >= 0) order[start[cl[u]] + rank[u]] = (int)(p0 + tid + 256 * u);
 }
 
-// grid: (k, ceil(d / 64)); 1024 threads.
+// grid: (k, ceil(d / SW)); 1024 threads.  SW = 64: a wave-wide load is one member's 64 dimensions.
+// SW = 16 (few clusters: more, narrower workgroups): it is 16 dimensions of four members.
+template <int SW>
 __global__ __launch_bounds__(1024) void kmeans_sum_kernel(const float *__restrict__ Z, int d, int k,
                                                           const int *__restrict__ counts, const int *__restrict__ offs,
                                                           const int *__restrict__ order, float *__restrict__ cent,
                                                           int *__restrict__ counts_next, int *__restrict__ cursor_next,
                                                           unsigned *reset_a, int *reset_b)
 {
-    __shared__ long long red[16][64];
+    constexpr int RPL = 64 / SW;   // members per wave-wide load
+    __shared__ long long red[16][SW];
     const int c = blockIdx.x, slice = blockIdx.y;
     const int lane = threadIdx.x & 63;
+    const int sub = lane / SW, jl = lane % SW;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (slice == 0 && threadIdx.x == 0) {  // scratch of the next assignment and update steps starts from zero
         counts_next[c] = 0;
@@ -687,32 +816,37 @@ __global__ __launch_bounds__(1024) void kmeans_sum_kernel(const float *__restric
     }
     const int cnt = counts[c];
     const int *__restrict__ mem = order + offs[c];
-    const int j = 64 * slice + lane;
+    const int j = SW * slice + jl;
     const bool jin = j < d;
     long long sum = 0;
     // the 16 wavefronts share out the members in contiguous runs; a wave reads up to 64 member
-    // indices at once (one per lane) and then requests 16 rows before the first is added
+    // indices at once (one per lane) and then requests 16 loads before the first is added
     const int per = (cnt + 15) / 16;
     const int beg = wave * per;
     const int end = beg + per < cnt ? beg + per : cnt;
     for (int base = beg; base < end; base += 64) {
         const int nloc = end - base < 64 ? end - base : 64;
         const int myidx = lane < nloc ? mem[base + lane] : 0;
-        for (int u0 = 0; u0 < nloc; u0 += 16) {
+        for (int u0 = 0; u0 < nloc; u0 += 16 * RPL) {
             float z[16];
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
-                const int uu = u0 + u;
-                const long long row = __builtin_amdgcn_readlane(myidx, uu < 64 ? uu : 63);
+                const int uu = u0 + u * RPL + sub;
+                long long row;
+                if (RPL == 1)
+                    row = __builtin_amdgcn_readlane(myidx, uu < 64 ? uu : 63);
+                else
+                    row = __shfl(myidx, uu < 64 ? uu : 63, 64);
                 z[u] = (uu < nloc && jin) ? Z[row * d + j] : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < 16; ++u) sum += __double2ll_rn((double)z[u] * 4294967296.0);
         }
     }
-    red[wave][lane] = sum;
+    for (int o = SW; o < 64; o <<= 1) sum += __shfl_xor(sum, o, 64);   // the members a load held side by side
+    if (lane < SW) red[wave][lane] = sum;
     __syncthreads();
-    if (wave == 0 && jin && cnt > 0) {  // an empty cluster keeps its centroid
+    if (wave == 0 && lane < SW && jin && cnt > 0) {  // an empty cluster keeps its centroid
         long long tot = 0;
 #pragma unroll
         for (int w = 0; w < 16; ++w) tot += red[w][lane];
@@ -733,8 +867,12 @@ hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_
     hipLaunchKernelGGL(kmeans_count_kernel, dim3(blocks), dim3(256), sizeof(int) * (size_t)k, s, assign, N, k, counts);
     hipLaunchKernelGGL(kmeans_scatter_kernel, dim3(blocks), dim3(256), 2 * sizeof(int) * (size_t)k, s, assign, N, k,
                        counts, cursor, order, offs);
-    hipLaunchKernelGGL(kmeans_sum_kernel, dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(1024), 0, s, Z, d, k,
-                       counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
+    if ((long long)k * ((d + 63) / 64) >= 512)
+        hipLaunchKernelGGL(kmeans_sum_kernel<64>, dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(1024), 0, s, Z, d, k,
+                           counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
+    else   // few clusters: narrower slices, four times the workgroups
+        hipLaunchKernelGGL(kmeans_sum_kernel<16>, dim3((unsigned)k, (unsigned)((d + 15) / 16)), dim3(1024), 0, s, Z, d, k,
+                           counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
     return hipGetLastError();
 }
 

@@ -75,6 +75,8 @@ struct Scratch {  // build-only buffers
     unsigned *cmax_bits;
     int *flagged, *nflagged, *pairs;
     unsigned long long *pp_state;  // k-means++: bits of the largest squared norm
+    int *horder, *hchunks, *nchild;  // hierarchical k-means: points grouped by parent, chunk list, children per parent
+    double *hcent;                   // ... and the children's centroids as fp64, [parent][dimension][child padded]
     char *zt, *ct;  // bf16 planes of the points and of the centroids (assignment filter)
     int zplanes;
 };
@@ -109,6 +111,13 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.cmax_bits = bump.take<unsigned>(4);
     sc.nflagged = bump.take<int>(4);
     sc.pp_state = bump.take<unsigned long long>(4);
+    if (h.hier_levels > 1) {
+        sc.horder = bump.take<int>((size_t)N);
+        sc.hchunks = bump.take<int>(3 * ((size_t)N / 64 + (size_t)kmax + 1));
+        sc.nchild = bump.take<int>((size_t)kmax);
+        // parents * padded children <= 8 * buckets (a level of fewer than 4 children is padded to 4)
+        sc.hcent = bump.take<double>(8 * (size_t)h.b * h.d);
+    }
     sc.flagged = bump.take<int>((size_t)N + 8);  // also the k-means++ sweep's 64-bit totals, one per 64 points
     sc.pairs = bump.take<int>(3 * (size_t)N);
     h.bucket = bump.take<int32_t>((size_t)(h.R > 0 ? h.R : 1) * N);
@@ -186,11 +195,33 @@ lcn_status check_params(long long n, long long m, int d, int dtype, float lambda
         if (!lsh) return LCN_ERR_INVALID_ARG;
         if (lsh->num_buckets < 1 || lsh->num_buckets > 4096) return LCN_ERR_INVALID_ARG;
         if (lsh->num_rounds < 1 || lsh->num_rounds > 8) return LCN_ERR_INVALID_ARG;
+        if (lsh->and_width < 0 || lsh->and_width > 12) return LCN_ERR_INVALID_ARG;
         if (lsh->hash == LCN_HASH_KMEANS) {
-            if (lsh->kmeans_iters < 1 || lsh->num_buckets > n + m) return LCN_ERR_INVALID_ARG;
+            if (lsh->kmeans_iters < 1 || lsh->and_width > 1) return LCN_ERR_INVALID_ARG;
+            if (lsh->branching[0] > 0) {   // hierarchical: the factors must multiply to num_buckets
+                long long prod = 1;
+                for (int j = 0; j < 3 && lsh->branching[j] > 0; ++j) {
+                    if (j > 0 && lsh->branching[j] > 32) return LCN_ERR_INVALID_ARG;
+                    prod *= lsh->branching[j];
+                    if (prod > 4096) return LCN_ERR_INVALID_ARG;
+                }
+                for (int j = 0; j < 3; ++j) {
+                    if (lsh->branching[j] < 0) return LCN_ERR_INVALID_ARG;
+                    if (j > 0 && lsh->branching[j] > 0 && lsh->branching[j - 1] == 0) return LCN_ERR_INVALID_ARG;
+                }
+                if (prod != lsh->num_buckets || lsh->branching[0] > n + m) return LCN_ERR_INVALID_ARG;
+            } else if (lsh->num_buckets > n + m) {
+                return LCN_ERR_INVALID_ARG;
+            }
             kmeans = true;
         } else if (lsh->hash == LCN_HASH_CROSSPOLYTOPE) {
             if ((lsh->num_buckets & 1) || !lsh->projections) return LCN_ERR_INVALID_ARG;
+            if (lsh->branching[0] != 0) return LCN_ERR_INVALID_ARG;
+            long long prod = 1;
+            for (int j = 0; j < (lsh->and_width > 1 ? lsh->and_width : 1); ++j) {
+                prod *= lsh->num_buckets;
+                if (prod > 4096) return LCN_ERR_INVALID_ARG;   // buckets of a band: num_buckets ^ and_width
+            }
         } else {
             return LCN_ERR_INVALID_ARG;
         }
@@ -209,10 +240,18 @@ void fill_shape(Handle &h, long long n, long long m, int d, int mode, const lcn_
     h.log_domain = (mode == LCN_MODE_SPARSE || mode == LCN_MODE_DENSE) ? 1 : 0;
     h.l = uses_landmarks(mode) ? lm->num_landmarks : 0;
     h.lp = (h.l + 63) / 64 * 64;
+    h.hier_levels = 0;
+    h.and_width = 1;
     if (uses_lsh(mode)) {
         h.R = lsh->num_rounds;
         h.b = lsh->num_buckets;
         h.hash = lsh->hash;
+        if (lsh->hash == LCN_HASH_KMEANS) {
+            while (h.hier_levels < 3 && lsh->branching[h.hier_levels] > 0) ++h.hier_levels;
+        } else if (lsh->and_width > 1) {   // a band's bucket is a tuple of and_width hash values
+            h.and_width = lsh->and_width;
+            for (int j = 1; j < h.and_width; ++j) h.b *= lsh->num_buckets;
+        }
     } else if (mode == LCN_MODE_DENSE) {  // the dense kernel is the single-bucket sparse kernel
         h.R = 1;
         h.b = 1;
@@ -274,6 +313,72 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
         // the last iteration leaves the count of undecided points in place for lcn_get_info
         HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.counts2, sc.cursor2, sc.order, sc.offs, it, cent, sc.cmax_bits,
                                     it + 1 < T ? sc.nflagged : nullptr, h.stream));
+    }
+    return LCN_OK;
+}
+
+// Hierarchical k-means hashing: level 0 is a k-means on all points; level j >= 1 runs, inside every
+// cluster of level j-1, a k-means with branching[j] clusters on that cluster's members (in index
+// order; fewer members than that: one cluster per member), seeded with seed + j * 2^32 + parent.
+// bucket = parent * branching[j] + child.  The grouping by parent and the seeded starts are made on
+// the host from a copy of the level above (one synchronisation per level).
+lcn_status run_hier_kmeans(Handle &h, Scratch &sc, const int32_t *branching, int levels, int T, uint64_t seed,
+                           int32_t *dst)
+{
+    const long long N = h.n + h.m;
+    lcn_status st = run_kmeans(h, sc, branching[0], T, seed, sc.cent, dst);
+    if (st != LCN_OK) return st;
+    long long parents = branching[0];
+    std::vector<int32_t> ids((size_t)N);
+    std::vector<int> order((size_t)N), offs, nchild, chunks;
+    std::vector<long long> start;
+    for (int lev = 1; lev < levels; ++lev) {
+        const int bl = branching[lev];
+        const long long k = parents * bl;
+        HIPCHK(hipMemcpyAsync(ids.data(), dst, sizeof(int32_t) * (size_t)N, hipMemcpyDeviceToHost, h.stream));
+        HIPCHK(hipStreamSynchronize(h.stream));
+        offs.assign((size_t)parents + 1, 0);
+        for (long long i = 0; i < N; ++i) offs[(size_t)ids[(size_t)i] + 1] += 1;
+        for (long long c = 0; c < parents; ++c) offs[(size_t)c + 1] += offs[(size_t)c];
+        {
+            std::vector<int> cur(offs.begin(), offs.end() - 1);
+            for (long long i = 0; i < N; ++i) order[(size_t)cur[(size_t)ids[(size_t)i]]++] = (int)i;   // stable
+        }
+        start.assign((size_t)k, -1);
+        nchild.assign((size_t)parents, 0);
+        chunks.clear();
+        for (long long c = 0; c < parents; ++c) {
+            const int nc = offs[(size_t)c + 1] - offs[(size_t)c];
+            if (nc == 0) continue;
+            const int kc = bl < nc ? bl : nc;
+            nchild[(size_t)c] = kc;
+            std::vector<long long> pick = seeded_indices(seed + ((uint64_t)lev << 32) + (uint64_t)c, nc, kc);
+            for (int j = 0; j < kc; ++j)
+                start[(size_t)(c * bl + j)] = order[(size_t)offs[(size_t)c] + (size_t)pick[(size_t)j]];
+            for (int s0 = 0; s0 < nc; s0 += 64) {
+                chunks.push_back((int)c);
+                chunks.push_back(offs[(size_t)c] + s0);
+                chunks.push_back(nc - s0 < 64 ? nc - s0 : 64);
+            }
+        }
+        const int nchunks = (int)(chunks.size() / 3);
+        HIPCHK(hipMemcpyAsync(sc.idx, start.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
+        HIPCHK(hipMemcpyAsync(sc.nchild, nchild.data(), sizeof(int) * (size_t)parents, hipMemcpyHostToDevice,
+                              h.stream));
+        HIPCHK(hipMemcpyAsync(sc.horder, order.data(), sizeof(int) * (size_t)N, hipMemcpyHostToDevice, h.stream));
+        HIPCHK(hipMemcpyAsync(sc.hchunks, chunks.data(), sizeof(int) * chunks.size(), hipMemcpyHostToDevice,
+                              h.stream));
+        HIPCHK(hipStreamSynchronize(h.stream));  // the host vectors are reused by the next level
+        HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, (int)k, sc.cent, h.stream));
+        HIPCHK(hipMemsetAsync(sc.counts2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
+        HIPCHK(hipMemsetAsync(sc.cursor2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
+        for (int it = 0; it < T; ++it) {
+            HIPCHK(launch_assign_children(h.Z, h.d, sc.cent, parents, bl, sc.nchild, sc.horder, sc.hchunks, nchunks,
+                                          sc.hcent, dst, h.stream));
+            HIPCHK(launch_kmeans_update(h.Z, N, h.d, dst, (int)k, sc.counts2, sc.cursor2, sc.order, sc.offs, it,
+                                        sc.cent, nullptr, nullptr, h.stream));
+        }
+        parents = k;
     }
     return LCN_OK;
 }
@@ -410,8 +515,19 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         for (int r = 0; r < h.R; ++r) {
             int32_t *dst = h.bucket + (long long)r * N;
             if (h.hash == LCN_HASH_KMEANS) {
-                st = run_kmeans(h, sc, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, sc.cent, dst);
+                if (h.hier_levels > 1)
+                    st = run_hier_kmeans(h, sc, lsh->branching, h.hier_levels, lsh->kmeans_iters,
+                                         lsh->seed + (uint64_t)r, dst);
+                else
+                    st = run_kmeans(h, sc, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, sc.cent, dst);
                 if (st != LCN_OK) return st;
+            } else if (h.and_width > 1) {
+                const int b1 = lsh->num_buckets;   // buckets of one hash; the band has b1 ^ and_width
+                for (int j = 0; j < h.and_width; ++j) {
+                    const float *Rm = lsh->projections + ((long long)r * h.and_width + j) * d * (b1 / 2);
+                    HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, b1, sc.assign, h.stream));
+                    HIPCHK(launch_combine_hash(dst, sc.assign, b1, j == 0, N, h.stream));
+                }
             } else {
                 const float *Rm = lsh->projections + (long long)r * d * (h.b / 2);
                 HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, h.b, dst, h.stream));

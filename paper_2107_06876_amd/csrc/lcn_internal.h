@@ -53,6 +53,10 @@ struct Handle;
 hipError_t launch_convert(const void *X, long long n, const void *Y, long long m, int d, int dtype, float *Z,
                           unsigned *range_flag, hipStream_t s);
 hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k, float *out, hipStream_t s);
+hipError_t launch_assign_children(const float *Z, int d, const float *cent, long long parents, int branch,
+                                  const int *nchild, const int *order, const int *chunks, int nchunks, double *centT,
+                                  int32_t *out, hipStream_t s);
+hipError_t launch_combine_hash(int32_t *acc, const int32_t *h, int b, int first, long long N, hipStream_t s);
 hipError_t launch_kmeanspp(const float *Z, long long N, int d, int k, const unsigned long long *rnd, double *w,
                            unsigned long long *partial, int *picks, unsigned long long *state, float *cent,
                            hipStream_t s);
@@ -151,6 +155,8 @@ struct Handle {
     int d, l, lp, R, b;
     int mode, cost, hash;
     int in_dtype;              // storage type X and Y were given in
+    int hier_levels;           // levels of hierarchical k-means hashing (0 or 1: flat)
+    int and_width;             // hashes per band of cross-polytope hashing (AND construction)
     int log_domain;            // kernel without signed parts (sparse, dense): values and vectors are logs
     double lambda, ridge;
     hipStream_t stream;

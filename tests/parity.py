@@ -29,7 +29,8 @@ TOL_RESID = 1e-5
 def oracle_run(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, iters=None):
     B = oracle.build_problem(p.X, p.Y, p.cost, p.lam, mode, p.num_landmarks, p.landmark_seed, p.kmeans_iters, p.ridge,
                              hash_kind, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections,
-                             landmark_init=p.landmark_init, landmark_iters=p.landmark_iters)
+                             landmark_init=p.landmark_init, landmark_iters=p.landmark_iters,
+                             branching=p.branching, and_width=p.and_width)
     st = oracle.sinkhorn(B.op, p.a, p.b, p.iters if iters is None else iters)
     r, c, dist, resid = oracle.marginals(B.op, p.a, p.b, p.lam, st)
     return B, st, r, c, dist, resid
@@ -48,7 +49,7 @@ def gpu_build(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, 
     else:
         lm["init_centroids"] = torch.from_numpy(np.ascontiguousarray(p.landmark_init, dtype=np.float32)).to(device)
     lsh = dict(hash=hash_kind, num_buckets=p.num_buckets, num_rounds=p.num_rounds, kmeans_iters=p.kmeans_iters,
-               seed=p.lsh_seed)
+               seed=p.lsh_seed, branching=p.branching, and_width=p.and_width)
     if hash_kind == workloads.HASH_CROSSPOLYTOPE:
         lsh["projections"] = torch.from_numpy(np.ascontiguousarray(p.projections)).to(device)
     return lcn.lcn_build(X, Y, a, b, p.lam, p.cost, MODES[mode],

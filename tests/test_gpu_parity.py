@@ -229,3 +229,49 @@ def test_landmarks_from_given_start():
     p.landmark_init = (start + 0.05 * rng.standard_normal(start.shape)).astype(np.float32)
     out = compare(p, "lcn")
     print("C1 given start", out, flush=True)
+
+
+@pytest.mark.parametrize("branching", [(6, 4), (3, 2, 4), (2, 32)])
+def test_hierarchical_kmeans_hashing(branching):
+    """Hierarchical k-means LSH (App. "Choosing LSH neighbors and Nystrom landmarks"): same bucket
+    of every point in every round, then the usual parity.  (2, 32) on 1400 points leaves parents
+    whose chunks of 64 members are ragged; config 1 with (3, 2, 4) has three levels."""
+    from parity import compare
+    p = workloads.config3(n=2000, d=70, landmarks=64, buckets=int(np.prod(branching)), rounds=2, iters=30,
+                          name="C3 reduced")
+    p.branching = branching
+    out = compare(p, "lcn")
+    print("C3r hierarchical", branching, out, flush=True)
+    p = workloads.config1(n=700, d=9)
+    p.num_buckets, p.branching = int(np.prod(branching)), branching
+    out = compare(p, "sparse")
+    print("C1 hierarchical", branching, out, flush=True)
+
+
+def test_hierarchical_kmeans_parent_smaller_than_branching():
+    """A parent with fewer members than children: one bucket per member."""
+    import torch
+    import oracle
+    import paper_2107_06876_amd as lcn
+    rng = np.random.default_rng(6)
+    X = np.concatenate([[[0, 0, 0], [1, 0, 0], [0, 1, 0]], 50 + rng.standard_normal((90, 3))]).astype(np.float32)
+    Y = (50 + rng.standard_normal((70, 3))).astype(np.float32)
+    want = oracle.hash_rounds(np.concatenate([X, Y]), 0, 10, 2, 6, 11, branching=(2, 5))
+    a = torch.full((len(X),), 1.0 / len(X), device="cuda")
+    b = torch.full((len(Y),), 1.0 / len(Y), device="cuda")
+    lsh = dict(num_buckets=10, num_rounds=2, kmeans_iters=6, seed=11, branching=(2, 5))
+    h = lcn.lcn_build(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda(), a, b, 5.0, lcn.COST_SQEUCLID,
+                      lcn.MODE_SPARSE, lsh=lsh)
+    np.testing.assert_array_equal(lcn.lcn_get_buckets(h).cpu().numpy(), want)
+    lcn.lcn_destroy(h)
+
+
+@pytest.mark.parametrize("width", [2, 3])
+def test_crosspolytope_and_construction(width):
+    """AND construction for cross-polytope hashing: a band of `width` hashes, bucket = the tuple."""
+    from parity import compare
+    p = workloads.config3(n=3000, landmarks=96, buckets=8 if width == 2 else 4, rounds=3, iters=40)
+    p.and_width = width
+    p.projections = workloads.projections(3, p.num_rounds * width, p.d, p.num_buckets)
+    out = compare(p, "sparse", workloads.HASH_CROSSPOLYTOPE)
+    print("C3r AND", width, out, flush=True)

@@ -53,6 +53,11 @@ class Problem:
     # iteration count if it differs from kmeans_iters (0: the start itself is the landmark set)
     landmark_init: object = "sample"
     landmark_iters: Optional[int] = None
+    # hierarchical k-means hashing: branching factors per level (their product is num_buckets)
+    branching: Optional[tuple] = None
+    # cross-polytope hashing: hashes per band (AND construction); num_buckets is then the bucket
+    # count of ONE hash and projections holds num_rounds * and_width matrices
+    and_width: int = 1
 
     @property
     def n(self):
