@@ -274,57 +274,92 @@ hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N,
     return hipGetLastError();
 }
 
-// One workgroup: Cholesky factor of the nb x nb diagonal block at (j0, j0) of Lm
-// (ridge added to its diagonal), written back into Lm's lower triangle, and the
-// inverse of that triangular factor into Dinv (NB x NB, zero above the diagonal).
+// One workgroup of 256 threads: Cholesky factor of the nb x nb diagonal block at (j0, j0) of Lm
+// (ridge added to its diagonal), written back into Lm's lower triangle, and the inverse of that
+// triangular factor into Dinv (NB x NB, zero above the diagonal and outside nb).
+// Factorisation: thread (ty, tx) of a 16 x 16 grid keeps the 4 x 4 patch rows 4ty.., columns 4tx..
+// in registers; at step j the owners of column j publish it (unscaled) through LDS and everybody
+// subtracts l_ij l_kj with l_ij = s_ij / sqrt(s_jj): one barrier per column.  A block smaller than
+// NB is padded with the identity.  Inversion: thread c < 64 solves column c by forward
+// substitution, its column in registers, L read from LDS as broadcasts.
 __global__ __launch_bounds__(256) void chol_diag_kernel(double *Lm, int l, int j0, int nb, double ridge, double *Dinv,
                                                         int *fail_flag)
 {
-    __shared__ double S[NB][NB + 1];
-    __shared__ double X[NB][NB + 1];
-    const int tid = threadIdx.x;
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int i = e / NB, j = e % NB;
-        double v = 0.0;
-        if (i < nb && j < nb) v = Lm[(long long)(j0 + i) * l + j0 + j] + (i == j ? ridge : 0.0);
-        S[i][j] = v;
-        X[i][j] = 0.0;
-    }
-    __syncthreads();
-    for (int j = 0; j < nb; ++j) {
-        if (tid == 0) {
-            double dd = S[j][j];
-            if (!(dd > 0.0)) {
-                *fail_flag = 1;
-                dd = 1.0;
+    static_assert(NB == 64, "16 x 16 threads with 4 x 4 patches");
+    __shared__ double colbuf[2][NB];
+    __shared__ double rs_sh[NB];          // 1 / L_jj
+    __shared__ double Ls[NB][NB + 1];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    double p[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int i = 4 * ty + a, k = 4 * tx + b;
+            double v = (i == k) ? 1.0 : 0.0;
+            if (i < nb && k < nb) v = Lm[(long long)(j0 + i) * l + j0 + k] + (i == k ? ridge : 0.0);
+            p[a][b] = v;
+        }
+    bool fail = false;
+    for (int j = 0; j < NB; ++j) {
+        double *cb = colbuf[j & 1];
+        if (tx == (j >> 2)) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                double v = p[a][0];
+                if ((j & 3) == 1) v = p[a][1];
+                if ((j & 3) == 2) v = p[a][2];
+                if ((j & 3) == 3) v = p[a][3];
+                cb[4 * ty + a] = v;
             }
-            S[j][j] = sqrt(dd);
         }
         __syncthreads();
-        const double piv = S[j][j];
-        for (int i = j + 1 + tid; i < nb; i += 256) S[i][j] /= piv;
-        __syncthreads();
-        const int rem = nb - j - 1;
-        for (int e = tid; e < rem * rem; e += 256) {
-            const int i = j + 1 + e / rem, k = j + 1 + e % rem;
-            if (k <= i) S[i][k] -= S[i][j] * S[k][j];
+        double dd = cb[j];
+        if (!(dd > 0.0)) {
+            fail = true;
+            dd = 1.0;
         }
-        __syncthreads();
+        const double rs = 1.0 / sqrt(dd);
+        if (tid == 0) rs_sh[j] = rs;
+        if (4 * tx + 3 > j && tx <= ty) {   // some column of the patch is still to the right of j, patch on or below the diagonal
+            double li[4], lk[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) li[a] = cb[4 * ty + a] * rs;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) lk[b] = cb[4 * tx + b] * rs;
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int i = 4 * ty + a, k = 4 * tx + b;
+                    if (k > j && k <= i) p[a][b] -= li[a] * lk[b];
+                }
+        }
     }
-    // X = S^{-1} by forward substitution, one thread per column
-    if (tid < nb) {
-        const int c = tid;
-        for (int i = c; i < nb; ++i) {
-            double t = (i == c) ? 1.0 : 0.0;
-            for (int k = c; k < i; ++k) t = fma(-S[i][k], X[k][c], t);
-            X[i][c] = t / S[i][i];
+    if (fail && tid == 0) *fail_flag = 1;
+    __syncthreads();   // rs_sh complete
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int i = 4 * ty + a, k = 4 * tx + b;
+            const double v = k <= i ? p[a][b] * rs_sh[k] : 0.0;   // column k was final once step k - 1 was done
+            Ls[i][k] = v;
+            if (i < nb && k <= i) Lm[(long long)(j0 + i) * l + j0 + k] = v;
         }
-    }
     __syncthreads();
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int i = e / NB, j = e % NB;
-        Dinv[e] = X[i][j];
-        if (i < nb && j <= i) Lm[(long long)(j0 + i) * l + j0 + j] = S[i][j];
+    if (tid < NB) {
+        const int c = tid;
+        double xc[NB];
+#pragma unroll
+        for (int r = 0; r < NB; ++r) {
+            double t = (r == c) ? 1.0 : 0.0;
+#pragma unroll
+            for (int k = 0; k < r; ++k) t = fma(-Ls[r][k], xc[k], t);   // xc[k] = 0 for k < c
+            xc[r] = r >= c ? t * rs_sh[r] : 0.0;
+        }
+#pragma unroll
+        for (int r = 0; r < NB; ++r) Dinv[r * NB + c] = (r < nb && c < nb) ? xc[r] : 0.0;
     }
 }
 

@@ -887,6 +887,31 @@ constexpr int CH = 1024;
 
 __global__ void scan_i64_kernel(long long *data, long long n);
 
+// Exclusive scan of 1024 per-thread values across a workgroup of 1024 threads: returns the sum
+// of the values of all lower threads; *total receives the sum of all.  wsum: 16 words of LDS.
+__device__ inline long long block_exclusive_scan_1024(long long local, long long *wsum, long long *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    long long incl = local;
+    for (int o = 1; o < 64; o <<= 1) {
+        const long long up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    __syncthreads();   // wsum may still be read from the previous use
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    long long before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const long long v = wsum[w];
+        if (w < wave) before += v;
+        all += v;
+    }
+    *total = all;
+    return before + incl - local;
+}
+
+
 int sort_chunks(long long n, long long m)
 {
     long long mx = n > m ? n : m;
@@ -934,119 +959,97 @@ __global__ void sort_chunk_prefix_kernel(SortBuffers B)
 // single block: bucket offsets per (side, round), tile offsets over all blocks
 __global__ __launch_bounds__(1024) void sort_offsets_kernel(SortBuffers B)
 {
-    __shared__ long long part[1024];
-    __shared__ long long part2[1024];
+    __shared__ long long wsum[16];
     const int tid = threadIdx.x;
     // per (side, round): exclusive scan of totals over buckets; 2R <= 16 sequences
     for (int sr = 0; sr < 2 * B.R; ++sr) {
         const int *tot = B.totals + sr * B.b;
         int *off = B.off + sr * (B.b + 1);
-        int seg = (B.b + 1023) / 1024;
-        int lo = tid * seg, hi = lo + seg < B.b ? lo + seg : B.b;
-        long long s = 0;
-        for (int i = lo; i < hi; ++i) s += tot[i];
-        part[tid] = s;
-        __syncthreads();
-        if (tid == 0) {
-            long long run = 0;
-            for (int i = 0; i < 1024; ++i) {
-                long long v = part[i];
-                part[i] = run;
-                run += v;
-            }
-            off[B.b] = (int)run;
-        }
-        __syncthreads();
-        long long run = part[tid];
+        const int seg = (B.b + 1023) / 1024;
+        const int lo = tid * seg, hi = lo + seg < B.b ? lo + seg : B.b;
+        long long sum = 0;
+        for (int i = lo; i < hi; ++i) sum += tot[i];
+        long long all;
+        long long run = block_exclusive_scan_1024(sum, wsum, &all);
+        if (tid == 0) off[B.b] = (int)all;
         for (int i = lo; i < hi; ++i) {
             off[i] = (int)run;
             run += tot[i];
         }
-        __syncthreads();
     }
     // blocks in (round, bucket) order: value offsets (nx * ny) and 64 x 64 build tiles
     const int nb = B.R * B.b;
-    int seg = (nb + 1023) / 1024;
-    int lo = tid * seg, hi = lo + seg < nb ? lo + seg : nb;
-    long long s = 0, s2 = 0;
+    const int seg = (nb + 1023) / 1024;
+    const int lo = tid * seg, hi = lo + seg < nb ? lo + seg : nb;
+    long long sum = 0, sum2 = 0;
     for (int i = lo; i < hi; ++i) {
-        long long nx = B.totals[i];
-        long long ny = B.totals[B.R * B.b + i];
-        s += nx * ny;
-        s2 += ((nx + 63) / 64) * ((ny + 63) / 64);
+        const long long nx = B.totals[i];
+        const long long ny = B.totals[B.R * B.b + i];
+        sum += nx * ny;
+        sum2 += ((nx + 63) / 64) * ((ny + 63) / 64);
     }
-    part[tid] = s;
-    part2[tid] = s2;
-    __syncthreads();
+    long long all, all2;
+    (void)block_exclusive_scan_1024(sum, wsum, &all);
+    long long run2 = block_exclusive_scan_1024(sum2, wsum, &all2);
     if (tid == 0) {
-        long long run = 0, run2 = 0;
-        for (int i = 0; i < 1024; ++i) {
-            long long v = part[i], v2 = part2[i];
-            part[i] = run;
-            part2[i] = run2;
-            run += v;
-            run2 += v2;
-        }
-        B.tile_off[nb] = (int)run2;
-        B.totals_out[0] = run;
-        B.totals_out[1] = run2;
+        B.tile_off[nb] = (int)all2;
+        B.totals_out[0] = all;
+        B.totals_out[1] = all2;
     }
-    __syncthreads();
-    long long run = part[tid], run2 = part2[tid];
     for (int i = lo; i < hi; ++i) {
-        long long nx = B.totals[i];
-        long long ny = B.totals[B.R * B.b + i];
+        const long long nx = B.totals[i];
+        const long long ny = B.totals[B.R * B.b + i];
         B.tile_off[i] = (int)run2;
-        run += nx * ny;
         run2 += ((nx + 63) / 64) * ((ny + 63) / 64);
     }
 }
 
-// grid: (chunks, R, 2), one wavefront per chunk
-__global__ __launch_bounds__(64) void sort_scatter_kernel(SortBuffers B)
+// grid: (chunks, R, 2); one workgroup of 16 wavefronts per chunk of 1024 elements, one element
+// per thread.  Stable: a wavefront ranks its 64 elements among equal keys by ballots, then the
+// wavefronts take their places in the running bucket positions one after the other.
+__global__ __launch_bounds__(1024) void sort_scatter_kernel(SortBuffers B)
 {
     extern __shared__ int running[];
     const int chunk = blockIdx.x, r = blockIdx.y, side = blockIdx.z;
     const long long cnt = side_count(B, side);
     const long long base = (long long)chunk * CH;
     if (base >= cnt) return;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sr = side * B.R + r;
     const int *pre = B.hist + ((long long)sr * B.chunks + chunk) * B.b;
     const int *off = B.off + sr * (B.b + 1);
-    for (int t = lane; t < B.b; t += 64) running[t] = off[t] + pre[t];
-    __syncthreads();
+    for (int t = threadIdx.x; t < B.b; t += 1024) running[t] = off[t] + pre[t];
     const int32_t *bk = B.bucket + (long long)r * (B.n + B.m) + (side ? B.n : 0);
     int *perm = B.perm + (side ? (long long)B.R * B.n + (long long)r * B.m : (long long)r * B.n);
     int *pos = B.pos + (side ? (long long)B.R * B.n + (long long)r * B.m : (long long)r * B.n);
-    for (int step = 0; step < CH / 64; ++step) {
-        long long i = base + step * 64 + lane;
-        bool valid = i < cnt;
-        int key = valid ? bk[i] : -1;
-        int rank = 0, group = 0;
-        // rank of this lane among the lanes with the same key (lower lanes first)
-        bool pending = valid;
-        while (true) {
-            unsigned long long todo = __ballot(pending);
-            if (todo == 0ull) break;
-            int leader = __ffsll((long long)todo) - 1;
-            int k0 = __shfl(key, leader, 64);
-            unsigned long long same = __ballot(pending && key == k0);
-            if (pending && key == k0) {
-                rank = __popcll(same & ((1ull << lane) - 1ull));
-                group = __popcll(same);
-                pending = false;
-            }
+    const long long i = base + threadIdx.x;
+    const bool valid = i < cnt;
+    const int key = valid ? bk[i] : -1;
+    int rank = 0, group = 0;
+    // rank of this lane among the lanes of its wavefront with the same key (lower lanes first)
+    bool pending = valid;
+    while (true) {
+        const unsigned long long todo = __ballot(pending);
+        if (todo == 0ull) break;
+        const int leader = __ffsll((long long)todo) - 1;
+        const int k0 = __shfl(key, leader, 64);
+        const unsigned long long same = __ballot(pending && key == k0);
+        if (pending && key == k0) {
+            rank = __popcll(same & ((1ull << lane) - 1ull));
+            group = __popcll(same);
+            pending = false;
         }
-        int dst = 0;
-        if (valid) dst = running[key] + rank;
-        __syncthreads();
-        if (valid && rank == group - 1) running[key] += group;  // one lane per key
-        __syncthreads();
-        if (valid) {
-            perm[dst] = (int)i;
-            pos[i] = dst;
-        }
+    }
+    int dst = 0;
+    for (int w = 0; w < CH / 64; ++w) {
+        __syncthreads();   // running[] as the wavefronts before w left it (w = 0: as initialised)
+        if (w == wave && valid) dst = running[key] + rank;
+        __syncthreads();   // every lane of wavefront w has read before one lane per key moves the position on
+        if (w == wave && valid && rank == group - 1) running[key] += group;
+    }
+    if (valid) {
+        perm[dst] = (int)i;
+        pos[i] = dst;
     }
 }
 
@@ -1081,7 +1084,7 @@ hipError_t launch_bucket_sort(const SortBuffers &B, hipStream_t s)
     int t = 2 * B.R * B.b;
     hipLaunchKernelGGL(sort_chunk_prefix_kernel, dim3((t + 127) / 128), dim3(128), 0, s, B);
     hipLaunchKernelGGL(sort_offsets_kernel, dim3(1), dim3(1024), 0, s, B);
-    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(64), lds, s, B);
+    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(1024), lds, s, B);
     long long mx = B.n > B.m ? B.n : B.m;
     hipLaunchKernelGGL(seg_kernel, dim3((unsigned)((mx + 255) / 256), 2), dim3(256), 0, s, B);
     hipLaunchKernelGGL(scan_i64_kernel, dim3(1), dim3(1024), 0, s, B.rowbase_x, B.n);
@@ -1332,32 +1335,27 @@ hipError_t launch_csr_values(const Handle &h, const float *rec, const float *rec
 }
 
 // in-place exclusive scan of n int64 values by one block; data[n] receives the total
+// One workgroup; tiles of 4096 elements, four consecutive ones per thread.
 __global__ __launch_bounds__(1024) void scan_i64_kernel(long long *data, long long n)
 {
-    __shared__ long long part[1024];
+    __shared__ long long wsum[16];
     const int tid = threadIdx.x;
-    long long seg = (n + 1023) / 1024;
-    long long lo = tid * seg, hi = lo + seg < n ? lo + seg : n;
-    long long s = 0;
-    for (long long i = lo; i < hi; ++i) s += data[i];
-    part[tid] = s;
-    __syncthreads();
-    if (tid == 0) {
-        long long run = 0;
-        for (int i = 0; i < 1024; ++i) {
-            long long v = part[i];
-            part[i] = run;
-            run += v;
+    long long carry = 0;
+    for (long long t0 = 0; t0 < n; t0 += 4096) {
+        const long long i0 = t0 + 4 * tid;
+        long long v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = i0 + q < n ? data[i0 + q] : 0;
+        long long tile_total;
+        long long run = carry + block_exclusive_scan_1024(v[0] + v[1] + v[2] + v[3], wsum, &tile_total);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (i0 + q < n) data[i0 + q] = run;
+            run += v[q];
         }
-        data[n] = run;
+        carry += tile_total;
     }
-    __syncthreads();
-    long long run = part[tid];
-    for (long long i = lo; i < hi; ++i) {
-        long long v = data[i];
-        data[i] = run;
-        run += v;
-    }
+    if (tid == 0) data[n] = carry;
 }
 
 hipError_t launch_scan_i64(long long *data, long long n, hipStream_t s)
