@@ -62,18 +62,26 @@ size_t split_plane_bytes(long long rows, int d)
 // Splits the rows of `src` (rows x d, fp32) into `planes` bf16 planes in operand
 // order: out[plane][group][step][lane] (16 bytes each); rows and dimensions
 // beyond the matrix are zero.  One workgroup per group of 32 rows.
+// NORMS (the centroids): also the squared norm of every row as fp32 into cn, and the
+// largest of them into cmax_bits (the bit pattern of a non-negative float orders like an
+// unsigned integer; cmax_bits is zero on entry).
+template <bool NORMS>
 __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restrict__ src, long long rows, int d, int S,
-                                                           int planes, bf16x8 *__restrict__ out, long long plane_stride)
+                                                           int planes, bf16x8 *__restrict__ out, long long plane_stride,
+                                                           float *__restrict__ cn, unsigned *cmax_bits)
 {
+    __shared__ double red[4][32];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const long long group = blockIdx.x;
     const long long row = group * 32 + (lane & 31);
+    double sq = 0.0;
     for (int s = w; s < S; s += 4) {
         const int k0 = 16 * s + 8 * (lane >> 5);
         u16x8 p1, p2;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float x = (row < rows && k0 + e < d) ? src[row * d + k0 + e] : 0.f;
+            if (NORMS) sq = fma((double)x, (double)x, sq);
             const unsigned h = bf16_bits(x);
             p1[e] = (unsigned short)h;
             p2[e] = (unsigned short)bf16_bits(x - __uint_as_float(h << 16));  // the difference is exact in fp32
@@ -82,36 +90,26 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
         out[at] = __builtin_bit_cast(bf16x8, p1);
         if (planes > 1) out[plane_stride + at] = __builtin_bit_cast(bf16x8, p2);
     }
+    if (NORMS) {
+        sq += __shfl_xor(sq, 32, 64);   // the two halves of a row's 16 dimensions per step
+        if (lane < 32) red[w][lane] = sq;
+        __syncthreads();
+        if (w == 0 && lane < 32 && row < rows) {
+            const float f = (float)(red[0][lane] + red[1][lane] + red[2][lane] + red[3][lane]);
+            cn[row] = f;
+            atomicMax(cmax_bits, __float_as_uint(f * 1.0000002f));
+        }
+    }
 }
 
 hipError_t launch_split_planes(const float *src, long long rows, int d, int planes, void *out, hipStream_t s)
 {
     const long long groups = (rows + 31) / 32;
     const int S = steps_of(d);
-    hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)groups), dim3(256), 0, s, src, rows, d, S, planes,
-                       (bf16x8 *)out, (long long)(split_plane_bytes(rows, d) / 16));
+    hipLaunchKernelGGL(split_planes_kernel<false>, dim3((unsigned)groups), dim3(256), 0, s, src, rows, d, S, planes,
+                       (bf16x8 *)out, (long long)(split_plane_bytes(rows, d) / 16), (float *)nullptr,
+                       (unsigned *)nullptr);
     return hipGetLastError();
-}
-
-// squared norms of the centroids as fp32 plus their maximum (bit pattern of a
-// non-negative float orders like an unsigned integer)
-__global__ void centroid_norms_kernel(const float *__restrict__ C, int k, int d, float *__restrict__ cn,
-                                      unsigned *cmax_bits)
-{
-    const int c = blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);
-    if (c >= k) return;
-    const int lane = threadIdx.x & 63;
-    double s = 0.0;
-    for (int j = lane; j < d; j += 64) {
-        const double v = (double)C[(long long)c * d + j];
-        s = fma(v, v, s);
-    }
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (lane == 0) {
-        const float f = (float)s;
-        cn[c] = f;
-        atomicMax(cmax_bits, __float_as_uint(f * 1.0000002f));
-    }
 }
 
 // ZP: planes of the points (2: fp32 input, 1: input exactly representable in bf16).
@@ -279,9 +277,9 @@ hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d,
     // cmax_bits and nflagged[0..1] are zero on entry: cleared by the caller before the first
     // call and by the centroid update after every call
     const int S = steps_of(d);
-    hipLaunchKernelGGL(centroid_norms_kernel, dim3((k + 3) / 4), dim3(256), 0, s, cent, k, d, cn, cmax_bits);
-    hipError_t e = launch_split_planes(cent, k, d, 2, Ct, s);
-    if (e != hipSuccess) return e;
+    // the centroids' two bf16 planes, their squared norms and the largest norm in one launch
+    hipLaunchKernelGGL(split_planes_kernel<true>, dim3((unsigned)((k + 31) / 32)), dim3(256), 0, s, cent, (long long)k, d,
+                       S, 2, (bf16x8 *)Ct, (long long)(split_plane_bytes(k, d) / 16), cn, cmax_bits);
     // Bound on |computed score - exact score| / (||z||^2 + max ||c||^2):
     //  * dropped products: z.c - (z1.c1 + z1.c2 + z2.c1) = z2.c2 + r_z.c + z.r_c - ..., each at most
     //    2^-16 sum |z_k||c_k| (plus terms of order 2^-24), and sum |z_k||c_k| <= (||z||^2 + ||c||^2) / 2;

@@ -790,15 +790,15 @@ __global__ __launch_bounds__(256) void kmeans_scatter_kernel(const int32_t *__re
 
 // grid: (k, ceil(d / SW)); 1024 threads.  SW = 64: a wave-wide load is one member's 64 dimensions.
 // SW = 16 (few clusters: more, narrower workgroups): it is 16 dimensions of four members.
-template <int SW>
-__global__ __launch_bounds__(1024) void kmeans_sum_kernel(const float *__restrict__ Z, int d, int k,
+template <int SW, int WPB>
+__global__ __launch_bounds__(64 * WPB) void kmeans_sum_kernel(const float *__restrict__ Z, int d, int k,
                                                           const int *__restrict__ counts, const int *__restrict__ offs,
                                                           const int *__restrict__ order, float *__restrict__ cent,
                                                           int *__restrict__ counts_next, int *__restrict__ cursor_next,
                                                           unsigned *reset_a, int *reset_b)
 {
     constexpr int RPL = 64 / SW;   // members per wave-wide load
-    __shared__ long long red[16][SW];
+    __shared__ long long red[WPB][SW];
     const int c = blockIdx.x, slice = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int sub = lane / SW, jl = lane % SW;
@@ -821,7 +821,7 @@ __global__ __launch_bounds__(1024) void kmeans_sum_kernel(const float *__restric
     long long sum = 0;
     // the 16 wavefronts share out the members in contiguous runs; a wave reads up to 64 member
     // indices at once (one per lane) and then requests 16 loads before the first is added
-    const int per = (cnt + 15) / 16;
+    const int per = (cnt + WPB - 1) / WPB;
     const int beg = wave * per;
     const int end = beg + per < cnt ? beg + per : cnt;
     for (int base = beg; base < end; base += 64) {
@@ -849,7 +849,7 @@ __global__ __launch_bounds__(1024) void kmeans_sum_kernel(const float *__restric
     if (wave == 0 && lane < SW && jin && cnt > 0) {  // an empty cluster keeps its centroid
         long long tot = 0;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) tot += red[w][lane];
+        for (int w = 0; w < WPB; ++w) tot += red[w][lane];
         const double mean = ((double)tot * (1.0 / 4294967296.0)) / (double)cnt;
         cent[(long long)c * d + j] = (float)mean;
     }
@@ -868,11 +868,11 @@ hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_
     hipLaunchKernelGGL(kmeans_scatter_kernel, dim3(blocks), dim3(256), 2 * sizeof(int) * (size_t)k, s, assign, N, k,
                        counts, cursor, order, offs);
     if ((long long)k * ((d + 63) / 64) >= 512)
-        hipLaunchKernelGGL(kmeans_sum_kernel<64>, dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(1024), 0, s, Z, d, k,
-                           counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
+        hipLaunchKernelGGL((kmeans_sum_kernel<64, 16>), dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(1024), 0, s, Z,
+                           d, k, counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
     else   // few clusters: narrower slices, four times the workgroups
-        hipLaunchKernelGGL(kmeans_sum_kernel<16>, dim3((unsigned)k, (unsigned)((d + 15) / 16)), dim3(1024), 0, s, Z, d, k,
-                           counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
+        hipLaunchKernelGGL((kmeans_sum_kernel<16, 16>), dim3((unsigned)k, (unsigned)((d + 15) / 16)), dim3(1024), 0, s, Z,
+                           d, k, counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
     return hipGetLastError();
 }
 

@@ -65,6 +65,7 @@ bool uses_lsh(int mode) { return mode == LCN_MODE_SPARSE || mode == LCN_MODE_LCN
 
 struct Scratch {  // build-only buffers
     long long *idx;
+    long long *starts;  // seeded start indices of every k-means run of the build: landmarks, then one set per round
     float *cent;
     int *counts2, *cursor2, *order, *offs;  // k-means update: [2][kmax], [2][kmax], [N], [kmax]
     int32_t *assign;
@@ -97,9 +98,13 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.totals = bump.take<long long>(4);
     h.L = bump.take<float>((size_t)(h.l > 0 ? h.l : 1) * h.d);
     sc.idx = bump.take<long long>((size_t)kmax);
+    sc.starts = bump.take<long long>((size_t)(h.l > 0 ? h.l : 1) + (size_t)(h.R > 0 ? h.R : 1) * (size_t)h.b);
     sc.cent = bump.take<float>((size_t)kmax * h.d);
+    // counts2 .. nflagged are cleared together at the start of a k-means run
     sc.counts2 = bump.take<int>(2 * (size_t)kmax);
     sc.cursor2 = bump.take<int>(2 * (size_t)kmax);
+    sc.cmax_bits = bump.take<unsigned>(4);
+    sc.nflagged = bump.take<int>(4);
     sc.order = bump.take<int>((size_t)N);
     sc.offs = bump.take<int>((size_t)kmax);
     sc.assign = bump.take<int32_t>((size_t)N);
@@ -108,8 +113,6 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.zplanes = h.in_dtype == LCN_BF16 ? 1 : 2;
     sc.zt = bump.take<char>((size_t)sc.zplanes * split_plane_bytes(N, h.d));
     sc.ct = bump.take<char>(2 * split_plane_bytes(kmax, h.d));
-    sc.cmax_bits = bump.take<unsigned>(4);
-    sc.nflagged = bump.take<int>(4);
     sc.pp_state = bump.take<unsigned long long>(4);
     if (h.hier_levels > 1) {
         sc.horder = bump.take<int>((size_t)N);
@@ -274,8 +277,9 @@ void fill_shape(Handle &h, long long n, long long m, int d, int mode, const lcn_
 
 // T Lloyd iterations on Z from the start `init` names (LCN_INIT_*): centroids into cent, the last
 // iteration's assignment into assign (untouched if T == 0).
+// start_dev (nullable): the k seeded start indices, already on the device (LCN_INIT_SAMPLE only).
 lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float *cent, int32_t *assign,
-                      int init = LCN_INIT_SAMPLE, const float *given = nullptr)
+                      const long long *start_dev = nullptr, int init = LCN_INIT_SAMPLE, const float *given = nullptr)
 {
     const long long N = h.n + h.m;
     if (init == LCN_INIT_GIVEN) {
@@ -290,16 +294,17 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
         // the assignment's buffers are free until the first Lloyd iteration
         HIPCHK(launch_kmeanspp(h.Z, N, h.d, k, (const unsigned long long *)sc.idx, (double *)sc.pairs,
                                (unsigned long long *)sc.flagged, sc.order, sc.pp_state, cent, h.stream));
+    } else if (start_dev) {
+        HIPCHK(launch_gather_rows(h.Z, h.d, start_dev, k, cent, h.stream));
     } else {
         std::vector<long long> idx = seeded_indices(seed, N, k);
         HIPCHK(hipMemcpyAsync(sc.idx, idx.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
         HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
         HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
     }
-    HIPCHK(hipMemsetAsync(sc.cmax_bits, 0, sizeof(unsigned), h.stream));
-    HIPCHK(hipMemsetAsync(sc.nflagged, 0, 2 * sizeof(int), h.stream));
-    HIPCHK(hipMemsetAsync(sc.counts2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
-    HIPCHK(hipMemsetAsync(sc.cursor2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
+    // member counts and cursors of the update, the filter's largest centroid norm and its two
+    // counters lie side by side: one clear
+    HIPCHK(hipMemsetAsync(sc.counts2, 0, (size_t)((char *)(sc.nflagged + 4) - (char *)sc.counts2), h.stream));
     for (int it = 0; it < T; ++it) {
         if (h.exact_assign_only) {
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, h.stream));
@@ -505,9 +510,43 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     if (!h.exact_assign_only && (h.l > 0 || (uses_lsh(mode) && h.hash == LCN_HASH_KMEANS)))
         HIPCHK(launch_split_planes(h.Z, N, d, sc.zplanes, sc.zt, h.stream));
 
+    // seeded starts of all flat k-means runs: one upload, consumed by the stream while `starts`
+    // lives; whichever way this function returns, the stream is drained before the vector goes
+    std::vector<long long> starts;
+    struct Drain {
+        hipStream_t s;
+        bool armed;
+        ~Drain()
+        {
+            if (armed) (void)hipStreamSynchronize(s);
+        }
+    } drain{h.stream, false};
+    const long long *starts_landmarks = nullptr, *starts_rounds = nullptr;
+    {
+        const bool lm_sample = h.l > 0 && lm->init == LCN_INIT_SAMPLE;
+        const bool flat_rounds = uses_lsh(mode) && h.hash == LCN_HASH_KMEANS && h.hier_levels <= 1;
+        if (lm_sample) {
+            std::vector<long long> idx = seeded_indices(lm->seed, N, h.l);
+            starts.insert(starts.end(), idx.begin(), idx.end());
+        }
+        const size_t rounds_at = starts.size();
+        if (flat_rounds)
+            for (int r = 0; r < h.R; ++r) {
+                std::vector<long long> idx = seeded_indices(lsh->seed + (uint64_t)r, N, h.b);
+                starts.insert(starts.end(), idx.begin(), idx.end());
+            }
+        if (!starts.empty()) {
+            drain.armed = true;
+            HIPCHK(hipMemcpyAsync(sc.starts, starts.data(), sizeof(long long) * starts.size(), hipMemcpyHostToDevice,
+                                  h.stream));
+            if (lm_sample) starts_landmarks = sc.starts;
+            if (flat_rounds) starts_rounds = sc.starts + rounds_at;
+        }
+    }
     // landmarks: centroids of k-means on X u Y (Sec. 4)
     if (h.l > 0) {
-        st = run_kmeans(h, sc, h.l, lm->kmeans_iters, lm->seed, h.L, sc.assign, lm->init, lm->init_centroids);
+        st = run_kmeans(h, sc, h.l, lm->kmeans_iters, lm->seed, h.L, sc.assign, starts_landmarks, lm->init,
+                        lm->init_centroids);
         if (st != LCN_OK) return st;
     }
     // hash rounds (Sec. 3)
@@ -519,7 +558,8 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
                     st = run_hier_kmeans(h, sc, lsh->branching, h.hier_levels, lsh->kmeans_iters,
                                          lsh->seed + (uint64_t)r, dst);
                 else
-                    st = run_kmeans(h, sc, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, sc.cent, dst);
+                    st = run_kmeans(h, sc, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, sc.cent, dst,
+                                    starts_rounds + (long long)r * h.b);
                 if (st != LCN_OK) return st;
             } else if (h.and_width > 1) {
                 const int b1 = lsh->num_buckets;   // buckets of one hash; the band has b1 ^ and_width
