@@ -586,18 +586,10 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     int undecided2[2] = {0, 0};  // points sent to the exact rule over all centroids, and over two
     HIPCHK(hipMemcpyAsync(undecided2, sc.nflagged, 2 * sizeof(int), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
-    HIPCHK(hipStreamSynchronize(h.stream));
-    if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
-    h.nnz_stored = totals[0];
-    h.undecided_last = (long long)undecided2[0] + undecided2[1];
-    h.ntiles = (int)totals[1];
-
-    // 64 entries of slack: a sweep reads whole wavefront-wide chunks and masks the excess
-    h.vals_x = bump.take<float>((size_t)h.nnz_stored + 64);
-    h.vals_y = bump.take<float>((size_t)h.nnz_stored + 64);
-    h.ws_used = bump.used;
-    if (bytes_needed) *bytes_needed = bump.used + 256;
-    if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;
+    // the host needs the counts above to lay out the sparse values; the factors do not depend on
+    // them and keep the device busy while it waits
+    HIPCHK(hipEventRecord(h.ev0, h.stream));
+    drain.armed = true;
 
     // Nystrom factors (Sec. 4; App. "Implementational details")
     if (h.l > 0) {
@@ -616,6 +608,19 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         // W^T = V^T A^{-1} (A^{-1} is symmetric)
         HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, h.stream));
     }
+    HIPCHK(hipEventSynchronize(h.ev0));
+    if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
+    h.nnz_stored = totals[0];
+    h.undecided_last = (long long)undecided2[0] + undecided2[1];
+    h.ntiles = (int)totals[1];
+
+    // 64 entries of slack: a sweep reads whole wavefront-wide chunks and masks the excess
+    h.vals_x = bump.take<float>((size_t)h.nnz_stored + 64);
+    h.vals_y = bump.take<float>((size_t)h.nnz_stored + 64);
+    h.ws_used = bump.used;
+    if (bytes_needed) *bytes_needed = bump.used + 256;
+    if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;
+
     // sparse values per bucket block (Sec. 3 / Sec. 4)
     if (h.R > 0) HIPCHK(launch_correction(h, h.ntiles, h.stream));
 
