@@ -251,29 +251,24 @@ __global__ __launch_bounds__(256) void batched_build_kernel(BatchDev B)
     if (tid == 0 && fail_sh) *B.fail = 1;
 }
 
-// block-wide maximum / sum of one value per thread (256 threads), result to all
+// block-wide maximum / sum of one value per thread (256 threads = 4 wavefronts), result to all:
+// butterfly inside each wavefront, then the four results through LDS (sh: at least 4 doubles)
 __device__ inline double block_max(double v, double *sh)
 {
-    sh[threadIdx.x] = v;
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (threadIdx.x < o) sh[threadIdx.x] = fmax(sh[threadIdx.x], sh[threadIdx.x + o]);
-        __syncthreads();
-    }
-    const double r = sh[0];
+    const double r = fmax(fmax(sh[0], sh[1]), fmax(sh[2], sh[3]));
     __syncthreads();
     return r;
 }
 
 __device__ inline double block_sum(double v, double *sh)
 {
-    sh[threadIdx.x] = v;
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
-        __syncthreads();
-    }
-    const double r = sh[0];
+    const double r = (sh[0] + sh[1]) + (sh[2] + sh[3]);
     __syncthreads();
     return r;
 }
@@ -306,12 +301,15 @@ __global__ __launch_bounds__(256) void batched_run_kernel(BatchDev B, int iters,
     auto apply = [&](bool transpose, const double *logs_in, int len_in, int len_out) -> double {
         const double M = block_max(tid < len_in ? logs_in[tid] : -INFINITY, red);
         const double Ms = (M > -INFINITY && M < INFINITY) ? M : 0.0;
-        if (tid < len_in) xin[tid] = exp(logs_in[tid] - Ms);
-        __syncthreads();
+        const double x = tid < len_in ? exp(logs_in[tid] - Ms) : 0.0;
+        if (tid < len_in) xin[tid] = x;
         const int pts_in = transpose ? n : m;    // point part of the input vector
         const int pts_out = transpose ? m : n;
         double tail = 0.0;                       // sum of the deletion part of the input
-        if (B.bp) tail = block_sum((tid >= pts_in && tid < len_in) ? xin[tid] : 0.0, red);
+        if (B.bp)
+            tail = block_sum(tid >= pts_in ? x : 0.0, red);   // its barrier also publishes xin
+        else
+            __syncthreads();
         const int o = tid >> 2, part = tid & 3;
         double s = 0.0;
         if (o < pts_out) {
