@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X, published
 
 
 def make_problem(config: int):
@@ -102,6 +103,7 @@ def bench_batched(args):
     t1 = time.perf_counter()
     run_mean = float(np.mean(rms))
     P = B.num_problems
+    flops = 4.0 * float(np.sum(np.diff(B.x_off) * np.diff(B.y_off))) * B.iters
     out = {
         "metric": "batched LCN-Sinkhorn (1024 pairs): aggregate Sinkhorn iterations/s", "value": P * B.iters / (run_mean * 1e-3),
         "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -110,9 +112,12 @@ def bench_batched(args):
         "config": {"workload": "C4 1024 pairs n,m in [16,64] d=32 Euclid + deletion cost 1, l=8 b=4 it=50", "mode": "lcn"},
         "build_ms": float(np.mean(bms)), "sinkhorn_ms": run_mean, "pairs_per_s": P / (run_mean * 1e-3),
         "mean_distance": float(np.mean(dist)),
-        "roofline": {"bound": "alu", "kernel": "batched_run_kernel", "achieved": None, "peak": None, "unit": "TFLOP/s",
-                     "frac": None, "traffic": None,
-                     "note": "LDS-resident iteration, synchronisation bound; neither HBM nor MFMA"},
+        "roofline": {"bound": "alu", "kernel": "batched_run_kernel", "achieved": flops / (run_mean * 1e-3) / 1e12,
+                     "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / (run_mean * 1e-3) / 1e12 / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                     "note": "4 n m fp64 flops per pair and iteration (two products with the n x m tile); one "
+                             "wavefront per pair in registers: bound by the latency of a single instruction "
+                             "stream, neither HBM nor MFMA"},
     }
     print(json.dumps(out))
 

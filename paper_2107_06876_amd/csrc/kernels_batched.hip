@@ -19,6 +19,7 @@
 #include <new>
 #include <vector>
 
+#include "iter_common.h"   // cross-lane sums and maxima through the DPP data path
 #include "lcn_internal.h"
 
 #pragma clang fp contract(off)
@@ -80,7 +81,7 @@ __device__ inline double pair_cost(const float *x, const float *y, int d, int co
 // definition as the large path: seeded distinct start, exact-rule assignment,
 // fixed-point means, empty clusters keep their centroid.
 __device__ void block_kmeans(const float (*Z)[BD + 1], int N, int d, int k, int T, unsigned long long seed,
-                             float (*cent)[BD + 1], int *assign, int *perm)
+                             float (*cent)[BD + 1], int *assign, int *perm, unsigned long long (*sums)[BD], int *cnts)
 {
     const int tid = threadIdx.x;
     if (tid == 0) {
@@ -96,34 +97,51 @@ __device__ void block_kmeans(const float (*Z)[BD + 1], int N, int d, int k, int 
     __syncthreads();
     for (int e = tid; e < k * d; e += blockDim.x) cent[e / d][e % d] = Z[perm[e / d]][e % d];
     __syncthreads();
+    // kp lanes share a point, one candidate centroid each (k <= 16)
+    const int kp = k <= 1 ? 1 : k <= 2 ? 2 : k <= 4 ? 4 : k <= 8 ? 8 : 16;
+    const int per_pass = (int)blockDim.x / kp;
     for (int it = 0; it < T; ++it) {
-        if (tid < N) {
-            int best = 0;
-            double bestD = 0.0;
-            for (int c = 0; c < k; ++c) {
-                double s = 0.0;
+        for (int base = 0; base < N; base += per_pass) {   // same trip count in every lane
+            const int pt = base + tid / kp;
+            int bc = tid % kp;
+            double s = INFINITY;
+            if (pt < N && bc < k) {
+                s = 0.0;
                 for (int j = 0; j < d; ++j) {
-                    double t = (double)Z[tid][j] - (double)cent[c][j];
+                    double t = (double)Z[pt][j] - (double)cent[bc][j];
                     double t2 = t * t;
                     s = s + t2;
                 }
-                if (c == 0 || s < bestD) {
-                    bestD = s;
-                    best = c;
+            }
+            for (int o = 1; o < kp; o <<= 1) {   // smallest distance, lowest index among equals
+                const double os = __shfl_xor(s, o, 64);
+                const int oc = __shfl_xor(bc, o, 64);
+                if (os < s || (os == s && oc < bc)) {
+                    s = os;
+                    bc = oc;
                 }
             }
-            assign[tid] = best;
+            if (pt < N && tid % kp == 0) assign[pt] = bc;
+        }
+        for (int e = tid; e < k * BD; e += blockDim.x) sums[e / BD][e % BD] = 0ull;
+        if (tid < k) cnts[tid] = 0;
+        __syncthreads();
+        // member sums in 2^-32 fixed point (integer addition: any order gives the same sum):
+        // lane j of a 64-lane group adds dimension j of the group's share of the points
+        {
+            const int j = tid & 63, grp = tid >> 6, groups = (int)blockDim.x >> 6;
+            for (int p = grp; p < N; p += groups) {
+                const int c = assign[p];
+                if (j < d)
+                    atomicAdd(&sums[c][j], (unsigned long long)__double2ll_rn((double)Z[p][j] * 4294967296.0));
+                if (j == 0) atomicAdd(&cnts[c], 1);
+            }
         }
         __syncthreads();
         for (int e = tid; e < k * d; e += blockDim.x) {
             const int c = e / d, j = e % d;
-            long long sum = 0, cnt = 0;
-            for (int p = 0; p < N; ++p)
-                if (assign[p] == c) {
-                    sum += __double2ll_rn((double)Z[p][j] * 4294967296.0);
-                    ++cnt;
-                }
-            if (cnt > 0) cent[c][j] = (float)(((double)sum * (1.0 / 4294967296.0)) / (double)cnt);
+            const int cnt = cnts[c];
+            if (cnt > 0) cent[c][j] = (float)(((double)(long long)sums[c][j] * (1.0 / 4294967296.0)) / (double)cnt);
         }
         __syncthreads();
     }
@@ -139,6 +157,8 @@ __global__ __launch_bounds__(256) void batched_build_kernel(BatchDev B)
     __shared__ int assign[2 * BMAX];
     __shared__ int bucket[BR][2 * BMAX];
     __shared__ int perm[2 * BMAX];
+    __shared__ unsigned long long sums[BL][BD];   // k-means: member sums and counts
+    __shared__ int cnts[BL];
     __shared__ int fail_sh;
 
     const int p = blockIdx.x, tid = threadIdx.x;
@@ -157,7 +177,7 @@ __global__ __launch_bounds__(256) void batched_build_kernel(BatchDev B)
     const int l = low_rank ? B.l : 0;
 
     if (low_rank) {
-        block_kmeans(Z, N, d, l, B.T_l, B.seed_l + (unsigned long long)p, cent, assign, perm);
+        block_kmeans(Z, N, d, l, B.T_l, B.seed_l + (unsigned long long)p, cent, assign, perm, sums, cnts);
         for (int e = tid; e < l * d; e += 256) B.landmarks[((long long)p * l + e / d) * d + e % d] = cent[e / d][e % d];
         // factors in fp64
         for (int e = tid; e < n * l; e += 256) Uf[e / l][e % l] = exp(-pair_cost(Z[e / l], cent[e % l], d, B.cost) / lam);
@@ -217,7 +237,8 @@ __global__ __launch_bounds__(256) void batched_build_kernel(BatchDev B)
     }
     if (hashed) {
         for (int r = 0; r < B.R; ++r) {
-            block_kmeans(Z, N, d, B.b, B.T_b, B.seed_b + (unsigned long long)p * B.R + r, cent, assign, perm);
+            block_kmeans(Z, N, d, B.b, B.T_b, B.seed_b + (unsigned long long)p * B.R + r, cent, assign, perm, sums,
+                         cnts);
             for (int i = tid; i < N; i += 256) {
                 bucket[r][i] = assign[i];
                 B.buckets[(x0 + y0) * B.R + (long long)r * N + i] = assign[i];
@@ -251,131 +272,157 @@ __global__ __launch_bounds__(256) void batched_build_kernel(BatchDev B)
     if (tid == 0 && fail_sh) *B.fail = 1;
 }
 
-// block-wide maximum / sum of one value per thread (256 threads = 4 wavefronts), result to all:
-// butterfly inside each wavefront, then the four results through LDS (sh: at least 4 doubles)
-__device__ inline double block_max(double v, double *sh)
+__device__ inline double lane_value(double v, int src_lane)   // src_lane: a constant
 {
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    const double r = fmax(fmax(sh[0], sh[1]), fmax(sh[2], sh[3]));
-    __syncthreads();
-    return r;
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+    return __hiloint2double(hi, lo);
 }
 
-__device__ inline double block_sum(double v, double *sh)
+__device__ inline double rcp64(double x)   // 1 / x for a positive finite x, to about one unit in the last place
 {
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    const double r = (sh[0] + sh[1]) + (sh[2] + sh[3]);
-    __syncthreads();
+    double r = __builtin_amdgcn_rcp(x);
+    r = fma(fma(-x, r, 1.0), r, r);
+    r = fma(fma(-x, r, 1.0), r, r);
     return r;
 }
 
 // iters Sinkhorn iterations per pair (iters == 0: only the query part), then the
 // pair's distance and marginal residual.
-__global__ __launch_bounds__(256) void batched_run_kernel(BatchDev B, int iters, float *row_marg, float *col_marg)
+//
+// One wavefront per pair, no workgroup-wide step and no LDS anywhere.  Lane l keeps in registers row l
+// and column l of the pair's kernel tile (zero beyond n x m) and the entries of index l of
+// the scaling vectors u = [u^ (n); u~ (m)], v = [v^ (m); v~ (n)] (point part; deletion part,
+// Sec. 6).  Inside the loop a vector is held as x * 2^E with one integer E for the whole
+// vector, chosen after every update so that the largest entry lies in [1, 2): the max-shift of
+// App. "Implementational details" with the shift restricted to powers of two, which costs an
+// exponent extraction instead of an exp and a log per entry and half-iteration.  Logs are
+// formed once, when the state is stored.  In a half-iteration every lane multiplies its row
+// (or column) with the point part of the input vector, whose entries it reads from the other
+// lanes' registers one by one (lane reads, no LDS, no barrier):
+//   (K_BP v)_i     = sum_j K_ij v^_j + k_{i,eps} v~_i          (K_BP v)_{n+j}     = k_{eps,j} v^_j + sum v~
+//   (K_BP^T u)_j   = sum_i K_ij u^_i + k_{eps,j} u~_j          (K_BP^T u)_{m+i}   = k_{i,eps} u^_i + sum u~
+__global__ __launch_bounds__(64) void batched_run_kernel(BatchDev B, int iters, float *row_marg, float *col_marg)
 {
-    __shared__ float K[BMAX][BMAX + 1];
-    __shared__ double lu[2 * BMAX], lv[2 * BMAX], xin[2 * BMAX], sums[2 * BMAX];
-    __shared__ double kpe[BMAX], keq[BMAX];
-    __shared__ double red[256];
-
-    const int p = blockIdx.x, tid = threadIdx.x;
+    const double LN2 = 0.69314718055994530942;
+    const int p = blockIdx.x, lane = threadIdx.x;
     const long long x0 = B.x_off[p], y0 = B.y_off[p];
     const int n = (int)(B.x_off[p + 1] - x0), m = (int)(B.y_off[p + 1] - y0);
-    const int N = n + m;
-    const int len_u = B.bp ? N : n, len_v = B.bp ? N : m;
+    const bool bp = B.bp != 0;
+    const int len_u = bp ? n + m : n, len_v = bp ? n + m : m;
     const float *Kt = B.Kt + (long long)p * BMAX * BMAX;
-    for (int e = tid; e < n * m; e += 256) K[e / m][e % m] = Kt[(e / m) * BMAX + e % m];
-    for (int i = tid; i < n; i += 256) kpe[i] = B.bp ? B.kpe[x0 + i] : 0.0;
-    for (int j = tid; j < m; j += 256) keq[j] = B.bp ? B.keq[y0 + j] : 0.0;
-    for (int i = tid; i < len_u; i += 256) lu[i] = B.log_u[x0 + y0 + i];
-    for (int i = tid; i < len_v; i += 256) lv[i] = B.log_v[x0 + y0 + i];
-    __syncthreads();
-    const double log_a = -log((double)len_u), log_b = -log((double)len_v);  // uniform marginals
+    float Kr[BMAX], Kc[BMAX];
+#pragma unroll
+    for (int j = 0; j < BMAX; ++j) {
+        Kr[j] = (lane < n && j < m) ? Kt[lane * BMAX + j] : 0.f;
+        Kc[j] = (j < n && lane < m) ? Kt[j * BMAX + lane] : 0.f;
+    }
+    const double kpe = (bp && lane < n) ? B.kpe[x0 + lane] : 0.0;
+    const double keq = (bp && lane < m) ? B.keq[y0 + lane] : 0.0;
+    const bool has_up = lane < n, has_ud = bp && lane < m;   // this lane's entries of u (point, deletion part)
+    const bool has_vp = lane < m, has_vd = bp && lane < n;   // ... and of v
+    double *gu = B.log_u + x0 + y0, *gv = B.log_v + x0 + y0;
+    const double a_each = 1.0 / (double)len_u, b_each = 1.0 / (double)len_v;   // uniform marginals
     unsigned long long nonpos = 0;
 
-    // sums[i] = (K_BP x)_i for x = exp(lin - M) (transpose: K_BP^T); 4 threads share an output
-    auto apply = [&](bool transpose, const double *logs_in, int len_in, int len_out) -> double {
-        const double M = block_max(tid < len_in ? logs_in[tid] : -INFINITY, red);
+    // stored logs -> x * 2^E
+    auto load_vec = [&](double lp, bool hp, double ld, bool hd, double &xp, double &xd) -> int {
+        const double M = wave_max(fmax(hp ? lp : -INFINITY, hd ? ld : -INFINITY));
         const double Ms = (M > -INFINITY && M < INFINITY) ? M : 0.0;
-        const double x = tid < len_in ? exp(logs_in[tid] - Ms) : 0.0;
-        if (tid < len_in) xin[tid] = x;
-        const int pts_in = transpose ? n : m;    // point part of the input vector
-        const int pts_out = transpose ? m : n;
-        double tail = 0.0;                       // sum of the deletion part of the input
-        if (B.bp)
-            tail = block_sum(tid >= pts_in ? x : 0.0, red);   // its barrier also publishes xin
-        else
-            __syncthreads();
-        const int o = tid >> 2, part = tid & 3;
-        double s = 0.0;
-        if (o < pts_out) {
-            for (int q = part; q < pts_in; q += 4) s = fma(transpose ? (double)K[q][o] : (double)K[o][q], xin[q], s);
+        const double Ef = floor(Ms * 1.4426950408889634074);
+        xp = hp ? exp(lp - Ef * LN2) : 0.0;
+        xd = hd ? exp(ld - Ef * LN2) : 0.0;
+        return (int)Ef;
+    };
+    // largest entry into [1, 2); returns the exponent taken out (NaN entries are ignored by fmax)
+    auto renorm = [&](double &xp, double &xd) -> int {
+        const double mx = wave_max(fmax(xp, xd));
+        if (!(mx > 0.0) || !(mx < INFINITY)) return 0;
+        const int e = ilogb(mx);
+        xp = ldexp(xp, -e);
+        xd = ldexp(xd, -e);
+        return e;
+    };
+    // One product with K_BP (Kreg = rows) or its transpose (Kreg = columns) for the input held in
+    // (xp, xd): k_p / k_d is the deletion kernel value that enters this lane's point / deletion output.
+    // len_in: length of the input's point part (the tile is zero beyond it; whole sixteens are skipped).
+    auto product = [&](const float (&Kreg)[BMAX], int len_in, double xp, double xd, double k_p, double k_d,
+                       double &s_p, double &s_d) {
+        const double tail = bp ? wave_sum(xd) : 0.0;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int j0 = 0; j0 < BMAX; j0 += 16) {
+            if (j0 < len_in) {   // the same in every lane
+#pragma unroll
+                for (int j = j0; j < j0 + 16; ++j) acc[j & 3] = fma((double)Kreg[j], lane_value(xp, j), acc[j & 3]);
+            }
         }
-        s += __shfl_xor(s, 1, 64);
-        s += __shfl_xor(s, 2, 64);
-        if (part == 0 && o < pts_out) {
-            if (B.bp) s += (transpose ? keq[o] : kpe[o]) * xin[pts_in + o];
-            sums[o] = s;
-        }
-        if (B.bp && tid < pts_in) sums[pts_out + tid] = (transpose ? kpe[tid] : keq[tid]) * xin[tid] + tail;
-        __syncthreads();
-        (void)len_out;
-        return Ms;
+        s_p = (acc[0] + acc[1]) + (acc[2] + acc[3]) + k_p * xd;
+        s_d = k_d * xp + tail;
+    };
+    auto scale = [&](double marg, double s, bool exists) -> double {
+        if (!exists) return 0.0;
+        if (s > 0.0) return marg * rcp64(s);
+        ++nonpos;
+        return NAN;
     };
 
+    double xu_p = 0.0, xu_d = 0.0, xv_p, xv_d, s_p, s_d;
+    int Eu = 0;
+    int Ev = load_vec(has_vp ? gv[lane] : 0.0, has_vp, has_vd ? gv[m + lane] : 0.0, has_vd, xv_p, xv_d);
+    if (iters == 0) Eu = load_vec(has_up ? gu[lane] : 0.0, has_up, has_ud ? gu[n + lane] : 0.0, has_ud, xu_p, xu_d);
     for (int it = 0; it < iters; ++it) {
-        double M = apply(false, lv, len_v, len_u);
-        if (tid < len_u) {
-            const double s = sums[tid];
-            if (s > 0.0) {
-                lu[tid] = log_a - log(s) - M;
-            } else {
-                lu[tid] = NAN;
-                ++nonpos;
-            }
-        }
-        __syncthreads();
-        M = apply(true, lu, len_u, len_v);
-        if (tid < len_v) {
-            const double s = sums[tid];
-            if (s > 0.0) {
-                lv[tid] = log_b - log(s) - M;
-            } else {
-                lv[tid] = NAN;
-                ++nonpos;
-            }
-        }
-        __syncthreads();
+        product(Kr, m, xv_p, xv_d, kpe, keq, s_p, s_d);        // u = a ./ (K_BP v), eq. 2
+        xu_p = scale(a_each, s_p, has_up);
+        xu_d = scale(a_each, s_d, has_ud);
+        Eu = -Ev + renorm(xu_p, xu_d);
+        product(Kc, n, xu_p, xu_d, keq, kpe, s_p, s_d);        // v = b ./ (K_BP^T u)
+        xv_p = scale(b_each, s_p, has_vp);
+        xv_d = scale(b_each, s_d, has_vd);
+        Ev = -Eu + renorm(xv_p, xv_d);
     }
-    for (int i = tid; i < len_u; i += 256) B.log_u[x0 + y0 + i] = lu[i];
-    for (int i = tid; i < len_v; i += 256) B.log_v[x0 + y0 + i] = lv[i];
-    if (nonpos) atomicAdd(&B.counters[0], nonpos);
+    const double lu_p = log(xu_p) + (double)Eu * LN2, lu_d = log(xu_d) + (double)Eu * LN2;
+    const double lv_p = log(xv_p) + (double)Ev * LN2, lv_d = log(xv_d) + (double)Ev * LN2;
+    if (iters > 0) {
+        if (has_up) gu[lane] = lu_p;
+        if (has_ud) gu[n + lane] = lu_d;
+        if (has_vp) gv[lane] = lv_p;
+        if (has_vd) gv[m + lane] = lv_d;
+        nonpos = (unsigned long long)wave_sum((double)nonpos);
+        if (lane == 0 && nonpos) atomicAdd(&B.counters[0], nonpos);
+    }
 
     // marginals r = u .* (K_BP v), c = v .* (K_BP^T u); distance and residual
-    double Mv = apply(false, lv, len_v, len_u);
     double dsum = 0.0, esum = 0.0;
-    if (tid < len_u) {
-        const double r = exp(lu[tid] + Mv) * sums[tid];
-        dsum += r * lu[tid];
-        esum += fabs(r - exp(log_a));
-        if (row_marg) row_marg[x0 + y0 + tid] = (float)r;
+    product(Kr, m, xv_p, xv_d, kpe, keq, s_p, s_d);
+    if (has_up) {
+        const double r = ldexp(xu_p * s_p, Eu + Ev);
+        dsum += r * lu_p;
+        esum += fabs(r - a_each);
+        if (row_marg) row_marg[x0 + y0 + lane] = (float)r;
     }
-    __syncthreads();
-    double Mu = apply(true, lu, len_u, len_v);
-    if (tid < len_v) {
-        const double c = exp(lv[tid] + Mu) * sums[tid];
-        dsum += c * lv[tid];
-        esum += fabs(c - exp(log_b));
-        if (col_marg) col_marg[x0 + y0 + tid] = (float)c;
+    if (has_ud) {
+        const double r = ldexp(xu_d * s_d, Eu + Ev);
+        dsum += r * lu_d;
+        esum += fabs(r - a_each);
+        if (row_marg) row_marg[x0 + y0 + n + lane] = (float)r;
     }
-    __syncthreads();
-    const double D = block_sum(dsum, red);
-    const double E = block_sum(esum, red);
-    if (tid == 0) {
+    product(Kc, n, xu_p, xu_d, keq, kpe, s_p, s_d);
+    if (has_vp) {
+        const double c = ldexp(xv_p * s_p, Eu + Ev);
+        dsum += c * lv_p;
+        esum += fabs(c - b_each);
+        if (col_marg) col_marg[x0 + y0 + lane] = (float)c;
+    }
+    if (has_vd) {
+        const double c = ldexp(xv_d * s_d, Eu + Ev);
+        dsum += c * lv_d;
+        esum += fabs(c - b_each);
+        if (col_marg) col_marg[x0 + y0 + m + lane] = (float)c;
+    }
+    const double D = wave_sum(dsum);
+    const double E = wave_sum(esum);
+    if (lane == 0) {
         B.dist[p] = (double)B.lambda[p] * D;
         B.resid[p] = E;
     }
@@ -427,7 +474,7 @@ lcn_status batched_run(void *hh, int iters)
 {
     BatchHandle &h = *(BatchHandle *)hh;
     BHIPCHK(hipEventRecord(h.ev0, h.stream));
-    hipLaunchKernelGGL(batched_run_kernel, dim3(h.dev.P), dim3(256), 0, h.stream, h.dev, iters, (float *)nullptr,
+    hipLaunchKernelGGL(batched_run_kernel, dim3(h.dev.P), dim3(64), 0, h.stream, h.dev, iters, (float *)nullptr,
                        (float *)nullptr);
     BHIPCHK(hipGetLastError());
     BHIPCHK(hipEventRecord(h.ev1, h.stream));
@@ -441,7 +488,7 @@ lcn_status batched_run(void *hh, int iters)
 lcn_status batched_query(void *hh, double *dist_host, double *resid_host, float *row_dev, float *col_dev)
 {
     BatchHandle &h = *(BatchHandle *)hh;
-    hipLaunchKernelGGL(batched_run_kernel, dim3(h.dev.P), dim3(256), 0, h.stream, h.dev, 0, row_dev, col_dev);
+    hipLaunchKernelGGL(batched_run_kernel, dim3(h.dev.P), dim3(64), 0, h.stream, h.dev, 0, row_dev, col_dev);
     BHIPCHK(hipGetLastError());
     if (dist_host)
         BHIPCHK(hipMemcpyAsync(dist_host, h.dev.dist, sizeof(double) * h.dev.P, hipMemcpyDeviceToHost, h.stream));
