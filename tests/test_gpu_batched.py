@@ -141,3 +141,29 @@ def test_multi_head_unbalanced():
     # d in R^K per pair: heads of a pair differ (their lambdas do)
     d_pk = dist.reshape(-1, K)
     assert np.all(np.ptp(d_pk, axis=1) > 0)
+
+
+def test_batched_runs_resume():
+    """sinkhorn_run(20) then sinkhorn_run(30) equals sinkhorn_run(50): the state between runs is
+    the stored log scalings."""
+    import paper_2107_06876_amd as lcn
+    B = workloads.config4(pairs=64)
+    dev = "cuda:0"
+    X, Y = torch.from_numpy(B.X).to(dev), torch.from_numpy(B.Y).to(dev)
+    dx, dy = torch.from_numpy(B.del_x).to(dev), torch.from_numpy(B.del_y).to(dev)
+    lm = dict(num_landmarks=B.num_landmarks, kmeans_iters=B.kmeans_iters, seed=B.landmark_seed, ridge=B.ridge)
+    lsh = dict(num_buckets=B.num_buckets, num_rounds=1, kmeans_iters=B.kmeans_iters, seed=B.lsh_seed)
+    out = []
+    for parts in ((50,), (20, 30)):
+        h = lcn.lcn_build_batched(X, Y, B.x_off, B.y_off, B.lam, B.cost, lcn.MODE_LCN, dx, dy, landmarks=lm, lsh=lsh)
+        for it in parts:
+            lcn.sinkhorn_run(h, it)
+        dist, resid = lcn.lcn_batched_results(h)
+        dist2, _ = lcn.lcn_batched_results(h)                 # a query leaves the state alone
+        np.testing.assert_array_equal(dist, dist2)
+        st = lcn.lcn_batched_get(h)
+        out.append((dist, st["log_u"].cpu().numpy(), st["log_v"].cpu().numpy()))
+        lcn.lcn_destroy(h)
+    np.testing.assert_allclose(out[0][0], out[1][0], rtol=1e-10)
+    np.testing.assert_allclose(out[0][1], out[1][1], rtol=0, atol=1e-11)
+    np.testing.assert_allclose(out[0][2], out[1][2], rtol=0, atol=1e-11)

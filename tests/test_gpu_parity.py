@@ -275,3 +275,13 @@ def test_crosspolytope_and_construction(width):
     p.projections = workloads.projections(3, p.num_rounds * width, p.d, p.num_buckets)
     out = compare(p, "sparse", workloads.HASH_CROSSPOLYTOPE)
     print("C3r AND", width, out, flush=True)
+
+
+def test_landmarks_by_uniform_sampling():
+    """Zero Lloyd iterations from the seeded sample: uniform landmark sampling, the baseline the
+    paper compares its landmark choices with (Sec. 4)."""
+    from parity import compare
+    p = workloads.config1(n=700, d=9)
+    p.landmark_iters = 0
+    out = compare(p, "nystrom")
+    print("C1 uniform landmarks", out, flush=True)
