@@ -17,8 +17,8 @@
  *     pointers ordinary host memory.  All matrices are row-major and dense.
  *   - The caller owns every buffer it passes in, including the workspace, and
  *     must keep the workspace alive and untouched until lcn_destroy.  X, Y, a,
- *     b and the projections are read during lcn_build only (the build
- *     synchronises the stream before it returns).
+ *     b, the projections and init_centroids are read during lcn_build only
+ *     (the build synchronises the stream before it returns, also on error).
  *   - All work is enqueued on the HIP stream given to lcn_build (a
  *     hipStream_t passed as void*; NULL = the default stream).  Calls that
  *     return host scalars synchronise that stream.
@@ -146,7 +146,8 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
                      size_t *bytes_needed, lcn_handle *out);
 
 /* A ragged batch of small problems (the graph-pair workloads of Sec. 6), all
- * solved by one launch, one workgroup per problem.  Problem p owns rows
+ * built by one launch (one workgroup per problem) and iterated by one launch
+ * (one wavefront per problem).  Problem p owns rows
  * x_off[p] .. x_off[p+1] of X and y_off[p] .. y_off[p+1] of Y (at most 64 each).
  * With deletion costs the problem is the bipartite-matching form of Sec. 6:
  *   C_BP = [[C, diag(c_{p,eps})], [diag(c_{eps,q}), 0]]   ((n+m) x (m+n)),
