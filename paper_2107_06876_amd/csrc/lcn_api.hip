@@ -496,6 +496,14 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         return LCN_ERR_ALLOC;
     }
 
+    // Whichever way this function returns from here on, the stream is drained first: the caller's
+    // inputs and the host vector below are read by work that may still be in flight.
+    std::vector<long long> starts;
+    struct Drain {
+        hipStream_t s;
+        ~Drain() { (void)hipStreamSynchronize(s); }
+    } drain{h.stream};
+
     HIPCHK(hipEventCreate(&h.ev0));
     HIPCHK(hipEventCreate(&h.ev1));
     HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
@@ -510,17 +518,7 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     if (!h.exact_assign_only && (h.l > 0 || (uses_lsh(mode) && h.hash == LCN_HASH_KMEANS)))
         HIPCHK(launch_split_planes(h.Z, N, d, sc.zplanes, sc.zt, h.stream));
 
-    // seeded starts of all flat k-means runs: one upload, consumed by the stream while `starts`
-    // lives; whichever way this function returns, the stream is drained before the vector goes
-    std::vector<long long> starts;
-    struct Drain {
-        hipStream_t s;
-        bool armed;
-        ~Drain()
-        {
-            if (armed) (void)hipStreamSynchronize(s);
-        }
-    } drain{h.stream, false};
+    // seeded starts of all flat k-means runs: one upload, consumed by the stream while `starts` lives
     const long long *starts_landmarks = nullptr, *starts_rounds = nullptr;
     {
         const bool lm_sample = h.l > 0 && lm->init == LCN_INIT_SAMPLE;
@@ -536,7 +534,6 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
                 starts.insert(starts.end(), idx.begin(), idx.end());
             }
         if (!starts.empty()) {
-            drain.armed = true;
             HIPCHK(hipMemcpyAsync(sc.starts, starts.data(), sizeof(long long) * starts.size(), hipMemcpyHostToDevice,
                                   h.stream));
             if (lm_sample) starts_landmarks = sc.starts;
@@ -589,7 +586,6 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     // the host needs the counts above to lay out the sparse values; the factors do not depend on
     // them and keep the device busy while it waits
     HIPCHK(hipEventRecord(h.ev0, h.stream));
-    drain.armed = true;
 
     // Nystrom factors (Sec. 4; App. "Implementational details")
     if (h.l > 0) {
