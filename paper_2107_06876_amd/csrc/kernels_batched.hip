@@ -77,11 +77,56 @@ __device__ inline double pair_cost(const float *x, const float *y, int d, int co
     return cost == LCN_COST_EUCLID ? sqrt(s) : s;
 }
 
+// A row-major matrix in LDS whose row length is only known at launch: M[i][j].
+template <typename T>
+struct Rows {
+    T *base;
+    int stride;
+    __device__ T *operator[](int i) const { return base + i * stride; }
+};
+
+// LDS of the build kernel, sized by the batch's d, l and bucket count (not by their upper
+// limits): doubles first, then floats, then integers.
+struct BuildLds {
+    int zs, ls, kmax;   // row length of the points / centroids, of U, and the larger of l and b
+    size_t uf, vf, am, lm, li, sums, z, cent, assign, bucket, perm, cnts, fail, bytes;
+};
+
+__host__ __device__ inline BuildLds build_lds(int d, int l, int b)
+{
+    BuildLds L;
+    L.zs = d + 1;
+    L.ls = l > 0 ? l : 1;
+    L.kmax = l > b ? l : b;
+    if (L.kmax < 1) L.kmax = 1;
+    size_t at = 0;
+    auto take = [&](size_t bytes) {
+        const size_t here = at;
+        at += (bytes + 15) & ~(size_t)15;
+        return here;
+    };
+    L.uf = take(sizeof(double) * BMAX * L.ls);
+    L.vf = take(sizeof(double) * L.ls * BMAX);
+    L.am = take(sizeof(double) * L.ls * L.ls);
+    L.lm = take(sizeof(double) * L.ls * L.ls);
+    L.li = take(sizeof(double) * L.ls * L.ls);
+    L.sums = take(sizeof(unsigned long long) * L.kmax * d);
+    L.z = take(sizeof(float) * 2 * BMAX * L.zs);
+    L.cent = take(sizeof(float) * L.kmax * L.zs);
+    L.assign = take(sizeof(int) * 2 * BMAX);
+    L.bucket = take(sizeof(int) * BR * 2 * BMAX);
+    L.perm = take(sizeof(int) * 2 * BMAX);
+    L.cnts = take(sizeof(int) * L.kmax);
+    L.fail = take(sizeof(int));
+    L.bytes = at;
+    return L;
+}
+
 // Lloyd's k-means on the N points in Z (LDS) by the whole workgroup; same
 // definition as the large path: seeded distinct start, exact-rule assignment,
 // fixed-point means, empty clusters keep their centroid.
-__device__ void block_kmeans(const float (*Z)[BD + 1], int N, int d, int k, int T, unsigned long long seed,
-                             float (*cent)[BD + 1], int *assign, int *perm, unsigned long long (*sums)[BD], int *cnts)
+__device__ void block_kmeans(Rows<float> Z, int N, int d, int k, int T, unsigned long long seed, Rows<float> cent,
+                             int *assign, int *perm, Rows<unsigned long long> sums, int *cnts)
 {
     const int tid = threadIdx.x;
     if (tid == 0) {
@@ -123,7 +168,7 @@ __device__ void block_kmeans(const float (*Z)[BD + 1], int N, int d, int k, int 
             }
             if (pt < N && tid % kp == 0) assign[pt] = bc;
         }
-        for (int e = tid; e < k * BD; e += blockDim.x) sums[e / BD][e % BD] = 0ull;
+        for (int e = tid; e < k * d; e += blockDim.x) sums[e / d][e % d] = 0ull;
         if (tid < k) cnts[tid] = 0;
         __syncthreads();
         // member sums in 2^-32 fixed point (integer addition: any order gives the same sum):
@@ -149,17 +194,17 @@ __device__ void block_kmeans(const float (*Z)[BD + 1], int N, int d, int k, int 
 
 __global__ __launch_bounds__(256) void batched_build_kernel(BatchDev B)
 {
-    __shared__ float Z[2 * BMAX][BD + 1];
-    __shared__ float cent[BL][BD + 1];
-    __shared__ double Uf[BMAX][BL];     // U, then U A^{-1}
-    __shared__ double Vf[BL][BMAX];
-    __shared__ double Am[BL][BL], Lm[BL][BL], Li[BL][BL];
-    __shared__ int assign[2 * BMAX];
-    __shared__ int bucket[BR][2 * BMAX];
-    __shared__ int perm[2 * BMAX];
-    __shared__ unsigned long long sums[BL][BD];   // k-means: member sums and counts
-    __shared__ int cnts[BL];
-    __shared__ int fail_sh;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const BuildLds L = build_lds(B.d, B.l, B.b);
+    const Rows<float> Z{(float *)(lds + L.z), L.zs};            // the pair's points, X then Y
+    const Rows<float> cent{(float *)(lds + L.cent), L.zs};
+    const Rows<double> Uf{(double *)(lds + L.uf), L.ls};        // U, then U A^{-1}
+    const Rows<double> Vf{(double *)(lds + L.vf), BMAX};
+    const Rows<double> Am{(double *)(lds + L.am), L.ls}, Lm{(double *)(lds + L.lm), L.ls}, Li{(double *)(lds + L.li), L.ls};
+    const Rows<unsigned long long> sums{(unsigned long long *)(lds + L.sums), B.d};   // k-means: member sums
+    const Rows<int> bucket{(int *)(lds + L.bucket), 2 * BMAX};
+    int *assign = (int *)(lds + L.assign), *perm = (int *)(lds + L.perm), *cnts = (int *)(lds + L.cnts);
+    int &fail_sh = *(int *)(lds + L.fail);
 
     const int p = blockIdx.x, tid = threadIdx.x;
     const long long x0 = B.x_off[p], y0 = B.y_off[p];
@@ -624,7 +669,10 @@ lcn_status lcn_build_batched(const float *X, const float *Y, int32_t d, const lc
     BHIPCHK(hipMemcpyAsync(lam, desc->lambda, sizeof(float) * P, hipMemcpyHostToDevice, h.stream));
     BHIPCHK(hipMemsetAsync(D.counters, 0, 64, h.stream));
     BHIPCHK(hipMemsetAsync(D.fail, 0, 64, h.stream));
-    hipLaunchKernelGGL(batched_build_kernel, dim3(P), dim3(256), 0, h.stream, D);
+    const size_t lds_bytes = build_lds(D.d, D.l, D.b).bytes;
+    BHIPCHK(hipFuncSetAttribute((const void *)batched_build_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes));
+    hipLaunchKernelGGL(batched_build_kernel, dim3(P), dim3(256), lds_bytes, h.stream, D);
     BHIPCHK(hipGetLastError());
     int fail = 0;
     BHIPCHK(hipMemcpyAsync(&fail, D.fail, sizeof(int), hipMemcpyDeviceToHost, h.stream));
