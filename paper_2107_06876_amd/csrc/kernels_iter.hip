@@ -325,8 +325,22 @@ __global__ __launch_bounds__(PASS_THREADS) void logpass_kernel(PassSide S, int R
                     if (mc.len[r] > 64) {
                         const float *tp = vals + segoff[r];
                         const double *vp = S.perm_in + mc.vstart[r];
-#pragma unroll 2
-                        for (int e = 64 + lane; e < mc.len[r]; e += 64) lse_step((double)tp[e] + vp[e], mx, sm);
+                        // four wavefront-wide pieces per trip, all eight loads requested before the first use
+                        for (int e0 = 64 + lane; e0 < mc.len[r]; e0 += 256) {
+                            float kv[4];
+                            double pv[4];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const int e = e0 + 64 * q;
+                                const bool in = e < mc.len[r];
+                                kv[q] = in ? tp[e] : 0.f;
+                                pv[q] = in ? vp[e] : -INFINITY;
+                            }
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (e0 - lane + 64 * q < mc.len[r])   // the same in every lane: whole pieces are skipped
+                                    lse_step((double)kv[q] + pv[q], mx, sm);
+                        }
                     }
                 }
             }
@@ -371,6 +385,125 @@ __global__ __launch_bounds__(PASS_THREADS) void logpass_kernel(PassSide S, int R
         }
     }
     if (lane == 0 && empty) atomicAdd(&counters[empty_slot], empty);
+}
+
+// The dense kernel (one bucket, one round): every row multiplies the same vector, so a workgroup
+// takes DENSE_ROWS consecutive rows and reads each piece of the vector once for all of them
+// (one row per wavefront reads it once per row: twice the bytes of the kernel matrix itself,
+// from cache).  Its DENSE_WAVES wavefronts share out the columns in pieces of 128 and merge their
+// running (maximum, scaled sum) pairs through LDS.  Otherwise as logpass_kernel; PASS_INIT stays
+// with logpass_kernel.
+constexpr int DENSE_ROWS = 8;
+constexpr int DENSE_WAVES = 4;
+
+template <int MODE>
+__global__ __launch_bounds__(64 * DENSE_WAVES) void logpass_dense_kernel(PassSide S, double *partial,
+                                                                         unsigned long long *counters, int empty_slot)
+{
+    __shared__ double msh[DENSE_WAVES][DENSE_ROWS][2];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    double q0 = 0.0, q1 = 0.0;
+    unsigned long long empty = 0;
+    for (long long r0 = (long long)blockIdx.x * DENSE_ROWS; r0 < S.rows; r0 += (long long)gridDim.x * DENSE_ROWS) {
+        RowMeta<1> mt[DENSE_ROWS];
+#pragma unroll
+        for (int i = 0; i < DENSE_ROWS; ++i)   // rows past the end repeat the last row and are dropped below
+            load_meta<1, MODE>(mt[i], S, 1, r0 + i < S.rows ? r0 + i : S.rows - 1, lane);
+        const int len = mt[0].len[0];
+        const double *__restrict__ vp = S.perm_in + mt[0].vstart[0];
+        double mx[DENSE_ROWS], sm[DENSE_ROWS];
+#pragma unroll
+        for (int i = 0; i < DENSE_ROWS; ++i) {
+            mx[i] = -INFINITY;
+            sm[i] = 0.0;
+        }
+        // two wavefront-wide pieces per trip; the next trip's loads are requested before this trip's
+        // values are used
+        double pv[2], pvn[2];
+        float kv[DENSE_ROWS][2], kvn[DENSE_ROWS][2];
+        auto fetch = [&](int e0, double (&p)[2], float (&k)[DENSE_ROWS][2]) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int e = e0 + 64 * q;
+                const bool in = e < len;
+                p[q] = in ? vp[e] : -INFINITY;
+#pragma unroll
+                for (int i = 0; i < DENSE_ROWS; ++i) k[i][q] = in ? S.vals[mt[i].base + e] : 0.f;
+            }
+        };
+        fetch(128 * wave + lane, pv, kv);
+        for (int e0 = 128 * wave + lane; e0 < len; e0 += 128 * DENSE_WAVES) {
+            fetch(e0 + 128 * DENSE_WAVES, pvn, kvn);   // beyond the row: nothing is read
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int i = 0; i < DENSE_ROWS; ++i) lse_step((double)kv[i][q] + pv[q], mx[i], sm[i]);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                pv[q] = pvn[q];
+#pragma unroll
+                for (int i = 0; i < DENSE_ROWS; ++i) kv[i][q] = kvn[i][q];
+            }
+        }
+        __syncthreads();   // the previous group's merge has read msh
+#pragma unroll
+        for (int i = 0; i < DENSE_ROWS; ++i) {
+            const double M = wave_max(mx[i]);
+            const double part = mx[i] > -INFINITY ? sm[i] * exp(mx[i] - M) : 0.0;
+            const double ssum = wave_sum(part);
+            if (lane == 0) {
+                msh[wave][i][0] = M;
+                msh[wave][i][1] = ssum;
+            }
+        }
+        __syncthreads();
+        // wavefront 0, lane i finishes row r0 + i
+        if (wave == 0 && lane < DENSE_ROWS && r0 + lane < S.rows) {
+            const long long row = r0 + lane;
+            double M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < DENSE_WAVES; ++w) M = fmax(M, msh[w][lane][0]);
+            double ssum = 0.0;
+#pragma unroll
+            for (int w = 0; w < DENSE_WAVES; ++w)
+                if (msh[w][lane][0] > -INFINITY) ssum += msh[w][lane][1] * exp(msh[w][lane][0] - M);
+            const double lse = ssum > 0.0 ? M + log(ssum) : -INFINITY;
+            // this lane's row record (the registers hold it per row index, which is a lane here)
+            const int *rec = S.meta + row * S.meta_stride;
+            if (MODE == PASS_UPDATE) {
+                const double log_marg = __hiloint2double(rec[5], rec[4]);
+                double lg;
+                if (lse > -INFINITY) {
+                    lg = log_marg - lse;
+                } else {  // no kernel entry reaches this point: it carries no mass
+                    lg = -INFINITY;
+                    ++empty;
+                }
+                S.log_out[row] = (float)lg;
+                S.lin_out[row] = lg;
+                S.perm_out[rec[6 + 2 * 1]] = lg;   // one round: the row's position in the bucket order
+            } else {  // PASS_QUERY
+                const double lg = S.lin_out[row];
+                const double ri = (lg > -INFINITY && lse > -INFINITY) ? exp(lg + lse) : 0.0;
+                if (S.marg_out) S.marg_out[row] = (float)ri;
+                if (ri != 0.0) q0 += ri * lg;
+                q1 += fabs(ri - (double)__int_as_float(rec[2]));
+            }
+        }
+    }
+    if (MODE == PASS_QUERY) {
+        // only wavefront 0 holds terms, one row per lane
+        q0 = wave_sum(q0);
+        q1 = wave_sum(q1);
+        if (threadIdx.x == 0) {
+            partial[(long long)blockIdx.x * 3 + 0] = q0;
+            partial[(long long)blockIdx.x * 3 + 1] = q1;
+            partial[(long long)blockIdx.x * 3 + 2] = -INFINITY;
+        }
+    }
+    empty = (unsigned long long)wave_sum((double)empty);
+    if (threadIdx.x == 0 && empty) atomicAdd(&counters[empty_slot], empty);
 }
 
 // Adds the per-workgroup partial sums of a sweep in a fixed order (so the
@@ -567,6 +700,23 @@ static hipError_t launch_logpass(const PassSide &S, const Handle &h, int side, i
     long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
     const int grid = (int)(g < h.grid ? g : h.grid);
     const int empty_slot = 1 + side;
+    if (h.mode == LCN_MODE_DENSE && mode != PASS_INIT) {
+        const long long gd = (S.rows + DENSE_ROWS - 1) / DENSE_ROWS;
+        // a query leaves 3 partial sums per workgroup and there is room for h.grid of them; an update
+        // leaves none and may fill every compute unit with eight of these small workgroups
+        const long long cap = mode == PASS_QUERY ? (long long)h.grid : 8ll * (h.cus > 0 ? h.cus : 256);
+        const int dgrid = (int)(gd < cap ? gd : cap);
+        if (mode == PASS_UPDATE)
+            hipLaunchKernelGGL(logpass_dense_kernel<PASS_UPDATE>, dim3(dgrid), dim3(64 * DENSE_WAVES), 0, s, S, h.partial,
+                               h.counters, empty_slot);
+        else
+            hipLaunchKernelGGL(logpass_dense_kernel<PASS_QUERY>, dim3(dgrid), dim3(64 * DENSE_WAVES), 0, s, S, h.partial,
+                               h.counters, empty_slot);
+        if (mode == PASS_QUERY)
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(1024), 0, s, h.partial, dgrid, 3, 0, S.acc_out,
+                               h.query_out + 2 * side, S.shift_self, mode);
+        return hipGetLastError();
+    }
     if (h.R <= 4) {
         if (mode == PASS_UPDATE)
             hipLaunchKernelGGL((logpass_kernel<4, PASS_UPDATE>), dim3(grid), dim3(PASS_THREADS), 0, s, S, h.R,
