@@ -781,7 +781,11 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
 // completes the state; otherwise every sweep is followed by its reduction launch.
 hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s)
 {
-    const bool fused = h.fused_reduce && !h.log_domain;
+    // a sweep's first ceil((lp + 3) / 64) workgroups add up its predecessor's partial sums: a side with
+    // fewer workgroups than that (a handful of rows) cannot, and every sweep gets its reduction launch
+    const int reducers = (h.lp + 3 + 63) / 64;
+    const bool fused = h.fused_reduce && !h.log_domain && sweep_groups(h, h.n) >= reducers &&
+                       sweep_groups(h, h.m) >= reducers;
     for (int t = 0; t < 2 * iters; ++t) {
         const int side = t & 1;
         const PassSide S = make_side(h, side, side == 0 ? 0 : 1, side == 0 ? 1 : 0, nullptr);

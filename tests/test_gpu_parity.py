@@ -285,3 +285,25 @@ def test_landmarks_by_uniform_sampling():
     p.landmark_iters = 0
     out = compare(p, "nystrom")
     print("C1 uniform landmarks", out, flush=True)
+
+
+def _edge_problem(n, m, d, l, b, R, iters=15):
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    Y = (rng.standard_normal((m, d)) + 0.3).astype(np.float32)
+    C = ((X[:, None, :].astype(np.float64) - Y[None].astype(np.float64)) ** 2).sum(-1)
+    lam = float(np.float32(max(0.5 * np.median(C), 0.1)))
+    return workloads.Problem("edge", X, Y, np.full(n, 1.0 / n, np.float32), np.full(m, 1.0 / m, np.float32), lam,
+                             workloads.COST_SQEUCLID, l, b, R, iters)
+
+
+@pytest.mark.parametrize("shape", [(300, 200, 5, 7, 3, 6), (1, 1, 1, 1, 1, 1), (65, 1, 3, 2, 2, 2),
+                                   (2, 130, 2, 3, 1, 8), (129, 127, 64, 33, 5, 5)])
+@pytest.mark.parametrize("mode", ["lcn", "sparse", "nystrom", "dense"])
+def test_edge_shapes(shape, mode):
+    """Smallest and most ragged shapes: a single point per side, one landmark, one bucket, a side of
+    one point against 65 (the Nystrom part goes negative there: both sides must say so), more
+    than four hash rounds (the eight-round code path), sizes one off a multiple of 64."""
+    from parity import compare
+    out = compare(_edge_problem(*shape), mode)
+    print("edge", shape, mode, out, flush=True)
