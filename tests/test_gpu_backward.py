@@ -87,3 +87,15 @@ def test_backward_requests_that_do_not_exist_are_refused():
     st = lib.lcn_backward(h.raw, None, None, ctypes.c_void_p(g.data_ptr()), None, None, 0)
     assert st == lcn.binding.ERR_STATE
     lcn.lcn_destroy(h)
+
+
+@pytest.mark.parametrize("shape,mode", [((300, 200, 5, 7, 3, 6), "lcn"), ((300, 200, 5, 7, 3, 6), "sparse"),
+                                        ((1, 1, 1, 1, 1, 1), "lcn"), ((1, 1, 1, 1, 1, 1), "dense"),
+                                        ((40, 2600, 4, 5, 1, 1), "lcn"), ((129, 127, 64, 33, 5, 5), "lcn"),
+                                        ((2, 130, 2, 3, 1, 8), "sparse")])
+def test_backward_edge_shapes(shape, mode):
+    """Derivatives and the CSR export behind them on the smallest and most ragged shapes: a single
+    pair, six and eight hash rounds, and rows of 2600 entries (longer than the 2048 a wavefront
+    ranks in LDS, so the serial merge takes them)."""
+    from test_gpu_parity import _edge_problem
+    _run(_edge_problem(*shape), mode, 15)
