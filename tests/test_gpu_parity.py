@@ -307,3 +307,13 @@ def test_edge_shapes(shape, mode):
     from parity import compare
     out = compare(_edge_problem(*shape), mode)
     print("edge", shape, mode, out, flush=True)
+
+
+@pytest.mark.parametrize("shape,mode", [((200, 150, 8192, 9, 4, 2), "lcn"), ((2100, 2100, 3, 5, 4096, 1), "lcn"),
+                                        ((2100, 2100, 3, 5, 4096, 1), "sparse"), ((300, 300, 1, 3, 2, 1), "lcn")])
+def test_limits_of_the_parameters(shape, mode):
+    """The largest dimension (8192), the largest bucket count (4096, most of them empty) and a
+    single dimension."""
+    from parity import compare
+    out = compare(_edge_problem(*shape), mode)
+    print("limits", shape, mode, out, flush=True)
