@@ -317,3 +317,19 @@ def test_limits_of_the_parameters(shape, mode):
     from parity import compare
     out = compare(_edge_problem(*shape), mode)
     print("limits", shape, mode, out, flush=True)
+
+
+def test_new_structure_options_on_tiny_inputs():
+    """k-means++ picking every point (l = n + m), hierarchical hashing with more leaves than
+    points, an AND band on a handful of points."""
+    from parity import compare
+    p = _edge_problem(3, 2, 4, 5, 1, 1)
+    p.landmark_init, p.landmark_iters = "kmeans++", 0
+    print("tiny kmeans++", compare(p, "nystrom"), flush=True)
+    p = _edge_problem(6, 5, 2, 2, 6, 3)
+    p.branching = (2, 3)
+    print("tiny hierarchical", compare(p, "sparse"), flush=True)
+    p = _edge_problem(9, 7, 3, 2, 2, 2)
+    p.and_width = 3
+    p.projections = workloads.projections(1, p.num_rounds * 3, p.d, p.num_buckets)
+    print("tiny AND", compare(p, "sparse", workloads.HASH_CROSSPOLYTOPE), flush=True)
