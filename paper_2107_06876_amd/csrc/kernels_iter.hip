@@ -305,21 +305,23 @@ __global__ __launch_bounds__(PASS_THREADS) void logpass_kernel(PassSide S, int R
             lg = (double)S.log_out[row];
         } else {
             const float *__restrict__ vals = S.vals + mc.base;
-            double mx = -INFINITY, sm = 0.0;
-            {
-                double t0[RR];
+            // f(log kernel value, log scaling) for every stored entry of the row; a lane past the end
+            // of a piece passes a scaling of -infinity
+            auto walk = [&](auto &&f) {
+                float k0[RR];
+                double p0[RR];
                 int segoff[RR];
                 int total_len = 0;
 #pragma unroll
                 for (int r = 0; r < RR; ++r) {
                     segoff[r] = total_len;
                     total_len += mc.len[r];
-                    t0[r] = lane < mc.len[r] ? (double)vals[segoff[r] + lane] + S.perm_in[mc.vstart[r] + lane]
-                                             : -INFINITY;
+                    const bool in = lane < mc.len[r];
+                    k0[r] = in ? vals[segoff[r] + lane] : 0.f;
+                    p0[r] = in ? S.perm_in[mc.vstart[r] + lane] : -INFINITY;
                 }
-                if (next < S.rows) load_meta<RR, MODE>(mn, S, R, next, lane);
 #pragma unroll
-                for (int r = 0; r < RR; ++r) lse_step(t0[r], mx, sm);
+                for (int r = 0; r < RR; ++r) f(k0[r], p0[r]);
 #pragma unroll
                 for (int r = 0; r < RR; ++r) {
                     if (mc.len[r] > 64) {
@@ -339,15 +341,38 @@ __global__ __launch_bounds__(PASS_THREADS) void logpass_kernel(PassSide S, int R
 #pragma unroll
                             for (int q = 0; q < 4; ++q)
                                 if (e0 - lane + 64 * q < mc.len[r])   // the same in every lane: whole pieces are skipped
-                                    lse_step((double)kv[q] + pv[q], mx, sm);
+                                    f(kv[q], pv[q]);
                         }
                     }
                 }
+            };
+            // The row's log-sum-exp.  First with the row's previous value as the shift (what its current
+            // scaling was computed from: near the answer, so the terms are of order one): one subtraction,
+            // one single-precision exp and one addition per entry.  If that shift is unusable (no previous
+            // value, or the sum leaves single precision's range) the row is walked again with a running
+            // maximum per lane, which cannot over- or underflow.
+            const double prev = MODE == PASS_QUERY ? mc.lin : S.lin_out[row];
+            const double shift = mc.log_marg - prev;
+            if (next < S.rows) load_meta<RR, MODE>(mn, S, R, next, lane);
+            double lse;
+            bool done = false;
+            if (shift > -INFINITY && shift < INFINITY) {
+                float accf = 0.f;
+                walk([&](float k, double pl) { accf += __expf(k + (float)(pl - shift)); });
+                const double tot = wave_sum((double)accf);
+                if (tot > 1e-30 && tot < 1e30) {
+                    lse = shift + fast_log(tot);
+                    done = true;
+                }
             }
-            const double M = wave_max(mx);
-            const double part = mx > -INFINITY ? sm * exp(mx - M) : 0.0;
-            const double ssum = wave_sum(part);
-            const double lse = ssum > 0.0 ? M + log(ssum) : -INFINITY;
+            if (!done) {   // the same in every lane
+                double mx = -INFINITY, sm = 0.0;
+                walk([&](float k, double pl) { lse_step((double)k + pl, mx, sm); });
+                const double M = wave_max(mx);
+                const double part = mx > -INFINITY ? sm * exp(mx - M) : 0.0;
+                const double ssum = wave_sum(part);
+                lse = ssum > 0.0 ? M + log(ssum) : -INFINITY;
+            }
             if (MODE == PASS_UPDATE) {
                 if (lse > -INFINITY) {
                     lg = mc.log_marg - lse;
@@ -401,6 +426,7 @@ __global__ __launch_bounds__(64 * DENSE_WAVES) void logpass_dense_kernel(PassSid
                                                                          unsigned long long *counters, int empty_slot)
 {
     __shared__ double msh[DENSE_WAVES][DENSE_ROWS][2];
+    __shared__ int flag;   // some row of the group needs the second pass
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     double q0 = 0.0, q1 = 0.0;
@@ -412,16 +438,8 @@ __global__ __launch_bounds__(64 * DENSE_WAVES) void logpass_dense_kernel(PassSid
             load_meta<1, MODE>(mt[i], S, 1, r0 + i < S.rows ? r0 + i : S.rows - 1, lane);
         const int len = mt[0].len[0];
         const double *__restrict__ vp = S.perm_in + mt[0].vstart[0];
-        double mx[DENSE_ROWS], sm[DENSE_ROWS];
-#pragma unroll
-        for (int i = 0; i < DENSE_ROWS; ++i) {
-            mx[i] = -INFINITY;
-            sm[i] = 0.0;
-        }
         // two wavefront-wide pieces per trip; the next trip's loads are requested before this trip's
         // values are used
-        double pv[2], pvn[2];
-        float kv[DENSE_ROWS][2], kvn[DENSE_ROWS][2];
         auto fetch = [&](int e0, double (&p)[2], float (&k)[DENSE_ROWS][2]) {
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
@@ -432,43 +450,108 @@ __global__ __launch_bounds__(64 * DENSE_WAVES) void logpass_dense_kernel(PassSid
                 for (int i = 0; i < DENSE_ROWS; ++i) k[i][q] = in ? S.vals[mt[i].base + e] : 0.f;
             }
         };
-        fetch(128 * wave + lane, pv, kv);
-        for (int e0 = 128 * wave + lane; e0 < len; e0 += 128 * DENSE_WAVES) {
-            fetch(e0 + 128 * DENSE_WAVES, pvn, kvn);   // beyond the row: nothing is read
+        // f(row of the group, log kernel value, log scaling, piece) for this wavefront's share of the columns
+        auto walk = [&](auto &&f) {
+            double pv[2], pvn[2];
+            float kv[DENSE_ROWS][2], kvn[DENSE_ROWS][2];
+            fetch(128 * wave + lane, pv, kv);
+            for (int e0 = 128 * wave + lane; e0 < len; e0 += 128 * DENSE_WAVES) {
+                fetch(e0 + 128 * DENSE_WAVES, pvn, kvn);   // beyond the row: nothing is read
+                f(kv, pv);
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+                for (int q = 0; q < 2; ++q) {
+                    pv[q] = pvn[q];
 #pragma unroll
-                for (int i = 0; i < DENSE_ROWS; ++i) lse_step((double)kv[i][q] + pv[q], mx[i], sm[i]);
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                pv[q] = pvn[q];
-#pragma unroll
-                for (int i = 0; i < DENSE_ROWS; ++i) kv[i][q] = kvn[i][q];
+                    for (int i = 0; i < DENSE_ROWS; ++i) kv[i][q] = kvn[i][q];
+                }
             }
-        }
-        __syncthreads();   // the previous group's merge has read msh
+        };
+        // First pass: every row's previous log-sum-exp as its shift (see logpass_kernel), sums in single
+        // precision; shifts as one common fp64 base plus a small per-row offset.
+        double shift[DENSE_ROWS];
+        bool usable = true;
 #pragma unroll
         for (int i = 0; i < DENSE_ROWS; ++i) {
-            const double M = wave_max(mx[i]);
-            const double part = mx[i] > -INFINITY ? sm[i] * exp(mx[i] - M) : 0.0;
-            const double ssum = wave_sum(part);
-            if (lane == 0) {
-                msh[wave][i][0] = M;
-                msh[wave][i][1] = ssum;
+            const long long row = r0 + i < S.rows ? r0 + i : S.rows - 1;
+            shift[i] = mt[i].log_marg - (MODE == PASS_QUERY ? mt[i].lin : S.lin_out[row]);
+            usable = usable && shift[i] > -INFINITY && shift[i] < INFINITY;
+        }
+        __syncthreads();   // the previous group's merge has read msh and flag
+        if (usable) {   // the same in every thread
+            float off[DENSE_ROWS], accf[DENSE_ROWS];
+#pragma unroll
+            for (int i = 0; i < DENSE_ROWS; ++i) {
+                off[i] = (float)(shift[i] - shift[0]);
+                accf[i] = 0.f;
+            }
+            walk([&](const float (&kv)[DENSE_ROWS][2], const double (&pv)[2]) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const float pf = (float)(pv[q] - shift[0]);
+#pragma unroll
+                    for (int i = 0; i < DENSE_ROWS; ++i) accf[i] += __expf(kv[i][q] + (pf - off[i]));
+                }
+            });
+#pragma unroll
+            for (int i = 0; i < DENSE_ROWS; ++i) {
+                const double tot = wave_sum((double)accf[i]);
+                if (lane == 0) msh[wave][i][0] = tot;
             }
         }
+        if (threadIdx.x == 0) flag = usable ? 0 : 1;
         __syncthreads();
+        double lse = 0.0;   // wavefront 0, lane i: row r0 + i
+        if (usable && wave == 0 && lane < DENSE_ROWS) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w = 0; w < DENSE_WAVES; ++w) tot += msh[w][lane][0];
+            double sh_l = shift[0];
+#pragma unroll
+            for (int i = 1; i < DENSE_ROWS; ++i) sh_l = lane == i ? shift[i] : sh_l;
+            if (tot > 1e-30 && tot < 1e30)
+                lse = sh_l + fast_log(tot);
+            else if (r0 + lane < S.rows)
+                flag = 1;   // benign race: every writer stores 1
+        }
+        __syncthreads();
+        if (flag) {   // the same in every thread: some sum left single precision's range, walk again with running maxima
+            double mx[DENSE_ROWS], sm[DENSE_ROWS];
+#pragma unroll
+            for (int i = 0; i < DENSE_ROWS; ++i) {
+                mx[i] = -INFINITY;
+                sm[i] = 0.0;
+            }
+            walk([&](const float (&kv)[DENSE_ROWS][2], const double (&pv)[2]) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int i = 0; i < DENSE_ROWS; ++i) lse_step((double)kv[i][q] + pv[q], mx[i], sm[i]);
+            });
+#pragma unroll
+            for (int i = 0; i < DENSE_ROWS; ++i) {
+                const double M = wave_max(mx[i]);
+                const double part = mx[i] > -INFINITY ? sm[i] * exp(mx[i] - M) : 0.0;
+                const double ssum = wave_sum(part);
+                if (lane == 0) {
+                    msh[wave][i][0] = M;
+                    msh[wave][i][1] = ssum;
+                }
+            }
+            __syncthreads();
+            if (wave == 0 && lane < DENSE_ROWS) {
+                double M = -INFINITY;
+#pragma unroll
+                for (int w = 0; w < DENSE_WAVES; ++w) M = fmax(M, msh[w][lane][0]);
+                double ssum = 0.0;
+#pragma unroll
+                for (int w = 0; w < DENSE_WAVES; ++w)
+                    if (msh[w][lane][0] > -INFINITY) ssum += msh[w][lane][1] * exp(msh[w][lane][0] - M);
+                lse = ssum > 0.0 ? M + log(ssum) : -INFINITY;
+            }
+        }
         // wavefront 0, lane i finishes row r0 + i
         if (wave == 0 && lane < DENSE_ROWS && r0 + lane < S.rows) {
             const long long row = r0 + lane;
-            double M = -INFINITY;
-#pragma unroll
-            for (int w = 0; w < DENSE_WAVES; ++w) M = fmax(M, msh[w][lane][0]);
-            double ssum = 0.0;
-#pragma unroll
-            for (int w = 0; w < DENSE_WAVES; ++w)
-                if (msh[w][lane][0] > -INFINITY) ssum += msh[w][lane][1] * exp(msh[w][lane][0] - M);
-            const double lse = ssum > 0.0 ? M + log(ssum) : -INFINITY;
             // this lane's row record (the registers hold it per row index, which is a lane here)
             const int *rec = S.meta + row * S.meta_stride;
             if (MODE == PASS_UPDATE) {
