@@ -19,9 +19,11 @@
  *     must keep the workspace alive and untouched until lcn_destroy.  X, Y, a,
  *     b, the projections and init_centroids are read during lcn_build only
  *     (the build synchronises the stream before it returns, also on error).
- *   - All work is enqueued on the HIP stream given to lcn_build (a
- *     hipStream_t passed as void*; NULL = the default stream).  Calls that
- *     return host scalars synchronise that stream.
+ *   - All work is ordered on the HIP stream given to lcn_build (a
+ *     hipStream_t passed as void*; NULL = the default stream); during a build
+ *     part of it runs on a stream of the library's own that forks from and
+ *     joins that stream through events.  Calls that return host scalars
+ *     synchronise that stream.
  *   - Every function returns an lcn_status and never throws or aborts.  On
  *     LCN_ERR_INVALID_ARG nothing has been written or launched.
  *   - Same inputs and seeds give bit-identical landmarks, buckets, block

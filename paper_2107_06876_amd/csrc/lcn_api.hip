@@ -3,6 +3,7 @@
 // enqueued.  No arithmetic of the method happens on the host except the choice
 // of the k-means start indices (integer only).
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <unordered_map>
 #include <vector>
@@ -411,6 +412,22 @@ lcn_status init_state(Handle &h)
     return LCN_OK;
 }
 
+// A second stream per device for the process (default priority, not synchronising with the null
+// stream), created on first use and never destroyed; null if it cannot be had.
+hipStream_t second_stream()
+{
+    static std::mutex mu;
+    static hipStream_t streams[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!streams[dev] && hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking) != hipSuccess) {
+        (void)hipGetLastError();
+        streams[dev] = nullptr;
+    }
+    return streams[dev];
+}
+
 bool valid(lcn_handle hh) { return hh && ((Handle *)hh)->magic == HANDLE_MAGIC; }
 
 }  // namespace
@@ -479,6 +496,7 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     h.ws_bytes = workspace_bytes;
     const long long N = n + m;
 
+    bool build_overlap = true;
     {
         const char *env = getenv("LCN_PASS_GRID");
         h.grid_cap = env ? atoi(env) : 0;
@@ -486,6 +504,8 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
         h.exact_assign_only = env ? atoi(env) : 0;
         env = getenv("LCN_FUSED_REDUCE");
         h.fused_reduce = env ? atoi(env) : 1;
+        env = getenv("LCN_BUILD_OVERLAP");
+        build_overlap = env ? atoi(env) != 0 : true;
         h.cus = device_compute_units();
     }
     Bump bump{h.ws, workspace_bytes, 0, false};
@@ -500,9 +520,13 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     // inputs and the host vector below are read by work that may still be in flight.
     std::vector<long long> starts;
     struct Drain {
-        hipStream_t s;
-        ~Drain() { (void)hipStreamSynchronize(s); }
-    } drain{h.stream};
+        hipStream_t s, aux;
+        ~Drain()
+        {
+            if (aux) (void)hipStreamSynchronize(aux);
+            (void)hipStreamSynchronize(s);
+        }
+    } drain{h.stream, build_overlap ? second_stream() : nullptr};
 
     HIPCHK(hipEventCreate(&h.ev0));
     HIPCHK(hipEventCreate(&h.ev1));
@@ -546,6 +570,36 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
                         lm->init_centroids);
         if (st != LCN_OK) return st;
     }
+    bool factors_forked = false;
+    // Nystrom factors (Sec. 4; App. "Implementational details").  They need the landmarks only, so they
+    // run on a second stream beside the hash rounds (many short launches that leave most of the
+    // device idle); the sparse values below wait for them.
+    if (h.l > 0) {
+        hipStream_t fs = h.stream;
+        if (drain.aux) {
+            HIPCHK(hipEventRecord(h.ev1, h.stream));
+            HIPCHK(hipStreamWaitEvent(drain.aux, h.ev1, 0));
+            fs = drain.aux;
+        }
+        const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
+        const bool cosn = cost == LCN_COST_COSINE;
+        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, fs));
+        HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, fs));
+        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
+        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
+                                    h.U, nullptr, h.lp, fs));
+        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, fs));
+        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, fs));
+        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
+        // W^T = V^T A^{-1} (A^{-1} is symmetric)
+        HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, fs));
+        if (drain.aux) {
+            HIPCHK(hipEventRecord(h.ev1, drain.aux));
+            factors_forked = true;
+        }
+    }
     // hash rounds (Sec. 3)
     if (uses_lsh(mode)) {
         for (int r = 0; r < h.R; ++r) {
@@ -587,23 +641,6 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     // them and keep the device busy while it waits
     HIPCHK(hipEventRecord(h.ev0, h.stream));
 
-    // Nystrom factors (Sec. 4; App. "Implementational details")
-    if (h.l > 0) {
-        const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
-        const bool cosn = cost == LCN_COST_COSINE;
-        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, h.stream));
-        HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, h.stream));
-        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, h.stream));
-        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
-                                    h.U, nullptr, h.lp, h.stream));
-        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, h.stream));
-        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, h.stream));
-        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, h.stream));
-        // W^T = V^T A^{-1} (A^{-1} is symmetric)
-        HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, h.stream));
-    }
     HIPCHK(hipEventSynchronize(h.ev0));
     if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
     h.nnz_stored = totals[0];
@@ -617,6 +654,7 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     if (bytes_needed) *bytes_needed = bump.used + 256;
     if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;
 
+    if (factors_forked) HIPCHK(hipStreamWaitEvent(h.stream, h.ev1, 0));
     // sparse values per bucket block (Sec. 3 / Sec. 4)
     if (h.R > 0) HIPCHK(launch_correction(h, h.ntiles, h.stream));
 
