@@ -21,8 +21,9 @@
  *     (the build synchronises the stream before it returns, also on error).
  *   - All work is ordered on the HIP stream given to lcn_build (a
  *     hipStream_t passed as void*; NULL = the default stream); during a build
- *     part of it runs on a stream of the library's own that forks from and
- *     joins that stream through events.  Calls that return host scalars
+ *     parts of it run on streams of the library's own that fork from and
+ *     join that stream through events, enqueued by short-lived host threads
+ *     that end before lcn_build returns.  Calls that return host scalars
  *     synchronise that stream.
  *   - Every function returns an lcn_status and never throws or aborts.  On
  *     LCN_ERR_INVALID_ARG nothing has been written or launched.

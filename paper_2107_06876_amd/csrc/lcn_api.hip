@@ -5,6 +5,7 @@
 #include <cstdlib>
 #include <mutex>
 #include <new>
+#include <thread>
 #include <unordered_map>
 #include <vector>
 
@@ -64,23 +65,30 @@ std::vector<long long> seeded_indices(uint64_t seed, long long N, int k)
 bool uses_landmarks(int mode) { return mode == LCN_MODE_NYSTROM || mode == LCN_MODE_LCN; }
 bool uses_lsh(int mode) { return mode == LCN_MODE_SPARSE || mode == LCN_MODE_LCN; }
 
-struct Scratch {  // build-only buffers
+constexpr int KM_LANES = 4;   // k-means runs of a build that may be in flight together
+
+struct KmScratch {  // what one k-means run needs for itself
     long long *idx;
-    long long *starts;  // seeded start indices of every k-means run of the build: landmarks, then one set per round
     float *cent;
     int *counts2, *cursor2, *order, *offs;  // k-means update: [2][kmax], [2][kmax], [N], [kmax]
     int32_t *assign;
-    double *Vt64, *A64, *Lt, *Li, *Ainv, *ln, *Dinv, *Tm;
-    int *fail_flag;
-    long long *totals;
     float *cn;
     unsigned *cmax_bits;
     int *flagged, *nflagged, *pairs;
     unsigned long long *pp_state;  // k-means++: bits of the largest squared norm
     int *horder, *hchunks, *nchild;  // hierarchical k-means: points grouped by parent, chunk list, children per parent
     double *hcent;                   // ... and the children's centroids as fp64, [parent][dimension][child padded]
-    char *zt, *ct;  // bf16 planes of the points and of the centroids (assignment filter)
+    char *ct;                        // bf16 planes of the centroids (assignment filter)
+};
+
+struct Scratch {  // build-only buffers
+    long long *starts;  // seeded start indices of every k-means run of the build: landmarks, then one set per round
+    double *Vt64, *A64, *Lt, *Li, *Ainv, *ln, *Dinv, *Tm;
+    int *fail_flag;
+    long long *totals;
+    char *zt;  // bf16 planes of the points (assignment filter)
     int zplanes;
+    KmScratch km[KM_LANES];
 };
 
 // Lays out everything except the sparse values.  With bump.dry only sizes are
@@ -98,32 +106,35 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     sc.fail_flag = bump.take<int>(4);
     sc.totals = bump.take<long long>(4);
     h.L = bump.take<float>((size_t)(h.l > 0 ? h.l : 1) * h.d);
-    sc.idx = bump.take<long long>((size_t)kmax);
     sc.starts = bump.take<long long>((size_t)(h.l > 0 ? h.l : 1) + (size_t)(h.R > 0 ? h.R : 1) * (size_t)h.b);
-    sc.cent = bump.take<float>((size_t)kmax * h.d);
-    // counts2 .. nflagged are cleared together at the start of a k-means run
-    sc.counts2 = bump.take<int>(2 * (size_t)kmax);
-    sc.cursor2 = bump.take<int>(2 * (size_t)kmax);
-    sc.cmax_bits = bump.take<unsigned>(4);
-    sc.nflagged = bump.take<int>(4);
-    sc.order = bump.take<int>((size_t)N);
-    sc.offs = bump.take<int>((size_t)kmax);
-    sc.assign = bump.take<int32_t>((size_t)N);
-    sc.cn = bump.take<float>((size_t)kmax);
     // bf16 planes for the assignment filter: points (one plane if the input was bf16), centroids
     sc.zplanes = h.in_dtype == LCN_BF16 ? 1 : 2;
     sc.zt = bump.take<char>((size_t)sc.zplanes * split_plane_bytes(N, h.d));
-    sc.ct = bump.take<char>(2 * split_plane_bytes(kmax, h.d));
-    sc.pp_state = bump.take<unsigned long long>(4);
-    if (h.hier_levels > 1) {
-        sc.horder = bump.take<int>((size_t)N);
-        sc.hchunks = bump.take<int>(3 * ((size_t)N / 64 + (size_t)kmax + 1));
-        sc.nchild = bump.take<int>((size_t)kmax);
-        // parents * padded children <= 8 * buckets (a level of fewer than 4 children is padded to 4)
-        sc.hcent = bump.take<double>(8 * (size_t)h.b * h.d);
+    for (int q = 0; q < KM_LANES; ++q) {
+        KmScratch &km = sc.km[q];
+        km.idx = bump.take<long long>((size_t)kmax);
+        km.cent = bump.take<float>((size_t)kmax * h.d);
+        // counts2 .. nflagged are cleared together at the start of a k-means run
+        km.counts2 = bump.take<int>(2 * (size_t)kmax);
+        km.cursor2 = bump.take<int>(2 * (size_t)kmax);
+        km.cmax_bits = bump.take<unsigned>(4);
+        km.nflagged = bump.take<int>(4);
+        km.order = bump.take<int>((size_t)N);
+        km.offs = bump.take<int>((size_t)kmax);
+        km.assign = bump.take<int32_t>((size_t)N);
+        km.cn = bump.take<float>((size_t)kmax);
+        km.ct = bump.take<char>(2 * split_plane_bytes(kmax, h.d));
+        km.pp_state = bump.take<unsigned long long>(4);
+        if (h.hier_levels > 1) {
+            km.horder = bump.take<int>((size_t)N);
+            km.hchunks = bump.take<int>(3 * ((size_t)N / 64 + (size_t)kmax + 1));
+            km.nchild = bump.take<int>((size_t)kmax);
+            // parents * padded children <= 8 * buckets (a level of fewer than 4 children is padded to 4)
+            km.hcent = bump.take<double>(8 * (size_t)h.b * h.d);
+        }
+        km.flagged = bump.take<int>((size_t)N + 8);  // also the k-means++ sweep's 64-bit totals, one per 64 points
+        km.pairs = bump.take<int>(3 * (size_t)N);
     }
-    sc.flagged = bump.take<int>((size_t)N + 8);  // also the k-means++ sweep's 64-bit totals, one per 64 points
-    sc.pairs = bump.take<int>(3 * (size_t)N);
     h.bucket = bump.take<int32_t>((size_t)(h.R > 0 ? h.R : 1) * N);
 
     SortBuffers &B = h.sort;
@@ -279,46 +290,48 @@ void fill_shape(Handle &h, long long n, long long m, int d, int mode, const lcn_
 // T Lloyd iterations on Z from the start `init` names (LCN_INIT_*): centroids into cent, the last
 // iteration's assignment into assign (untouched if T == 0).
 // start_dev (nullable): the k seeded start indices, already on the device (LCN_INIT_SAMPLE only).
-lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float *cent, int32_t *assign,
-                      const long long *start_dev = nullptr, int init = LCN_INIT_SAMPLE, const float *given = nullptr)
+// km: the run's own scratch; s: the stream it is ordered on.
+lcn_status run_kmeans(Handle &h, Scratch &sc, KmScratch &km, hipStream_t s, int k, int T, uint64_t seed, float *cent,
+                      int32_t *assign, const long long *start_dev = nullptr, int init = LCN_INIT_SAMPLE,
+                      const float *given = nullptr)
 {
     const long long N = h.n + h.m;
     if (init == LCN_INIT_GIVEN) {
-        HIPCHK(hipMemcpyAsync(cent, given, sizeof(float) * (size_t)k * h.d, hipMemcpyDeviceToDevice, h.stream));
+        HIPCHK(hipMemcpyAsync(cent, given, sizeof(float) * (size_t)k * h.d, hipMemcpyDeviceToDevice, s));
     } else if (init == LCN_INIT_KMEANSPP) {
         std::vector<unsigned long long> rnd((size_t)k);
         uint64_t st = seed;
         for (int t = 0; t < k; ++t) rnd[(size_t)t] = splitmix64(st);
-        HIPCHK(hipMemcpyAsync(sc.idx, rnd.data(), sizeof(unsigned long long) * (size_t)k, hipMemcpyHostToDevice,
-                              h.stream));
-        HIPCHK(hipStreamSynchronize(h.stream));  // rnd is a local host vector
+        HIPCHK(hipMemcpyAsync(km.idx, rnd.data(), sizeof(unsigned long long) * (size_t)k, hipMemcpyHostToDevice,
+                              s));
+        HIPCHK(hipStreamSynchronize(s));  // rnd is a local host vector
         // the assignment's buffers are free until the first Lloyd iteration
-        HIPCHK(launch_kmeanspp(h.Z, N, h.d, k, (const unsigned long long *)sc.idx, (double *)sc.pairs,
-                               (unsigned long long *)sc.flagged, sc.order, sc.pp_state, cent, h.stream));
+        HIPCHK(launch_kmeanspp(h.Z, N, h.d, k, (const unsigned long long *)km.idx, (double *)km.pairs,
+                               (unsigned long long *)km.flagged, km.order, km.pp_state, cent, s));
     } else if (start_dev) {
-        HIPCHK(launch_gather_rows(h.Z, h.d, start_dev, k, cent, h.stream));
+        HIPCHK(launch_gather_rows(h.Z, h.d, start_dev, k, cent, s));
     } else {
         std::vector<long long> idx = seeded_indices(seed, N, k);
-        HIPCHK(hipMemcpyAsync(sc.idx, idx.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
-        HIPCHK(hipStreamSynchronize(h.stream));  // idx is a local host vector
-        HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, k, cent, h.stream));
+        HIPCHK(hipMemcpyAsync(km.idx, idx.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, s));
+        HIPCHK(hipStreamSynchronize(s));  // idx is a local host vector
+        HIPCHK(launch_gather_rows(h.Z, h.d, km.idx, k, cent, s));
     }
     // member counts and cursors of the update, the filter's largest centroid norm and its two
     // counters lie side by side: one clear
-    HIPCHK(hipMemsetAsync(sc.counts2, 0, (size_t)((char *)(sc.nflagged + 4) - (char *)sc.counts2), h.stream));
+    HIPCHK(hipMemsetAsync(km.counts2, 0, (size_t)((char *)(km.nflagged + 4) - (char *)km.counts2), s));
     for (int it = 0; it < T; ++it) {
         if (h.exact_assign_only) {
-            HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, h.stream));
+            HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, nullptr, nullptr, s));
         } else {
-            HIPCHK(launch_assign_filter(sc.zt, sc.zplanes, N, h.d, cent, k, sc.ct, h.zn, sc.cn, sc.cmax_bits, assign,
-                                        sc.flagged, sc.pairs, sc.nflagged, h.stream));
+            HIPCHK(launch_assign_filter(sc.zt, sc.zplanes, N, h.d, cent, k, km.ct, h.zn, km.cn, km.cmax_bits, assign,
+                                        km.flagged, km.pairs, km.nflagged, s));
             if (filter_uses_pairs(k))
-                HIPCHK(launch_assign_pairs(h.Z, h.d, cent, assign, sc.pairs, sc.nflagged + 1, h.stream));
-            HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, sc.flagged, sc.nflagged, h.stream));
+                HIPCHK(launch_assign_pairs(h.Z, h.d, cent, assign, km.pairs, km.nflagged + 1, s));
+            HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, km.flagged, km.nflagged, s));
         }
         // the last iteration leaves the count of undecided points in place for lcn_get_info
-        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, sc.counts2, sc.cursor2, sc.order, sc.offs, it, cent, sc.cmax_bits,
-                                    it + 1 < T ? sc.nflagged : nullptr, h.stream));
+        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, km.counts2, km.cursor2, km.order, km.offs, it, cent, km.cmax_bits,
+                                    it + 1 < T ? km.nflagged : nullptr, s));
     }
     return LCN_OK;
 }
@@ -328,11 +341,11 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, int k, int T, uint64_t seed, float
 // order; fewer members than that: one cluster per member), seeded with seed + j * 2^32 + parent.
 // bucket = parent * branching[j] + child.  The grouping by parent and the seeded starts are made on
 // the host from a copy of the level above (one synchronisation per level).
-lcn_status run_hier_kmeans(Handle &h, Scratch &sc, const int32_t *branching, int levels, int T, uint64_t seed,
-                           int32_t *dst)
+lcn_status run_hier_kmeans(Handle &h, Scratch &sc, KmScratch &km, hipStream_t s, const int32_t *branching, int levels,
+                           int T, uint64_t seed, int32_t *dst)
 {
     const long long N = h.n + h.m;
-    lcn_status st = run_kmeans(h, sc, branching[0], T, seed, sc.cent, dst);
+    lcn_status st = run_kmeans(h, sc, km, s, branching[0], T, seed, km.cent, dst);
     if (st != LCN_OK) return st;
     long long parents = branching[0];
     std::vector<int32_t> ids((size_t)N);
@@ -341,8 +354,8 @@ lcn_status run_hier_kmeans(Handle &h, Scratch &sc, const int32_t *branching, int
     for (int lev = 1; lev < levels; ++lev) {
         const int bl = branching[lev];
         const long long k = parents * bl;
-        HIPCHK(hipMemcpyAsync(ids.data(), dst, sizeof(int32_t) * (size_t)N, hipMemcpyDeviceToHost, h.stream));
-        HIPCHK(hipStreamSynchronize(h.stream));
+        HIPCHK(hipMemcpyAsync(ids.data(), dst, sizeof(int32_t) * (size_t)N, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
         offs.assign((size_t)parents + 1, 0);
         for (long long i = 0; i < N; ++i) offs[(size_t)ids[(size_t)i] + 1] += 1;
         for (long long c = 0; c < parents; ++c) offs[(size_t)c + 1] += offs[(size_t)c];
@@ -368,21 +381,21 @@ lcn_status run_hier_kmeans(Handle &h, Scratch &sc, const int32_t *branching, int
             }
         }
         const int nchunks = (int)(chunks.size() / 3);
-        HIPCHK(hipMemcpyAsync(sc.idx, start.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, h.stream));
-        HIPCHK(hipMemcpyAsync(sc.nchild, nchild.data(), sizeof(int) * (size_t)parents, hipMemcpyHostToDevice,
-                              h.stream));
-        HIPCHK(hipMemcpyAsync(sc.horder, order.data(), sizeof(int) * (size_t)N, hipMemcpyHostToDevice, h.stream));
-        HIPCHK(hipMemcpyAsync(sc.hchunks, chunks.data(), sizeof(int) * chunks.size(), hipMemcpyHostToDevice,
-                              h.stream));
-        HIPCHK(hipStreamSynchronize(h.stream));  // the host vectors are reused by the next level
-        HIPCHK(launch_gather_rows(h.Z, h.d, sc.idx, (int)k, sc.cent, h.stream));
-        HIPCHK(hipMemsetAsync(sc.counts2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
-        HIPCHK(hipMemsetAsync(sc.cursor2, 0, 2 * sizeof(int) * (size_t)k, h.stream));
+        HIPCHK(hipMemcpyAsync(km.idx, start.data(), sizeof(long long) * (size_t)k, hipMemcpyHostToDevice, s));
+        HIPCHK(hipMemcpyAsync(km.nchild, nchild.data(), sizeof(int) * (size_t)parents, hipMemcpyHostToDevice,
+                              s));
+        HIPCHK(hipMemcpyAsync(km.horder, order.data(), sizeof(int) * (size_t)N, hipMemcpyHostToDevice, s));
+        HIPCHK(hipMemcpyAsync(km.hchunks, chunks.data(), sizeof(int) * chunks.size(), hipMemcpyHostToDevice,
+                              s));
+        HIPCHK(hipStreamSynchronize(s));  // the host vectors are reused by the next level
+        HIPCHK(launch_gather_rows(h.Z, h.d, km.idx, (int)k, km.cent, s));
+        HIPCHK(hipMemsetAsync(km.counts2, 0, 2 * sizeof(int) * (size_t)k, s));
+        HIPCHK(hipMemsetAsync(km.cursor2, 0, 2 * sizeof(int) * (size_t)k, s));
         for (int it = 0; it < T; ++it) {
-            HIPCHK(launch_assign_children(h.Z, h.d, sc.cent, parents, bl, sc.nchild, sc.horder, sc.hchunks, nchunks,
-                                          sc.hcent, dst, h.stream));
-            HIPCHK(launch_kmeans_update(h.Z, N, h.d, dst, (int)k, sc.counts2, sc.cursor2, sc.order, sc.offs, it,
-                                        sc.cent, nullptr, nullptr, h.stream));
+            HIPCHK(launch_assign_children(h.Z, h.d, km.cent, parents, bl, km.nchild, km.horder, km.hchunks, nchunks,
+                                          km.hcent, dst, s));
+            HIPCHK(launch_kmeans_update(h.Z, N, h.d, dst, (int)k, km.counts2, km.cursor2, km.order, km.offs, it,
+                                        km.cent, nullptr, nullptr, s));
         }
         parents = k;
     }
@@ -412,20 +425,28 @@ lcn_status init_state(Handle &h)
     return LCN_OK;
 }
 
-// A second stream per device for the process (default priority, not synchronising with the null
-// stream), created on first use and never destroyed; null if it cannot be had.
-hipStream_t second_stream()
+// KM_LANES streams per device for the process (default priority, not synchronising with the null
+// stream), created on first use and never destroyed.  False if they cannot be had.
+bool lane_streams(hipStream_t (&out)[KM_LANES])
 {
     static std::mutex mu;
-    static hipStream_t streams[64] = {};
+    static hipStream_t streams[64][KM_LANES] = {};
+    static bool ready[64] = {};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
     std::lock_guard<std::mutex> lock(mu);
-    if (!streams[dev] && hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking) != hipSuccess) {
-        (void)hipGetLastError();
-        streams[dev] = nullptr;
+    if (!ready[dev]) {
+        for (int q = 0; q < KM_LANES; ++q) {
+            if (!streams[dev][q] && hipStreamCreateWithFlags(&streams[dev][q], hipStreamNonBlocking) != hipSuccess) {
+                (void)hipGetLastError();
+                streams[dev][q] = nullptr;
+                return false;
+            }
+        }
+        ready[dev] = true;
     }
-    return streams[dev];
+    for (int q = 0; q < KM_LANES; ++q) out[q] = streams[dev][q];
+    return true;
 }
 
 bool valid(lcn_handle hh) { return hh && ((Handle *)hh)->magic == HANDLE_MAGIC; }
@@ -520,20 +541,34 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     // inputs and the host vector below are read by work that may still be in flight.
     std::vector<long long> starts;
     struct Drain {
-        hipStream_t s, aux;
+        hipStream_t s;
+        hipStream_t lane[KM_LANES];
+        bool forked;
+        hipEvent_t join[KM_LANES], extra[2];
         ~Drain()
         {
-            if (aux) (void)hipStreamSynchronize(aux);
+            for (int q = 0; q < KM_LANES; ++q) {
+                if (forked) (void)hipStreamSynchronize(lane[q]);
+                if (join[q]) (void)hipEventDestroy(join[q]);
+            }
+            for (int q = 0; q < 2; ++q)
+                if (extra[q]) (void)hipEventDestroy(extra[q]);
             (void)hipStreamSynchronize(s);
         }
-    } drain{h.stream, build_overlap ? second_stream() : nullptr};
+    } drain{h.stream, {}, false, {}, {}};
+    // The k-means runs of a build (landmarks, one per hash round) are independent chains of short
+    // launches; each gets a stream of the library's own (forked from and joined into the caller's
+    // stream by events) and scratch of its own, so that they fill the device together.
+    drain.forked = build_overlap && lane_streams(drain.lane);
+    if (!drain.forked)
+        for (int q = 0; q < KM_LANES; ++q) drain.lane[q] = h.stream;
+    bool lane_used[KM_LANES] = {};
 
     HIPCHK(hipEventCreate(&h.ev0));
     HIPCHK(hipEventCreate(&h.ev1));
     HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
     HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
     HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
-    HIPCHK(hipMemsetAsync(sc.nflagged, 0, 4 * sizeof(int), h.stream));
     HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
     HIPCHK(hipMemcpyAsync(h.b_marg, b, sizeof(float) * (size_t)m, hipMemcpyDeviceToDevice, h.stream));
     HIPCHK(launch_convert(X, n, Y, m, d, dtype, h.Z, (unsigned *)(h.counters + 4), h.stream));
@@ -564,68 +599,136 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
             if (flat_rounds) starts_rounds = sc.starts + rounds_at;
         }
     }
-    // landmarks: centroids of k-means on X u Y (Sec. 4)
-    if (h.l > 0) {
-        st = run_kmeans(h, sc, h.l, lm->kmeans_iters, lm->seed, h.L, sc.assign, starts_landmarks, lm->init,
-                        lm->init_centroids);
-        if (st != LCN_OK) return st;
-    }
-    bool factors_forked = false;
-    // Nystrom factors (Sec. 4; App. "Implementational details").  They need the landmarks only, so they
-    // run on a second stream beside the hash rounds (many short launches that leave most of the
-    // device idle); the sparse values below wait for them.
-    if (h.l > 0) {
-        hipStream_t fs = h.stream;
-        if (drain.aux) {
-            HIPCHK(hipEventRecord(h.ev1, h.stream));
-            HIPCHK(hipStreamWaitEvent(drain.aux, h.ev1, 0));
-            fs = drain.aux;
+    if (drain.forked) {
+        HIPCHK(hipEventRecord(h.ev1, h.stream));
+        for (int q = 0; q < KM_LANES; ++q) {
+            HIPCHK(hipEventCreateWithFlags(&drain.join[q], hipEventDisableTiming));
+            HIPCHK(hipStreamWaitEvent(drain.lane[q], h.ev1, 0));
         }
-        const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
-        const bool cosn = cost == LCN_COST_COSINE;
-        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, fs));
-        HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, fs));
-        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
-        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
-                                    h.U, nullptr, h.lp, fs));
-        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, fs));
-        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, fs));
-        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
-        // W^T = V^T A^{-1} (A^{-1} is symmetric)
-        HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, fs));
-        if (drain.aux) {
-            HIPCHK(hipEventRecord(h.ev1, drain.aux));
-            factors_forked = true;
-        }
+        for (int q = 0; q < 2; ++q) HIPCHK(hipEventCreateWithFlags(&drain.extra[q], hipEventDisableTiming));
     }
-    // hash rounds (Sec. 3)
-    if (uses_lsh(mode)) {
+    const int *last_nflagged = nullptr;   // the undecided counts of the build's last k-means run
+    // hash rounds (Sec. 3).  The host needs about as long to enqueue one of the short launches of a
+    // k-means run as the device to execute it, so runs only overlap if they are enqueued at the same
+    // time: with the lanes in use every lane's rounds are enqueued by a thread of their own while
+    // this thread goes on with the landmarks' factors.
+    auto lane_of_round = [&](int r) { return h.l > 0 ? 1 + r % (KM_LANES - 1) : r % KM_LANES; };
+    auto rounds_of_lane = [&](int q) -> lcn_status {
         for (int r = 0; r < h.R; ++r) {
+            if (lane_of_round(r) != q) continue;
             int32_t *dst = h.bucket + (long long)r * N;
+            KmScratch &km = sc.km[q];
+            hipStream_t ls = drain.lane[q];
             if (h.hash == LCN_HASH_KMEANS) {
+                lcn_status rs;
                 if (h.hier_levels > 1)
-                    st = run_hier_kmeans(h, sc, lsh->branching, h.hier_levels, lsh->kmeans_iters,
+                    rs = run_hier_kmeans(h, sc, km, ls, lsh->branching, h.hier_levels, lsh->kmeans_iters,
                                          lsh->seed + (uint64_t)r, dst);
                 else
-                    st = run_kmeans(h, sc, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, sc.cent, dst,
+                    rs = run_kmeans(h, sc, km, ls, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, km.cent, dst,
                                     starts_rounds + (long long)r * h.b);
-                if (st != LCN_OK) return st;
+                if (rs != LCN_OK) return rs;
             } else if (h.and_width > 1) {
                 const int b1 = lsh->num_buckets;   // buckets of one hash; the band has b1 ^ and_width
                 for (int j = 0; j < h.and_width; ++j) {
                     const float *Rm = lsh->projections + ((long long)r * h.and_width + j) * d * (b1 / 2);
-                    HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, b1, sc.assign, h.stream));
-                    HIPCHK(launch_combine_hash(dst, sc.assign, b1, j == 0, N, h.stream));
+                    HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, b1, km.assign, ls));
+                    HIPCHK(launch_combine_hash(dst, km.assign, b1, j == 0, N, ls));
                 }
             } else {
                 const float *Rm = lsh->projections + (long long)r * d * (h.b / 2);
-                HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, h.b, dst, h.stream));
+                HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, h.b, dst, ls));
+            }
+        }
+        return LCN_OK;
+    };
+    struct Workers {   // joined before the streams are drained, whichever way this function returns
+        std::thread t[KM_LANES];
+        lcn_status st[KM_LANES];
+        void join_all()
+        {
+            for (int q = 0; q < KM_LANES; ++q)
+                if (t[q].joinable()) t[q].join();
+        }
+        ~Workers() { join_all(); }
+    } workers;
+    for (int q = 0; q < KM_LANES; ++q) workers.st[q] = LCN_OK;
+    int device_id = 0;
+    (void)hipGetDevice(&device_id);
+    if (uses_lsh(mode)) {
+        for (int r = 0; r < h.R; ++r) lane_used[lane_of_round(r)] = true;
+        if (h.hash == LCN_HASH_KMEANS && h.R > 0) last_nflagged = sc.km[lane_of_round(h.R - 1)].nflagged;
+        const bool threaded = drain.forked && h.hash == LCN_HASH_KMEANS;
+        for (int q = 0; q < KM_LANES; ++q) {
+            bool has_round = false;
+            for (int r = 0; r < h.R; ++r) has_round = has_round || lane_of_round(r) == q;
+            if (!has_round) continue;
+            if (threaded) {
+                workers.t[q] = std::thread([&, q]() {
+                    (void)hipSetDevice(device_id);
+                    workers.st[q] = rounds_of_lane(q);
+                });
+            } else {
+                st = rounds_of_lane(q);
+                if (st != LCN_OK) return st;
             }
         }
     } else if (mode == LCN_MODE_DENSE) {
         HIPCHK(hipMemsetAsync(h.bucket, 0, sizeof(int32_t) * (size_t)N, h.stream));
+    }
+    // landmarks: centroids of k-means on X u Y (Sec. 4)
+    if (h.l > 0) {
+        st = run_kmeans(h, sc, sc.km[0], drain.lane[0], h.l, lm->kmeans_iters, lm->seed, h.L, sc.km[0].assign,
+                        starts_landmarks, lm->init, lm->init_centroids);
+        if (st != LCN_OK) return st;
+        lane_used[0] = true;
+        if (!last_nflagged) last_nflagged = sc.km[0].nflagged;
+    }
+    // Nystrom factors (Sec. 4; App. "Implementational details").  They need the landmarks only and run
+    // beside the hash rounds: A and its inverse follow the landmarks on lane 0, U and V go to lanes 1
+    // and 2 (behind the hash rounds queued there), W = A^{-1} V waits for both.
+    if (h.l > 0) {
+        hipStream_t fs = drain.lane[0], us = drain.lane[0], vs = drain.lane[0];
+        if (drain.forked) {
+            us = drain.lane[1];
+            vs = drain.lane[2];
+            HIPCHK(hipEventRecord(drain.extra[0], drain.lane[0]));   // landmarks done
+            HIPCHK(hipStreamWaitEvent(us, drain.extra[0], 0));
+            HIPCHK(hipStreamWaitEvent(vs, drain.extra[0], 0));
+            lane_used[1] = lane_used[2] = true;
+        }
+        const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
+        const bool cosn = cost == LCN_COST_COSINE;
+        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, fs));
+        if (cosn && drain.forked) {   // the landmarks' norms are an input of U and V as well
+            HIPCHK(hipEventRecord(drain.extra[0], fs));
+            HIPCHK(hipStreamWaitEvent(us, drain.extra[0], 0));
+            HIPCHK(hipStreamWaitEvent(vs, drain.extra[0], 0));
+        }
+        HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, us));
+        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
+                                    h.U, nullptr, h.lp, us));
+        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, vs));
+        if (drain.forked) HIPCHK(hipEventRecord(drain.extra[1], vs));   // V done
+        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
+        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, fs));
+        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
+        if (drain.forked) HIPCHK(hipStreamWaitEvent(fs, drain.extra[1], 0));
+        // W^T = V^T A^{-1} (A^{-1} is symmetric)
+        HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, fs));
+    }
+    workers.join_all();
+    for (int q = 0; q < KM_LANES; ++q)
+        if (workers.st[q] != LCN_OK) return workers.st[q];
+    const bool factors_apart = drain.forked && h.l > 0;   // lane 0 holds landmarks and factors only
+    if (drain.forked) {   // the buckets are needed from here on, the factors only by the sparse values
+        for (int q = factors_apart ? 1 : 0; q < KM_LANES; ++q) {
+            if (!lane_used[q]) continue;
+            HIPCHK(hipEventRecord(drain.join[q], drain.lane[q]));
+            HIPCHK(hipStreamWaitEvent(h.stream, drain.join[q], 0));
+        }
     }
     long long totals[2] = {0, 0};
     unsigned long long range_flag = 0;
@@ -635,10 +738,10 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     }
     HIPCHK(launch_build_meta(h.sort, h.a, h.b_marg, h.stream));
     int undecided2[2] = {0, 0};  // points sent to the exact rule over all centroids, and over two
-    HIPCHK(hipMemcpyAsync(undecided2, sc.nflagged, 2 * sizeof(int), hipMemcpyDeviceToHost, h.stream));
+    if (last_nflagged)
+        HIPCHK(hipMemcpyAsync(undecided2, last_nflagged, 2 * sizeof(int), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
-    // the host needs the counts above to lay out the sparse values; the factors do not depend on
-    // them and keep the device busy while it waits
+    // the host needs the counts above to lay out the sparse values
     HIPCHK(hipEventRecord(h.ev0, h.stream));
 
     HIPCHK(hipEventSynchronize(h.ev0));
@@ -654,7 +757,10 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
     if (bytes_needed) *bytes_needed = bump.used + 256;
     if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;
 
-    if (factors_forked) HIPCHK(hipStreamWaitEvent(h.stream, h.ev1, 0));
+    if (factors_apart) {
+        HIPCHK(hipEventRecord(drain.join[0], drain.lane[0]));
+        HIPCHK(hipStreamWaitEvent(h.stream, drain.join[0], 0));
+    }
     // sparse values per bucket block (Sec. 3 / Sec. 4)
     if (h.R > 0) HIPCHK(launch_correction(h, h.ntiles, h.stream));
 
