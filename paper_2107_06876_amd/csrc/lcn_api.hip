@@ -663,12 +663,18 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
             bool has_round = false;
             for (int r = 0; r < h.R; ++r) has_round = has_round || lane_of_round(r) == q;
             if (!has_round) continue;
+            bool started = false;
             if (threaded) {
-                workers.t[q] = std::thread([&, q]() {
-                    (void)hipSetDevice(device_id);
-                    workers.st[q] = rounds_of_lane(q);
-                });
-            } else {
+                try {
+                    workers.t[q] = std::thread([&, q]() {
+                        (void)hipSetDevice(device_id);
+                        workers.st[q] = rounds_of_lane(q);
+                    });
+                    started = true;
+                } catch (...) {   // no thread to be had: this thread does it
+                }
+            }
+            if (!started) {
                 st = rounds_of_lane(q);
                 if (st != LCN_OK) return st;
             }
