@@ -481,12 +481,32 @@ lcn_status lcn_workspace_bytes(int64_t n, int64_t m, int32_t d, int32_t mode, co
     return LCN_OK;
 }
 
+static lcn_status build_one(const void *X, int64_t n, const void *Y, int64_t m, int32_t d, int32_t dtype, const float *a,
+                            const float *b, float lambda, int32_t cost, int32_t mode, const lcn_landmark_params *lm,
+                            const lcn_lsh_params *lsh, void *workspace, size_t workspace_bytes, void *hip_stream,
+                            size_t *bytes_needed, lcn_handle *out);
+
 lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t d, int32_t dtype, const float *a,
                      const float *b, float lambda, int32_t cost, int32_t mode, const lcn_landmark_params *lm,
                      const lcn_lsh_params *lsh, void *workspace, size_t workspace_bytes, void *hip_stream,
                      size_t *bytes_needed, lcn_handle *out)
 {
     if (!out) return LCN_ERR_INVALID_ARG;
+    *out = nullptr;
+    try {   // host containers are the only things in there that can throw: out of host memory
+        return build_one(X, n, Y, m, d, dtype, a, b, lambda, cost, mode, lm, lsh, workspace, workspace_bytes, hip_stream,
+                         bytes_needed, out);
+    } catch (...) {
+        *out = nullptr;
+        return LCN_ERR_ALLOC;
+    }
+}
+
+static lcn_status build_one(const void *X, int64_t n, const void *Y, int64_t m, int32_t d, int32_t dtype, const float *a,
+                            const float *b, float lambda, int32_t cost, int32_t mode, const lcn_landmark_params *lm,
+                            const lcn_lsh_params *lsh, void *workspace, size_t workspace_bytes, void *hip_stream,
+                            size_t *bytes_needed, lcn_handle *out)
+{
     *out = nullptr;
     if (!X || !Y || !a || !b || !workspace || ((uintptr_t)workspace & 255)) return LCN_ERR_INVALID_ARG;
     lcn_status st = check_params(n, m, d, dtype, lambda, cost, mode, lm, lsh);
@@ -668,7 +688,11 @@ lcn_status lcn_build(const void *X, int64_t n, const void *Y, int64_t m, int32_t
                 try {
                     workers.t[q] = std::thread([&, q]() {
                         (void)hipSetDevice(device_id);
-                        workers.st[q] = rounds_of_lane(q);
+                        try {
+                            workers.st[q] = rounds_of_lane(q);
+                        } catch (...) {   // out of host memory in a container
+                            workers.st[q] = LCN_ERR_ALLOC;
+                        }
                     });
                     started = true;
                 } catch (...) {   // no thread to be had: this thread does it
