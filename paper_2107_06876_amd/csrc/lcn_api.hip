@@ -449,6 +449,309 @@ bool lane_streams(hipStream_t (&out)[KM_LANES])
     return true;
 }
 
+// One lcn_build call: what it holds while it runs, and its stages as member functions, called in
+// order by build_one.  Whichever way the build ends, the destructor first joins the host threads,
+// then drains every stream (the caller's inputs and the host vector `starts` are read by work
+// that may still be in flight), then lets the members go.
+//
+// The k-means runs of a build (landmarks, one per hash round) and the factors are independent
+// chains of short launches, and the host needs about as long to enqueue such a launch as the
+// device to execute it.  Each run therefore gets scratch of its own and one of KM_LANES streams of
+// the library's own ("lanes": forked from and joined into the caller's stream by events), and the
+// hash rounds of a lane are enqueued by a host thread of their own while the calling thread
+// enqueues the landmarks and the factors.
+struct Builder {
+    Handle &h;
+    Bump bump;
+    const lcn_landmark_params *lm;
+    const lcn_lsh_params *lsh;
+    const long long n, m, N;
+    const int d, cost, mode;
+    Scratch sc{};
+    std::vector<long long> starts;   // seeded starts of all flat k-means runs (host copy of sc.starts)
+    const long long *starts_landmarks = nullptr, *starts_rounds = nullptr;
+    hipStream_t lane[KM_LANES] = {};
+    bool forked = false;             // the lanes are streams of their own (else all are the caller's stream)
+    bool lane_used[KM_LANES] = {};
+    hipEvent_t join[KM_LANES] = {}, extra[2] = {};
+    std::thread threads[KM_LANES];
+    lcn_status thread_status[KM_LANES];
+    const int *last_nflagged = nullptr;   // the undecided counts of the build's last k-means run
+    int device_id = 0;
+
+    Builder(Handle &handle, const lcn_landmark_params *lm_, const lcn_lsh_params *lsh_, int cost_, int mode_)
+        : h(handle), bump{handle.ws, handle.ws_bytes, 0, false}, lm(lm_), lsh(lsh_), n(handle.n), m(handle.m),
+          N(handle.n + handle.m), d(handle.d), cost(cost_), mode(mode_)
+    {
+        for (int q = 0; q < KM_LANES; ++q) {
+            lane[q] = h.stream;
+            thread_status[q] = LCN_OK;
+        }
+    }
+    Builder(const Builder &) = delete;
+    Builder &operator=(const Builder &) = delete;
+    ~Builder()
+    {
+        join_threads();
+        for (int q = 0; q < KM_LANES; ++q) {
+            if (forked) (void)hipStreamSynchronize(lane[q]);
+            if (join[q]) (void)hipEventDestroy(join[q]);
+        }
+        for (int q = 0; q < 2; ++q)
+            if (extra[q]) (void)hipEventDestroy(extra[q]);
+        (void)hipStreamSynchronize(h.stream);
+    }
+    void join_threads()
+    {
+        for (int q = 0; q < KM_LANES; ++q)
+            if (threads[q].joinable()) threads[q].join();
+    }
+    bool kmeans_hashing() const { return uses_lsh(mode) && h.hash == LCN_HASH_KMEANS; }
+    // the landmarks and the factors keep lane 0 to themselves
+    int lane_of_round(int r) const { return h.l > 0 ? 1 + r % (KM_LANES - 1) : r % KM_LANES; }
+
+    // Inputs into the workspace (fp32 points, norms, bf16 planes, marginals), seeded starts to the
+    // device in one copy, lanes forked.
+    lcn_status prepare(const void *X, const void *Y, const float *a, const float *b, int dtype, bool overlap)
+    {
+        (void)hipGetDevice(&device_id);
+        forked = overlap && lane_streams(lane);
+        if (!forked)
+            for (int q = 0; q < KM_LANES; ++q) lane[q] = h.stream;
+        HIPCHK(hipEventCreate(&h.ev0));
+        HIPCHK(hipEventCreate(&h.ev1));
+        HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
+        HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
+        HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
+        HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
+        HIPCHK(hipMemcpyAsync(h.b_marg, b, sizeof(float) * (size_t)m, hipMemcpyDeviceToDevice, h.stream));
+        HIPCHK(launch_convert(X, n, Y, m, d, dtype, h.Z, (unsigned *)(h.counters + 4), h.stream));
+        HIPCHK(launch_sqnorms(h.Z, N, d, h.zn, h.stream));
+        // bf16 planes of the points for the assignment filter of every k-means run
+        if (!h.exact_assign_only && (h.l > 0 || kmeans_hashing()))
+            HIPCHK(launch_split_planes(h.Z, N, d, sc.zplanes, sc.zt, h.stream));
+
+        const bool lm_sample = h.l > 0 && lm->init == LCN_INIT_SAMPLE;
+        const bool flat_rounds = kmeans_hashing() && h.hier_levels <= 1;
+        if (lm_sample) {
+            std::vector<long long> idx = seeded_indices(lm->seed, N, h.l);
+            starts.insert(starts.end(), idx.begin(), idx.end());
+        }
+        const size_t rounds_at = starts.size();
+        if (flat_rounds)
+            for (int r = 0; r < h.R; ++r) {
+                std::vector<long long> idx = seeded_indices(lsh->seed + (uint64_t)r, N, h.b);
+                starts.insert(starts.end(), idx.begin(), idx.end());
+            }
+        if (!starts.empty()) {
+            HIPCHK(hipMemcpyAsync(sc.starts, starts.data(), sizeof(long long) * starts.size(), hipMemcpyHostToDevice,
+                                  h.stream));
+            if (lm_sample) starts_landmarks = sc.starts;
+            if (flat_rounds) starts_rounds = sc.starts + rounds_at;
+        }
+        if (forked) {
+            HIPCHK(hipEventRecord(h.ev1, h.stream));
+            for (int q = 0; q < KM_LANES; ++q) {
+                HIPCHK(hipEventCreateWithFlags(&join[q], hipEventDisableTiming));
+                HIPCHK(hipStreamWaitEvent(lane[q], h.ev1, 0));
+            }
+            for (int q = 0; q < 2; ++q) HIPCHK(hipEventCreateWithFlags(&extra[q], hipEventDisableTiming));
+        }
+        return LCN_OK;
+    }
+
+    // All hash rounds (Sec. 3) that lane q carries, in order.
+    lcn_status rounds_of_lane(int q)
+    {
+        for (int r = 0; r < h.R; ++r) {
+            if (lane_of_round(r) != q) continue;
+            int32_t *dst = h.bucket + (long long)r * N;
+            KmScratch &km = sc.km[q];
+            hipStream_t ls = lane[q];
+            if (h.hash == LCN_HASH_KMEANS) {
+                lcn_status rs;
+                if (h.hier_levels > 1)
+                    rs = run_hier_kmeans(h, sc, km, ls, lsh->branching, h.hier_levels, lsh->kmeans_iters,
+                                         lsh->seed + (uint64_t)r, dst);
+                else
+                    rs = run_kmeans(h, sc, km, ls, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, km.cent, dst,
+                                    starts_rounds + (long long)r * h.b);
+                if (rs != LCN_OK) return rs;
+            } else if (h.and_width > 1) {
+                const int b1 = lsh->num_buckets;   // buckets of one hash; the band has b1 ^ and_width
+                for (int j = 0; j < h.and_width; ++j) {
+                    const float *Rm = lsh->projections + ((long long)r * h.and_width + j) * d * (b1 / 2);
+                    HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, b1, km.assign, ls));
+                    HIPCHK(launch_combine_hash(dst, km.assign, b1, j == 0, N, ls));
+                }
+            } else {
+                const float *Rm = lsh->projections + (long long)r * d * (h.b / 2);
+                HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, h.b, dst, ls));
+            }
+        }
+        return LCN_OK;
+    }
+
+    // Starts the hash rounds: with lanes and k-means hashing one host thread per lane enqueues them
+    // (so that they overlap with what the calling thread enqueues next), otherwise they are enqueued
+    // here and now.
+    lcn_status start_hash_rounds()
+    {
+        if (mode == LCN_MODE_DENSE) {
+            HIPCHK(hipMemsetAsync(h.bucket, 0, sizeof(int32_t) * (size_t)N, h.stream));
+            return LCN_OK;
+        }
+        if (!uses_lsh(mode)) return LCN_OK;
+        for (int r = 0; r < h.R; ++r) lane_used[lane_of_round(r)] = true;
+        if (kmeans_hashing() && h.R > 0) last_nflagged = sc.km[lane_of_round(h.R - 1)].nflagged;
+        const bool threaded = forked && kmeans_hashing();
+        for (int q = 0; q < KM_LANES; ++q) {
+            bool has_round = false;
+            for (int r = 0; r < h.R; ++r) has_round = has_round || lane_of_round(r) == q;
+            if (!has_round) continue;
+            bool started = false;
+            if (threaded) {
+                try {
+                    threads[q] = std::thread([this, q]() {
+                        (void)hipSetDevice(device_id);
+                        try {
+                            thread_status[q] = rounds_of_lane(q);
+                        } catch (...) {   // out of host memory in a container
+                            thread_status[q] = LCN_ERR_ALLOC;
+                        }
+                    });
+                    started = true;
+                } catch (...) {   // no thread to be had: this thread does it
+                }
+            }
+            if (!started) {
+                const lcn_status st = rounds_of_lane(q);
+                if (st != LCN_OK) return st;
+            }
+        }
+        return LCN_OK;
+    }
+
+    // landmarks: centroids of k-means on X u Y, or sampled points (Sec. 4); lane 0
+    lcn_status landmarks()
+    {
+        if (h.l == 0) return LCN_OK;
+        const lcn_status st = run_kmeans(h, sc, sc.km[0], lane[0], h.l, lm->kmeans_iters, lm->seed, h.L, sc.km[0].assign,
+                                         starts_landmarks, lm->init, lm->init_centroids);
+        if (st != LCN_OK) return st;
+        lane_used[0] = true;
+        if (!last_nflagged) last_nflagged = sc.km[0].nflagged;
+        return LCN_OK;
+    }
+
+    // Nystrom factors (Sec. 4; App. "Implementational details").  They need the landmarks only and run
+    // beside the hash rounds: A and its inverse follow the landmarks on lane 0, U and V go to lanes 1
+    // and 2 (behind the hash rounds queued there), W = A^{-1} V waits for both.
+    lcn_status factors()
+    {
+        if (h.l == 0) return LCN_OK;
+        hipStream_t fs = lane[0], us = lane[0], vs = lane[0];
+        if (forked) {
+            us = lane[1];
+            vs = lane[2];
+            HIPCHK(hipEventRecord(extra[0], lane[0]));   // landmarks done
+            HIPCHK(hipStreamWaitEvent(us, extra[0], 0));
+            HIPCHK(hipStreamWaitEvent(vs, extra[0], 0));
+            lane_used[1] = lane_used[2] = true;
+        }
+        const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
+        const bool cosn = cost == LCN_COST_COSINE;
+        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, fs));
+        if (cosn && forked) {   // the landmarks' norms are an input of U and V as well
+            HIPCHK(hipEventRecord(extra[0], fs));
+            HIPCHK(hipStreamWaitEvent(us, extra[0], 0));
+            HIPCHK(hipStreamWaitEvent(vs, extra[0], 0));
+        }
+        HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, us));
+        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
+                                    h.U, nullptr, h.lp, us));
+        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, vs));
+        if (forked) HIPCHK(hipEventRecord(extra[1], vs));   // V done
+        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
+        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
+                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, fs));
+        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
+        if (forked) HIPCHK(hipStreamWaitEvent(fs, extra[1], 0));
+        // W^T = V^T A^{-1} (A^{-1} is symmetric)
+        HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, fs));
+        return LCN_OK;
+    }
+
+    // lane 0 holds the landmarks and the factors only
+    bool factors_apart() const { return forked && h.l > 0; }
+
+    // Buckets -> blocks (bucket sort, per-row metadata); the host learns the pair count, the
+    // undecided-point count and the input-range flag (the build's one wait for the device) and lays
+    // out the sparse values.
+    lcn_status structure(size_t *bytes_needed)
+    {
+        join_threads();
+        for (int q = 0; q < KM_LANES; ++q)
+            if (thread_status[q] != LCN_OK) return thread_status[q];
+        if (forked) {   // the buckets are needed from here on, the factors only by the sparse values
+            for (int q = factors_apart() ? 1 : 0; q < KM_LANES; ++q) {
+                if (!lane_used[q]) continue;
+                HIPCHK(hipEventRecord(join[q], lane[q]));
+                HIPCHK(hipStreamWaitEvent(h.stream, join[q], 0));
+            }
+        }
+        long long totals[2] = {0, 0};
+        unsigned long long range_flag = 0;
+        if (h.R > 0) {
+            HIPCHK(launch_bucket_sort(h.sort, h.stream));
+            HIPCHK(hipMemcpyAsync(totals, sc.totals, sizeof(totals), hipMemcpyDeviceToHost, h.stream));
+        }
+        HIPCHK(launch_build_meta(h.sort, h.a, h.b_marg, h.stream));
+        int undecided2[2] = {0, 0};  // points sent to the exact rule over all centroids, and over two
+        if (last_nflagged)
+            HIPCHK(hipMemcpyAsync(undecided2, last_nflagged, 2 * sizeof(int), hipMemcpyDeviceToHost, h.stream));
+        HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
+        HIPCHK(hipEventRecord(h.ev0, h.stream));
+        HIPCHK(hipEventSynchronize(h.ev0));
+        if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
+        h.nnz_stored = totals[0];
+        h.undecided_last = (long long)undecided2[0] + undecided2[1];
+        h.ntiles = (int)totals[1];
+
+        // 64 entries of slack: a sweep reads whole wavefront-wide chunks and masks the excess
+        h.vals_x = bump.take<float>((size_t)h.nnz_stored + 64);
+        h.vals_y = bump.take<float>((size_t)h.nnz_stored + 64);
+        h.ws_used = bump.used;
+        if (bytes_needed) *bytes_needed = bump.used + 256;
+        if (bump.used > h.ws_bytes) return LCN_ERR_ALLOC;
+        return LCN_OK;
+    }
+
+    // Sparse values per bucket block (Sec. 3 / Sec. 4), scalings at their start v = 1 (eq. 2), the
+    // state derived from them; the build's final synchronisation.
+    lcn_status values_and_state()
+    {
+        if (factors_apart()) {
+            HIPCHK(hipEventRecord(join[0], lane[0]));
+            HIPCHK(hipStreamWaitEvent(h.stream, join[0], 0));
+        }
+        if (h.R > 0) HIPCHK(launch_correction(h, h.ntiles, h.stream));
+        HIPCHK(hipMemsetAsync(h.log_u, 0, sizeof(float) * (size_t)n, h.stream));
+        HIPCHK(hipMemsetAsync(h.log_v, 0, sizeof(float) * (size_t)m, h.stream));
+        const lcn_status st = init_state(h);
+        if (st != LCN_OK) return st;
+        int fail = 0;
+        unsigned long long uniq = 0;
+        HIPCHK(hipMemcpyAsync(&fail, sc.fail_flag, sizeof(int), hipMemcpyDeviceToHost, h.stream));
+        HIPCHK(hipMemcpyAsync(&uniq, h.counters + 3, sizeof(uniq), hipMemcpyDeviceToHost, h.stream));
+        HIPCHK(hipStreamSynchronize(h.stream));
+        if (fail) return LCN_ERR_SINGULAR;
+        h.nnz_unique = (long long)uniq;
+        return LCN_OK;
+    }
+};
+
 bool valid(lcn_handle hh) { return hh && ((Handle *)hh)->magic == HANDLE_MAGIC; }
 
 }  // namespace
@@ -535,8 +838,6 @@ static lcn_status build_one(const void *X, int64_t n, const void *Y, int64_t m, 
     h.stream = (hipStream_t)hip_stream;
     h.ws = (char *)workspace;
     h.ws_bytes = workspace_bytes;
-    const long long N = n + m;
-
     bool build_overlap = true;
     {
         const char *env = getenv("LCN_PASS_GRID");
@@ -549,264 +850,19 @@ static lcn_status build_one(const void *X, int64_t n, const void *Y, int64_t m, 
         build_overlap = env ? atoi(env) != 0 : true;
         h.cus = device_compute_units();
     }
-    Bump bump{h.ws, workspace_bytes, 0, false};
-    Scratch sc{};
-    layout(h, bump, sc);
-    if (bump.used > workspace_bytes) {
+    Builder B(h, lm, lsh, cost, mode);   // after the handle's guard: it is torn down first
+    layout(h, B.bump, B.sc);
+    if (B.bump.used > workspace_bytes) {
         if (bytes_needed) lcn_workspace_bytes(n, m, d, mode, lm, lsh, 0, bytes_needed);
         return LCN_ERR_ALLOC;
     }
-
-    // Whichever way this function returns from here on, the stream is drained first: the caller's
-    // inputs and the host vector below are read by work that may still be in flight.
-    std::vector<long long> starts;
-    struct Drain {
-        hipStream_t s;
-        hipStream_t lane[KM_LANES];
-        bool forked;
-        hipEvent_t join[KM_LANES], extra[2];
-        ~Drain()
-        {
-            for (int q = 0; q < KM_LANES; ++q) {
-                if (forked) (void)hipStreamSynchronize(lane[q]);
-                if (join[q]) (void)hipEventDestroy(join[q]);
-            }
-            for (int q = 0; q < 2; ++q)
-                if (extra[q]) (void)hipEventDestroy(extra[q]);
-            (void)hipStreamSynchronize(s);
-        }
-    } drain{h.stream, {}, false, {}, {}};
-    // The k-means runs of a build (landmarks, one per hash round) are independent chains of short
-    // launches; each gets a stream of the library's own (forked from and joined into the caller's
-    // stream by events) and scratch of its own, so that they fill the device together.
-    drain.forked = build_overlap && lane_streams(drain.lane);
-    if (!drain.forked)
-        for (int q = 0; q < KM_LANES; ++q) drain.lane[q] = h.stream;
-    bool lane_used[KM_LANES] = {};
-
-    HIPCHK(hipEventCreate(&h.ev0));
-    HIPCHK(hipEventCreate(&h.ev1));
-    HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
-    HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
-    HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
-    HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
-    HIPCHK(hipMemcpyAsync(h.b_marg, b, sizeof(float) * (size_t)m, hipMemcpyDeviceToDevice, h.stream));
-    HIPCHK(launch_convert(X, n, Y, m, d, dtype, h.Z, (unsigned *)(h.counters + 4), h.stream));
-    HIPCHK(launch_sqnorms(h.Z, N, d, h.zn, h.stream));
-    // bf16 planes of the points for the assignment filter of every k-means run
-    if (!h.exact_assign_only && (h.l > 0 || (uses_lsh(mode) && h.hash == LCN_HASH_KMEANS)))
-        HIPCHK(launch_split_planes(h.Z, N, d, sc.zplanes, sc.zt, h.stream));
-
-    // seeded starts of all flat k-means runs: one upload, consumed by the stream while `starts` lives
-    const long long *starts_landmarks = nullptr, *starts_rounds = nullptr;
-    {
-        const bool lm_sample = h.l > 0 && lm->init == LCN_INIT_SAMPLE;
-        const bool flat_rounds = uses_lsh(mode) && h.hash == LCN_HASH_KMEANS && h.hier_levels <= 1;
-        if (lm_sample) {
-            std::vector<long long> idx = seeded_indices(lm->seed, N, h.l);
-            starts.insert(starts.end(), idx.begin(), idx.end());
-        }
-        const size_t rounds_at = starts.size();
-        if (flat_rounds)
-            for (int r = 0; r < h.R; ++r) {
-                std::vector<long long> idx = seeded_indices(lsh->seed + (uint64_t)r, N, h.b);
-                starts.insert(starts.end(), idx.begin(), idx.end());
-            }
-        if (!starts.empty()) {
-            HIPCHK(hipMemcpyAsync(sc.starts, starts.data(), sizeof(long long) * starts.size(), hipMemcpyHostToDevice,
-                                  h.stream));
-            if (lm_sample) starts_landmarks = sc.starts;
-            if (flat_rounds) starts_rounds = sc.starts + rounds_at;
-        }
-    }
-    if (drain.forked) {
-        HIPCHK(hipEventRecord(h.ev1, h.stream));
-        for (int q = 0; q < KM_LANES; ++q) {
-            HIPCHK(hipEventCreateWithFlags(&drain.join[q], hipEventDisableTiming));
-            HIPCHK(hipStreamWaitEvent(drain.lane[q], h.ev1, 0));
-        }
-        for (int q = 0; q < 2; ++q) HIPCHK(hipEventCreateWithFlags(&drain.extra[q], hipEventDisableTiming));
-    }
-    const int *last_nflagged = nullptr;   // the undecided counts of the build's last k-means run
-    // hash rounds (Sec. 3).  The host needs about as long to enqueue one of the short launches of a
-    // k-means run as the device to execute it, so runs only overlap if they are enqueued at the same
-    // time: with the lanes in use every lane's rounds are enqueued by a thread of their own while
-    // this thread goes on with the landmarks' factors.
-    auto lane_of_round = [&](int r) { return h.l > 0 ? 1 + r % (KM_LANES - 1) : r % KM_LANES; };
-    auto rounds_of_lane = [&](int q) -> lcn_status {
-        for (int r = 0; r < h.R; ++r) {
-            if (lane_of_round(r) != q) continue;
-            int32_t *dst = h.bucket + (long long)r * N;
-            KmScratch &km = sc.km[q];
-            hipStream_t ls = drain.lane[q];
-            if (h.hash == LCN_HASH_KMEANS) {
-                lcn_status rs;
-                if (h.hier_levels > 1)
-                    rs = run_hier_kmeans(h, sc, km, ls, lsh->branching, h.hier_levels, lsh->kmeans_iters,
-                                         lsh->seed + (uint64_t)r, dst);
-                else
-                    rs = run_kmeans(h, sc, km, ls, h.b, lsh->kmeans_iters, lsh->seed + (uint64_t)r, km.cent, dst,
-                                    starts_rounds + (long long)r * h.b);
-                if (rs != LCN_OK) return rs;
-            } else if (h.and_width > 1) {
-                const int b1 = lsh->num_buckets;   // buckets of one hash; the band has b1 ^ and_width
-                for (int j = 0; j < h.and_width; ++j) {
-                    const float *Rm = lsh->projections + ((long long)r * h.and_width + j) * d * (b1 / 2);
-                    HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, b1, km.assign, ls));
-                    HIPCHK(launch_combine_hash(dst, km.assign, b1, j == 0, N, ls));
-                }
-            } else {
-                const float *Rm = lsh->projections + (long long)r * d * (h.b / 2);
-                HIPCHK(launch_assign_crosspolytope(h.Z, N, d, Rm, h.b, dst, ls));
-            }
-        }
-        return LCN_OK;
-    };
-    struct Workers {   // joined before the streams are drained, whichever way this function returns
-        std::thread t[KM_LANES];
-        lcn_status st[KM_LANES];
-        void join_all()
-        {
-            for (int q = 0; q < KM_LANES; ++q)
-                if (t[q].joinable()) t[q].join();
-        }
-        ~Workers() { join_all(); }
-    } workers;
-    for (int q = 0; q < KM_LANES; ++q) workers.st[q] = LCN_OK;
-    int device_id = 0;
-    (void)hipGetDevice(&device_id);
-    if (uses_lsh(mode)) {
-        for (int r = 0; r < h.R; ++r) lane_used[lane_of_round(r)] = true;
-        if (h.hash == LCN_HASH_KMEANS && h.R > 0) last_nflagged = sc.km[lane_of_round(h.R - 1)].nflagged;
-        const bool threaded = drain.forked && h.hash == LCN_HASH_KMEANS;
-        for (int q = 0; q < KM_LANES; ++q) {
-            bool has_round = false;
-            for (int r = 0; r < h.R; ++r) has_round = has_round || lane_of_round(r) == q;
-            if (!has_round) continue;
-            bool started = false;
-            if (threaded) {
-                try {
-                    workers.t[q] = std::thread([&, q]() {
-                        (void)hipSetDevice(device_id);
-                        try {
-                            workers.st[q] = rounds_of_lane(q);
-                        } catch (...) {   // out of host memory in a container
-                            workers.st[q] = LCN_ERR_ALLOC;
-                        }
-                    });
-                    started = true;
-                } catch (...) {   // no thread to be had: this thread does it
-                }
-            }
-            if (!started) {
-                st = rounds_of_lane(q);
-                if (st != LCN_OK) return st;
-            }
-        }
-    } else if (mode == LCN_MODE_DENSE) {
-        HIPCHK(hipMemsetAsync(h.bucket, 0, sizeof(int32_t) * (size_t)N, h.stream));
-    }
-    // landmarks: centroids of k-means on X u Y (Sec. 4)
-    if (h.l > 0) {
-        st = run_kmeans(h, sc, sc.km[0], drain.lane[0], h.l, lm->kmeans_iters, lm->seed, h.L, sc.km[0].assign,
-                        starts_landmarks, lm->init, lm->init_centroids);
-        if (st != LCN_OK) return st;
-        lane_used[0] = true;
-        if (!last_nflagged) last_nflagged = sc.km[0].nflagged;
-    }
-    // Nystrom factors (Sec. 4; App. "Implementational details").  They need the landmarks only and run
-    // beside the hash rounds: A and its inverse follow the landmarks on lane 0, U and V go to lanes 1
-    // and 2 (behind the hash rounds queued there), W = A^{-1} V waits for both.
-    if (h.l > 0) {
-        hipStream_t fs = drain.lane[0], us = drain.lane[0], vs = drain.lane[0];
-        if (drain.forked) {
-            us = drain.lane[1];
-            vs = drain.lane[2];
-            HIPCHK(hipEventRecord(drain.extra[0], drain.lane[0]));   // landmarks done
-            HIPCHK(hipStreamWaitEvent(us, drain.extra[0], 0));
-            HIPCHK(hipStreamWaitEvent(vs, drain.extra[0], 0));
-            lane_used[1] = lane_used[2] = true;
-        }
-        const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
-        const bool cosn = cost == LCN_COST_COSINE;
-        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, fs));
-        if (cosn && drain.forked) {   // the landmarks' norms are an input of U and V as well
-            HIPCHK(hipEventRecord(drain.extra[0], fs));
-            HIPCHK(hipStreamWaitEvent(us, drain.extra[0], 0));
-            HIPCHK(hipStreamWaitEvent(vs, drain.extra[0], 0));
-        }
-        HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, us));
-        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
-                                    h.U, nullptr, h.lp, us));
-        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, vs));
-        if (drain.forked) HIPCHK(hipEventRecord(drain.extra[1], vs));   // V done
-        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
-        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, fs));
-        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
-        if (drain.forked) HIPCHK(hipStreamWaitEvent(fs, drain.extra[1], 0));
-        // W^T = V^T A^{-1} (A^{-1} is symmetric)
-        HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, fs));
-    }
-    workers.join_all();
-    for (int q = 0; q < KM_LANES; ++q)
-        if (workers.st[q] != LCN_OK) return workers.st[q];
-    const bool factors_apart = drain.forked && h.l > 0;   // lane 0 holds landmarks and factors only
-    if (drain.forked) {   // the buckets are needed from here on, the factors only by the sparse values
-        for (int q = factors_apart ? 1 : 0; q < KM_LANES; ++q) {
-            if (!lane_used[q]) continue;
-            HIPCHK(hipEventRecord(drain.join[q], drain.lane[q]));
-            HIPCHK(hipStreamWaitEvent(h.stream, drain.join[q], 0));
-        }
-    }
-    long long totals[2] = {0, 0};
-    unsigned long long range_flag = 0;
-    if (h.R > 0) {
-        HIPCHK(launch_bucket_sort(h.sort, h.stream));
-        HIPCHK(hipMemcpyAsync(totals, sc.totals, sizeof(totals), hipMemcpyDeviceToHost, h.stream));
-    }
-    HIPCHK(launch_build_meta(h.sort, h.a, h.b_marg, h.stream));
-    int undecided2[2] = {0, 0};  // points sent to the exact rule over all centroids, and over two
-    if (last_nflagged)
-        HIPCHK(hipMemcpyAsync(undecided2, last_nflagged, 2 * sizeof(int), hipMemcpyDeviceToHost, h.stream));
-    HIPCHK(hipMemcpyAsync(&range_flag, h.counters + 4, sizeof(range_flag), hipMemcpyDeviceToHost, h.stream));
-    // the host needs the counts above to lay out the sparse values
-    HIPCHK(hipEventRecord(h.ev0, h.stream));
-
-    HIPCHK(hipEventSynchronize(h.ev0));
-    if (range_flag && (h.l > 0 || h.hash == LCN_HASH_KMEANS)) return LCN_ERR_INVALID_ARG;  // |x| >= 2^10 or not finite
-    h.nnz_stored = totals[0];
-    h.undecided_last = (long long)undecided2[0] + undecided2[1];
-    h.ntiles = (int)totals[1];
-
-    // 64 entries of slack: a sweep reads whole wavefront-wide chunks and masks the excess
-    h.vals_x = bump.take<float>((size_t)h.nnz_stored + 64);
-    h.vals_y = bump.take<float>((size_t)h.nnz_stored + 64);
-    h.ws_used = bump.used;
-    if (bytes_needed) *bytes_needed = bump.used + 256;
-    if (bump.used > workspace_bytes) return LCN_ERR_ALLOC;
-
-    if (factors_apart) {
-        HIPCHK(hipEventRecord(drain.join[0], drain.lane[0]));
-        HIPCHK(hipStreamWaitEvent(h.stream, drain.join[0], 0));
-    }
-    // sparse values per bucket block (Sec. 3 / Sec. 4)
-    if (h.R > 0) HIPCHK(launch_correction(h, h.ntiles, h.stream));
-
-    // scalings start at 1 (eq. 2)
-    HIPCHK(hipMemsetAsync(h.log_u, 0, sizeof(float) * (size_t)n, h.stream));
-    HIPCHK(hipMemsetAsync(h.log_v, 0, sizeof(float) * (size_t)m, h.stream));
-    st = init_state(h);
-    if (st != LCN_OK) return st;
-
-    int fail = 0;
-    unsigned long long uniq = 0;
-    HIPCHK(hipMemcpyAsync(&fail, sc.fail_flag, sizeof(int), hipMemcpyDeviceToHost, h.stream));
-    HIPCHK(hipMemcpyAsync(&uniq, h.counters + 3, sizeof(uniq), hipMemcpyDeviceToHost, h.stream));
-    HIPCHK(hipStreamSynchronize(h.stream));
-    if (fail) return LCN_ERR_SINGULAR;
-    h.nnz_unique = (long long)uniq;
+    // hash rounds first: their threads enqueue while this one goes on with the landmarks and factors
+    if ((st = B.prepare(X, Y, a, b, dtype, build_overlap)) != LCN_OK) return st;
+    if ((st = B.start_hash_rounds()) != LCN_OK) return st;
+    if ((st = B.landmarks()) != LCN_OK) return st;
+    if ((st = B.factors()) != LCN_OK) return st;
+    if ((st = B.structure(bytes_needed)) != LCN_OK) return st;
+    if ((st = B.values_and_state()) != LCN_OK) return st;
 
     h.magic = HANDLE_MAGIC;
     guard.p = nullptr;
