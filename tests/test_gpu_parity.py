@@ -333,3 +333,40 @@ def test_new_structure_options_on_tiny_inputs():
     p.and_width = 3
     p.projections = workloads.projections(1, p.num_rounds * 3, p.d, p.num_buckets)
     print("tiny AND", compare(p, "sparse", workloads.HASH_CROSSPOLYTOPE), flush=True)
+
+
+def test_overlapped_build_gives_the_same_bits(monkeypatch):
+    """The build with its k-means runs on streams and host threads of their own against the build
+    that keeps everything on the caller's stream: landmarks, buckets, pattern, values, factors and
+    the scalings after a few iterations, bit for bit; five builds in a row of the former."""
+    import torch
+    import paper_2107_06876_amd as lcn
+    from parity import gpu_build
+    cases = [(workloads.config3(n=3000, d=48, landmarks=96, buckets=12, rounds=3, iters=6, name="C3 reduced"), "lcn", {}),
+             (workloads.config1(), "sparse", {}),
+             (workloads.config3(n=2000, d=70, landmarks=64, buckets=24, rounds=5, iters=6, name="C3 reduced"), "lcn",
+              dict(branching=(6, 4), landmark_init="kmeans++", landmark_iters=2))]
+    for p, mode, opts in cases:
+        for k, v in opts.items():
+            setattr(p, k, v)
+
+        def snapshot():
+            h = gpu_build(p, mode)
+            lcn.sinkhorn_run(h, 4)
+            out = [x.clone() for x in lcn.lcn_get_scalings(h)]
+            out.append(lcn.lcn_get_buckets(h).clone())
+            out.extend(x.clone() for x in lcn.lcn_get_csr(h))
+            if mode == "lcn":
+                out.append(lcn.lcn_get_landmarks(h).clone())
+                out.extend(x.clone() for x in lcn.lcn_get_factors(h))
+            lcn.lcn_destroy(h)
+            return out
+
+        monkeypatch.setenv("LCN_BUILD_OVERLAP", "0")
+        ref = snapshot()
+        monkeypatch.setenv("LCN_BUILD_OVERLAP", "1")
+        for _ in range(5):
+            got = snapshot()
+            assert len(got) == len(ref)
+            for a, b in zip(got, ref):
+                assert torch.equal(a, b)
