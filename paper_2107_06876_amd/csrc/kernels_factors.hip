@@ -36,12 +36,32 @@ hipError_t launch_sqnorms(const float *P, long long rows, int d, double *out, hi
 
 // ------------------------------------------------ pairwise tile machinery --
 //
-// 256 threads hold a 64 x 64 tile of fp64 accumulators, 4 x 4 per thread.
+// 256 threads (4 wavefronts) hold a 64 x 64 tile of fp64 accumulators of a product P Q^T, built by
+// the fp64 matrix instruction v_mfma_f64_16x16x4_f64: wavefront w owns the 32 x 32 quarter at rows
+// 32 (w / 2), columns 32 (w % 2), as 2 x 2 instruction tiles of 16 x 16.  Operand layout of the
+// instruction: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16] (one fp64 each, 4 deep) and
+// receives D[4 v + l / 16][l % 16], v = 0..3.  A thread's 16 accumulators are numbered
+// e = 4 (2 ti + tj) + v; tile_row / tile_col give their place in the 64 x 64 tile.
 // Rows of both operands may be gathered through index lists held in LDS.
 
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
 struct TileAcc {
-    double v[4][4];
+    double4_t t[4];   // [2 ti + tj]
+    __device__ inline double get(int e) const { return t[e >> 2][e & 3]; }
 };
+
+__device__ inline int tile_row(int e)
+{
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    return 32 * (w >> 1) + 16 * (e >> 3) + 4 * (e & 3) + (l >> 4);
+}
+
+__device__ inline int tile_col(int e)
+{
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    return 32 * (w & 1) + 16 * ((e >> 2) & 1) + (l & 15);
+}
 
 // stage 64 rows x KCH features of a row-major matrix into dst[k][row]
 __device__ inline void stage_rows(float (*dst)[LDT], const float *__restrict__ base, long long ld,
@@ -60,44 +80,39 @@ __device__ inline void stage_rows(float (*dst)[LDT], const float *__restrict__ b
     }
 }
 
-template <bool SQDIFF>
-__device__ inline void tile_fma(TileAcc &acc, const float (*Ps)[LDT], const float (*Cs)[LDT])
+// acc += P_chunk Q_chunk^T for the KCH staged features (dot products; the staged values are fp32,
+// products and sums fp64)
+__device__ inline void tile_mma(TileAcc &acc, const float (*Ps)[LDT], const float (*Cs)[LDT])
 {
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-#pragma unroll 4
-    for (int kk = 0; kk < KCH; ++kk) {
-        const float4 pz = *(const float4 *)&Ps[kk][ty * 4];
-        const float4 cz = *(const float4 *)&Cs[kk][tx * 4];
-        const double pv[4] = {(double)pz.x, (double)pz.y, (double)pz.z, (double)pz.w};
-        const double cv[4] = {(double)cz.x, (double)cz.y, (double)cz.z, (double)cz.w};
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int r0 = 32 * (w >> 1) + (l & 15), c0 = 32 * (w & 1) + (l & 15), kq = l >> 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (SQDIFF) {
-                    double t = pv[i] - cv[j];
-                    acc.v[i][j] = fma(t, t, acc.v[i][j]);
-                } else {
-                    acc.v[i][j] = fma(pv[i], cv[j], acc.v[i][j]);
-                }
-            }
+    for (int ks = 0; ks < KCH / 4; ++ks) {
+        const int k = 4 * ks + kq;
+        const double a0 = (double)Ps[k][r0], a1 = (double)Ps[k][r0 + 16];
+        const double b0 = (double)Cs[k][c0], b1 = (double)Cs[k][c0 + 16];
+        acc.t[0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc.t[0], 0, 0, 0);
+        acc.t[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc.t[1], 0, 0, 0);
+        acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.t[2], 0, 0, 0);
+        acc.t[3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc.t[3], 0, 0, 0);
     }
 }
 
 __device__ inline void tile_zero(TileAcc &acc)
 {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc.v[i][j] = 0.0;
+        for (int v = 0; v < 4; ++v) acc.t[q][v] = 0.0;
 }
 
-// cost from the accumulated quantity (squared distance, or dot product for cosine)
-__device__ inline double cost_from_acc(double acc, int cost, double pn, double qn)
+// cost from the dot product and the squared norms of the two points; the squared distance is
+// |p|^2 + |q|^2 - 2 p.q in fp64 (rounding can leave it a hair below zero for coinciding points)
+__device__ inline double cost_from_dot(double dot, int cost, double pn, double qn)
 {
-    if (cost == LCN_COST_COSINE) return 1.0 - acc / (sqrt(pn) * sqrt(qn));
-    if (cost == LCN_COST_EUCLID) return sqrt(acc);
-    return acc;
+    if (cost == LCN_COST_COSINE) return 1.0 - dot / (sqrt(pn) * sqrt(qn));
+    const double sq = fmax(pn + qn - 2.0 * dot, 0.0);
+    return cost == LCN_COST_EUCLID ? sqrt(sq) : sq;
 }
 
 // ----------------------------------------------------- kernel matrix k(P, Q) --
@@ -125,25 +140,18 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
         stage_rows(Ps, P, d, pidx, k0, d);
         stage_rows(Cs, Q, d, qidx, k0, d);
         __syncthreads();
-        if (cost == LCN_COST_COSINE)
-            tile_fma<false>(acc, Ps, Cs);
-        else
-            tile_fma<true>(acc, Ps, Cs);
+        tile_mma(acc, Ps, Cs);
     }
-    const int tx = tid & 15, ty = tid >> 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        long long p = p0 + ty * 4 + i;
-        if (p >= rows) continue;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int q = q0 + tx * 4 + j;
-            if (q >= cols) continue;
-            double c = cost_from_acc(acc.v[i][j], cost, pn ? pn[p] : 0.0, qn ? qn[q] : 0.0);
-            double kv = exp(-c * inv_lambda);
-            if (out32) out32[p * ldo + q] = (float)kv;
-            if (out64) out64[p * cols + q] = kv;
-        }
+    for (int e = 0; e < 16; ++e) {
+        const long long p = p0 + tile_row(e);
+        const int q = q0 + tile_col(e);
+        if (p >= rows || q >= cols) continue;
+        // a point against itself (the diagonal of the landmarks' matrix) is at cost zero exactly
+        const double c = (P == Q && p == q) ? 0.0 : cost_from_dot(acc.get(e), cost, pn[p], qn[q]);
+        const double kv = exp(-c * inv_lambda);
+        if (out32) out32[p * ldo + q] = (float)kv;
+        if (out64) out64[p * cols + q] = kv;
     }
 }
 
@@ -180,14 +188,12 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const double *A, int lda, i
     __shared__ double As[KC][TILE + 2];
     __shared__ double Bs[KC][TILE + 2];
     const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
     const long long r0 = (long long)blockIdx.x * TILE;
     const int c0 = blockIdx.y * TILE;
-    double acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    const int wv = tid >> 6, ln = tid & 63;
+    const int ar = 32 * (wv >> 1) + (ln & 15), bc = 32 * (wv & 1) + (ln & 15), kq4 = ln >> 4;
+    TileAcc acc;
+    tile_zero(acc);
     for (int k0 = 0; k0 < K; k0 += KC) {
         __syncthreads();
         if (transA) {
@@ -230,31 +236,25 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const double *A, int lda, i
         }
         __syncthreads();
 #pragma unroll
-        for (int kk = 0; kk < KC; ++kk) {
-            double av[4], bv[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) av[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fma(av[i], bv[j], acc[i][j]);
+        for (int ks = 0; ks < KC / 4; ++ks) {
+            const int k = 4 * ks + kq4;
+            const double a0 = As[k][ar], a1 = As[k][ar + 16];
+            const double b0 = Bs[k][bc], b1 = Bs[k][bc + 16];
+            acc.t[0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc.t[0], 0, 0, 0);
+            acc.t[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc.t[1], 0, 0, 0);
+            acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.t[2], 0, 0, 0);
+            acc.t[3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc.t[3], 0, 0, 0);
         }
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const long long r = r0 + ty * 4 + i;
-        if (r >= M) continue;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = c0 + tx * 4 + j;
-            if (c >= N) continue;
-            double v = alpha * acc[i][j];
-            if (beta != 0.0) v += beta * C[r * ldc + c];
-            if (C) C[r * ldc + c] = v;
-            if (C32) C32[r * ldc32 + c] = (float)v;
-        }
+    for (int e = 0; e < 16; ++e) {
+        const long long r = r0 + tile_row(e);
+        const int c = c0 + tile_col(e);
+        if (r >= M || c >= N) continue;
+        double v = alpha * acc.get(e);
+        if (beta != 0.0) v += beta * C[r * ldc + c];
+        if (C) C[r * ldc + c] = v;
+        if (C32) C32[r * ldc32 + c] = (float)v;
     }
 }
 
@@ -501,25 +501,19 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
         stage_rows(Ps, Z, d, xi, k0, d);
         stage_rows(Cs, Z, d, yj, k0, d);
         __syncthreads();
-        if (cost == LCN_COST_COSINE)
-            tile_fma<false>(acc, Ps, Cs);
-        else
-            tile_fma<true>(acc, Ps, Cs);
+        tile_mma(acc, Ps, Cs);
     }
-    const int tx = tid & 15, ty = tid >> 4;
-    double kv[4][4];
+    double kv[16];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            long long gi = xi[ty * 4 + i], gj = yj[tx * 4 + j];
-            double v = 0.0;
-            if (gi >= 0 && gj >= 0) {
-                double c = cost_from_acc(acc.v[i][j], cost, zn ? zn[gi] : 0.0, zn ? zn[gj] : 0.0);
-                v = log_values ? -c * inv_lambda : exp(-c * inv_lambda);
-            }
-            kv[i][j] = v;
+    for (int e = 0; e < 16; ++e) {
+        const long long gi = xi[tile_row(e)], gj = yj[tile_col(e)];
+        double v = 0.0;
+        if (gi >= 0 && gj >= 0) {
+            const double c = cost_from_dot(acc.get(e), cost, zn[gi], zn[gj]);
+            v = log_values ? -c * inv_lambda : exp(-c * inv_lambda);
         }
+        kv[e] = v;
+    }
     if (U) {
         // Nystrom value on the same pairs: sum_k U[i][k] * Wt[j][k]
         __syncthreads();
@@ -532,13 +526,11 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
             stage_rows(Ps, U, lp, xi, k0, lp);
             stage_rows(Cs, Wt, lp, yj, k0, lp);
             __syncthreads();
-            tile_fma<false>(acc, Ps, Cs);
+            tile_mma(acc, Ps, Cs);
         }
         if (!bw.lin_u) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) kv[i][j] -= acc.v[i][j];
+            for (int e = 0; e < 16; ++e) kv[e] -= acc.get(e);
         }
     }
     if (bw.lin_u) {
@@ -548,18 +540,16 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
         for (int which = 0; which < (U ? 2 : 1); ++which) {
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int li = ty * 4 + i, lj = tx * 4 + j;
-                    const long long gi = xi[li], gj = yj[lj];
-                    double g = 0.0;
-                    if (gi >= 0 && gj >= 0) {
-                        const double uv = bw.lin_u[gi] * bw.lin_v[U ? gj : gj - B.n] * scale;
-                        g = which == 0 ? -uv * kv[i][j] : uv * acc.v[i][j];
-                    }
-                    vals[li][lj] = (float)g;
+            for (int e = 0; e < 16; ++e) {
+                const int li = tile_row(e), lj = tile_col(e);
+                const long long gi = xi[li], gj = yj[lj];
+                double g = 0.0;
+                if (gi >= 0 && gj >= 0) {
+                    const double uv = bw.lin_u[gi] * bw.lin_v[U ? gj : gj - B.n] * scale;
+                    g = which == 0 ? -uv * kv[e] : uv * acc.get(e);
                 }
+                vals[li][lj] = (float)g;
+            }
             __syncthreads();
             float *dst = which == 0 ? bw.rec_sp : bw.rec_nys;
             const int lane = tid & 63, w = tid >> 6;
@@ -574,17 +564,15 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
     // drop pairs an earlier round owns, count the rest
     unsigned mine = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int li = ty * 4 + i, lj = tx * 4 + j;
-            bool present = xi[li] >= 0 && yj[lj] >= 0;
-            bool dup = false;
-            for (int q = 0; q < r; ++q) dup |= bx[q][li] == by[q][lj];
-            if (!present || dup) kv[i][j] = log_values ? -INFINITY : 0.0;
-            if (present && !dup) ++mine;
-            vals[li][lj] = (float)kv[i][j];
-        }
+    for (int e = 0; e < 16; ++e) {
+        const int li = tile_row(e), lj = tile_col(e);
+        bool present = xi[li] >= 0 && yj[lj] >= 0;
+        bool dup = false;
+        for (int q = 0; q < r; ++q) dup |= bx[q][li] == by[q][lj];
+        if (!present || dup) kv[e] = log_values ? -INFINITY : 0.0;
+        if (present && !dup) ++mine;
+        vals[li][lj] = (float)kv[e];
+    }
     atomicAdd(&cnt_sh, mine);
     __syncthreads();
     if (tid == 0) atomicAdd(unique_counter, (unsigned long long)cnt_sh);
@@ -603,8 +591,7 @@ hipError_t launch_correction(const Handle &h, int ntiles, hipStream_t s)
     if (ntiles <= 0) return hipSuccess;
     const bool lcn_mode = h.mode == LCN_MODE_LCN;
     hipLaunchKernelGGL(correction_kernel, dim3(ntiles), dim3(256), 0, s, h.sort, h.Z, h.d, h.cost, 1.0 / h.lambda,
-                       h.cost == LCN_COST_COSINE ? h.zn : (const double *)nullptr,
-                       lcn_mode ? h.U : (const float *)nullptr, lcn_mode ? h.Wt : (const float *)nullptr, h.lp,
+                       h.zn, lcn_mode ? h.U : (const float *)nullptr, lcn_mode ? h.Wt : (const float *)nullptr, h.lp,
                        h.log_domain, h.vals_x, h.vals_y, h.counters + 3, BackwardArgs{});
     return hipGetLastError();
 }
@@ -623,7 +610,7 @@ hipError_t launch_backward_pattern(const Handle &h, float *rec_sp, float *rec_ny
     bw.rec_sp = rec_sp;
     bw.rec_nys = rec_nys;
     hipLaunchKernelGGL(correction_kernel, dim3(h.ntiles), dim3(256), 0, s, h.sort, h.Z, h.d, h.cost, 1.0 / h.lambda,
-                       h.cost == LCN_COST_COSINE ? h.zn : (const double *)nullptr, h.U, h.Wt, h.lp, 0,
+                       h.zn, h.U, h.Wt, h.lp, 0,
                        (float *)nullptr, (float *)nullptr, (unsigned long long *)nullptr, bw);
     return hipGetLastError();
 }
@@ -679,17 +666,14 @@ __global__ __launch_bounds__(256) void plan_nystrom_kernel(const float *__restri
         stage_rows(Ps, U, lp, xi, k0, lp);
         stage_rows(Cs, Wt, lp, yj, k0, lp);
         __syncthreads();
-        tile_fma<false>(acc, Ps, Cs);
+        tile_mma(acc, Ps, Cs);
     }
     const double scale = exp(acc_y[lp] + acc_z[lp]);  // exponents taken out of v and u
-    const int tx = tid & 15, ty = tid >> 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const long long gi = xi[ty * 4 + i], gj = yj[tx * 4 + j];
-            if (gi >= 0 && gj >= 0) out[(gi - i0) * m + gj] = (float)(acc.v[i][j] * lin_u[gi] * lin_v[gj] * scale);
-        }
+    for (int e = 0; e < 16; ++e) {
+        const long long gi = xi[tile_row(e)], gj = yj[tile_col(e)];
+        if (gi >= 0 && gj >= 0) out[(gi - i0) * m + gj] = (float)(acc.get(e) * lin_u[gi] * lin_v[gj] * scale);
+    }
 }
 
 hipError_t launch_plan_nystrom(const Handle &h, long long i0, long long nrows, float *out, hipStream_t s)

@@ -660,22 +660,21 @@ struct Builder {
             lane_used[1] = lane_used[2] = true;
         }
         const float *Xz = h.Z, *Yz = h.Z + (long long)n * d;
-        const bool cosn = cost == LCN_COST_COSINE;
-        if (cosn) HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, fs));
-        if (cosn && forked) {   // the landmarks' norms are an input of U and V as well
+        HIPCHK(launch_sqnorms(h.L, h.l, d, sc.ln, fs));   // every cost is formed from dot products and norms
+        if (forked) {   // the landmarks' norms are an input of U and V as well
             HIPCHK(hipEventRecord(extra[0], fs));
             HIPCHK(hipStreamWaitEvent(us, extra[0], 0));
             HIPCHK(hipStreamWaitEvent(vs, extra[0], 0));
         }
         HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, us));
-        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, cosn ? h.zn : nullptr, cosn ? sc.ln : nullptr,
+        HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, h.zn, sc.ln,
                                     h.U, nullptr, h.lp, us));
-        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, cosn ? h.zn + n : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.Vt64, h.l, vs));
+        HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, h.zn + n, sc.ln,
+                                    nullptr, sc.Vt64, h.l, vs));
         if (forked) HIPCHK(hipEventRecord(extra[1], vs));   // V done
         HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
-        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, cosn ? sc.ln : nullptr,
-                                    cosn ? sc.ln : nullptr, nullptr, sc.A64, h.l, fs));
+        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, sc.ln, sc.ln,
+                                    nullptr, sc.A64, h.l, fs));
         HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
         if (forked) HIPCHK(hipStreamWaitEvent(fs, extra[1], 0));
         // W^T = V^T A^{-1} (A^{-1} is symmetric)
