@@ -77,8 +77,15 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
     struct RowData {
         FRow<T> f;
         float tv[RR];
-        double vv[RR];
+        float vv[RR];
     };
+    // The bucket-ordered copies of the scalings are single precision in this kernel (the buffers are
+    // sized for doubles; the logarithmic kernels keep doubles there): they are gathered once per
+    // stored value, and at half the size they stay in the per-die cache beside the streamed rows.
+    // The exponent taken out keeps the largest entry near one; an entry 2^-126 below it counts as zero,
+    // like a kernel value of that size in the single-precision factors and sparse values.
+    const float *__restrict__ perm_in = reinterpret_cast<const float *>(S.perm_in);
+    float *__restrict__ perm_out = reinterpret_cast<float *>(S.perm_out);
     // Loads are issued for whole wavefront-wide chunks without predication: lanes
     // beyond a segment's length read the next stored values (masked when used; the
     // arrays end with 64 entries of slack) and the zero slot behind the gathered vector.
@@ -91,7 +98,7 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
 #pragma unroll
             for (int q = 0; q < RR; ++q) {
                 D.tv[q] = vals[off];
-                D.vv[q] = S.perm_in[lane < M.len[q] ? (unsigned)M.vstart[q] + lane : zero_slot];
+                D.vv[q] = perm_in[lane < M.len[q] ? (unsigned)M.vstart[q] + lane : zero_slot];
                 off += (unsigned)M.len[q];
             }
         }
@@ -135,7 +142,7 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
         } else {
             double acc = 0.0;
 #pragma unroll
-            for (int q = 0; q < RR; ++q) acc = fma((double)(lane < mc.len[q] ? C.tv[q] : 0.f), C.vv[q], acc);
+            for (int q = 0; q < RR; ++q) acc = fma((double)(lane < mc.len[q] ? C.tv[q] : 0.f), (double)C.vv[q], acc);
             {   // what is left of segments longer than a wavefront
                 const float *__restrict__ vals = S.vals + mc.base;
                 int off = 0;
@@ -144,10 +151,10 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
                     if (mc.len[q] > 64) {
                         // 256 entries per trip, all eight loads requested before the first is used
                         const float *tp = vals + off;
-                        const double *vp = S.perm_in + mc.vstart[q];
+                        const float *vp = perm_in + mc.vstart[q];
                         for (int e0 = 64; e0 < mc.len[q]; e0 += 256) {
                             float tt[4];
-                            double pv[4];
+                            float pv[4];
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const int e = e0 + 64 * k + lane;
@@ -157,7 +164,7 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
                                 if (!ok) tt[k] = 0.f;
                             }
 #pragma unroll
-                            for (int k = 0; k < 4; ++k) acc = fma((double)tt[k], pv[k], acc);
+                            for (int k = 0; k < 4; ++k) acc = fma((double)tt[k], (double)pv[k], acc);
                         }
                     }
                     off += mc.len[q];
@@ -196,7 +203,7 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
         }
         if (MODE != PASS_QUERY) {
             if (lane == 0) S.lin_out[row] = out;
-            if (lane < R) S.perm_out[(long long)lane * S.rows + mc.pos] = out;
+            if (lane < R) perm_out[(long long)lane * S.rows + mc.pos] = (float)out;
             if (T > 0) {
 #pragma unroll
                 for (int t = 0; t < TT; ++t) zacc[t] = fma((double)C.f.f[t], out, zacc[t]);

@@ -418,8 +418,14 @@ lcn_status status_from_counters(Handle &h)
 lcn_status init_state(Handle &h)
 {
     const size_t R1 = (size_t)(h.R > 0 ? h.R : 1);
+    // the slot behind the bucket-ordered copies that stays zero: entry R n (R m) of an array of doubles
+    // (logarithmic sweeps) or of floats (linear sweeps)
     HIPCHK(hipMemsetAsync(h.perm_u + R1 * h.n, 0, 8 * sizeof(double), h.stream));
     HIPCHK(hipMemsetAsync(h.perm_v + R1 * h.m, 0, 8 * sizeof(double), h.stream));
+    if (!h.log_domain) {
+        HIPCHK(hipMemsetAsync(reinterpret_cast<float *>(h.perm_u) + R1 * h.n, 0, 8 * sizeof(float), h.stream));
+        HIPCHK(hipMemsetAsync(reinterpret_cast<float *>(h.perm_v) + R1 * h.m, 0, 8 * sizeof(float), h.stream));
+    }
     HIPCHK(launch_pass(h, 0, PASS_INIT, -1, 1, nullptr, h.stream));
     HIPCHK(launch_pass(h, 1, PASS_INIT, -1, 0, nullptr, h.stream));
     return LCN_OK;
