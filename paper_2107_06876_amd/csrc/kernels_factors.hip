@@ -115,6 +115,24 @@ __device__ inline double cost_from_dot(double dot, int cost, double pn, double q
     return cost == LCN_COST_EUCLID ? sqrt(sq) : sq;
 }
 
+// Which 64 x 64 tile of a (row tiles x col_tiles) grid a workgroup of a one-dimensional launch takes.
+// Workgroups go to the eight dies in turn, each die with a cache of its own: die x takes the row tiles
+// x, x + 8, ... and runs through all column tiles of one row tile back to back, so the rows of the tall
+// operand are fetched from memory once instead of once per column tile.  (A different dealing of
+// workgroups to dies costs bandwidth, not correctness.)
+__device__ inline void die_tile(int col_tiles, long long &row_tile, int &col_tile)
+{
+    const unsigned w = blockIdx.x, s = w >> 3;
+    col_tile = (int)(s % (unsigned)col_tiles);
+    row_tile = (long long)(s / (unsigned)col_tiles) * 8 + (w & 7);
+}
+
+static unsigned die_grid(long long rows, int cols)
+{
+    const long long rt = (rows + TILE - 1) / TILE, ct = (cols + TILE - 1) / TILE;
+    return (unsigned)((rt + 7) / 8 * 8 * ct);
+}
+
 // ----------------------------------------------------- kernel matrix k(P, Q) --
 
 __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restrict__ P, long long rows,
@@ -127,8 +145,12 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
     __shared__ float Cs[KCH][LDT];
     __shared__ long long pidx[TILE], qidx[TILE];
     const int tid = threadIdx.x;
-    const long long p0 = (long long)blockIdx.x * TILE;
-    const int q0 = blockIdx.y * TILE;
+    long long ptile;
+    int qtile;
+    die_tile((cols + TILE - 1) / TILE, ptile, qtile);
+    const long long p0 = ptile * TILE;
+    const int q0 = qtile * TILE;
+    if (p0 >= rows) return;   // padding of the launch to a multiple of eight row tiles
     if (tid < TILE) {
         pidx[tid] = p0 + tid < rows ? p0 + tid : -1;
         qidx[tid] = q0 + tid < cols ? q0 + tid : -1;
@@ -159,8 +181,8 @@ hipError_t launch_kernel_matrix(const float *P, long long rows, const float *Q, 
                                 double lambda, const double *pn, const double *qn, float *out32, double *out64,
                                 int ldo, hipStream_t s)
 {
-    dim3 grid((unsigned)((rows + TILE - 1) / TILE), (unsigned)((cols + TILE - 1) / TILE));
-    hipLaunchKernelGGL(kernel_matrix_kernel, grid, dim3(256), 0, s, P, rows, Q, cols, d, cost, 1.0 / lambda, pn, qn,
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL(kernel_matrix_kernel, dim3(die_grid(rows, cols)), dim3(256), 0, s, P, rows, Q, cols, d, cost, 1.0 / lambda, pn, qn,
                        out32, out64, ldo);
     return hipGetLastError();
 }
@@ -188,8 +210,12 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const double *A, int lda, i
     __shared__ double As[KC][TILE + 2];
     __shared__ double Bs[KC][TILE + 2];
     const int tid = threadIdx.x;
-    const long long r0 = (long long)blockIdx.x * TILE;
-    const int c0 = blockIdx.y * TILE;
+    long long rtile;
+    int ctile;
+    die_tile((N + TILE - 1) / TILE, rtile, ctile);
+    const long long r0 = rtile * TILE;
+    const int c0 = ctile * TILE;
+    if (r0 >= M) return;   // padding of the launch to a multiple of eight row tiles
     const int wv = tid >> 6, ln = tid & 63;
     const int ar = 32 * (wv >> 1) + (ln & 15), bc = 32 * (wv & 1) + (ln & 15), kq4 = ln >> 4;
     TileAcc acc;
@@ -262,8 +288,7 @@ static void gemm64(const double *A, int lda, bool tA, const double *B, int ldb, 
                    long long M, int N, int K, double alpha, double beta, float *C32, int ldc32, hipStream_t s)
 {
     if (M <= 0 || N <= 0) return;
-    dim3 grid((unsigned)((M + TILE - 1) / TILE), (unsigned)((N + TILE - 1) / TILE));
-    hipLaunchKernelGGL(gemm64_kernel, grid, dim3(256), 0, s, A, lda, tA ? 1 : 0, B, ldb, tB ? 1 : 0, C, ldc, M, N, K,
+    hipLaunchKernelGGL(gemm64_kernel, dim3(die_grid(M, N)), dim3(256), 0, s, A, lda, tA ? 1 : 0, B, ldb, tB ? 1 : 0, C, ldc, M, N, K,
                        alpha, beta, C32, ldc32);
 }
 
