@@ -302,19 +302,44 @@ hipError_t launch_gemm_f64(const double *A, const double *B, long long M, int N,
 // One workgroup of 256 threads: Cholesky factor of the nb x nb diagonal block at (j0, j0) of Lm
 // (ridge added to its diagonal), written back into Lm's lower triangle, and the inverse of that
 // triangular factor into Dinv (NB x NB, zero above the diagonal and outside nb).
-// Factorisation: thread (ty, tx) of a 16 x 16 grid keeps the 4 x 4 patch rows 4ty.., columns 4tx..
-// in registers; at step j the owners of column j publish it (unscaled) through LDS and everybody
-// subtracts l_ij l_kj with l_ij = s_ij / sqrt(s_jj): one barrier per column.  A block smaller than
-// NB is padded with the identity.  Inversion: thread c < 64 solves column c by forward
-// substitution, its column in registers, L read from LDS as broadcasts.
+// A block smaller than NB is padded with the identity.  The block is worked through in panels of
+// PB columns: one wavefront factors the panel's PB x PB diagonal part with a row per lane (the
+// pivot column is passed on by lane reads, no barrier), a thread per row below solves against it,
+// and all threads update the columns to the right, which they hold as 4 x 4 register patches
+// (thread (ty, tx): rows 4 ty.., columns 4 tx..).  Three barriers per panel.  The inverse is built
+// from the inverses of the 16 x 16 diagonal parts (a thread per column, forward substitution) and
+// three rounds of 16 x 16 block products, X_ij = -X_ii sum_k L_ik X_kj.
+constexpr int PB = 8;            // panel width
+constexpr int CB = 16;           // block size of the inverse
+constexpr int CLD = NB + 1;      // row stride of the LDS copies
+constexpr size_t CHOL_LDS = sizeof(double) * (2 * NB * CLD + 3 * CB * CB + NB);
+
+__device__ inline double lane_read64(double v, int lane)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// 1 / sqrt(x) to fp64 rounding for positive normal x: hardware estimate and two Newton steps
+__device__ inline double rsqrt64(double x)
+{
+    double r = __builtin_amdgcn_rsq(x);
+    r = fma(0.5 * r, fma(-x * r, r, 1.0), r);
+    r = fma(0.5 * r, fma(-x * r, r, 1.0), r);
+    return r;
+}
+
 __global__ __launch_bounds__(256) void chol_diag_kernel(double *Lm, int l, int j0, int nb, double ridge, double *Dinv,
                                                         int *fail_flag)
 {
-    static_assert(NB == 64, "16 x 16 threads with 4 x 4 patches");
-    __shared__ double colbuf[2][NB];
-    __shared__ double rs_sh[NB];          // 1 / L_jj
-    __shared__ double Ls[NB][NB + 1];
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    extern __shared__ double chol_lds[];
+    double (*As)[CLD] = reinterpret_cast<double (*)[CLD]>(chol_lds);                 // the block, then L
+    double (*Xs)[CLD] = reinterpret_cast<double (*)[CLD]>(chol_lds + NB * CLD);      // L^{-1}
+    double (*Ts)[CB][CB] = reinterpret_cast<double (*)[CB][CB]>(chol_lds + 2 * NB * CLD);
+    double *rs_sh = chol_lds + 2 * NB * CLD + 3 * CB * CB;                           // 1 / L_jj
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
     double p[4][4];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -324,68 +349,131 @@ __global__ __launch_bounds__(256) void chol_diag_kernel(double *Lm, int l, int j
             double v = (i == k) ? 1.0 : 0.0;
             if (i < nb && k < nb) v = Lm[(long long)(j0 + i) * l + j0 + k] + (i == k ? ridge : 0.0);
             p[a][b] = v;
+            Xs[i][k] = 0.0;
         }
     bool fail = false;
-    for (int j = 0; j < NB; ++j) {
-        double *cb = colbuf[j & 1];
-        if (tx == (j >> 2)) {
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                double v = p[a][0];
-                if ((j & 3) == 1) v = p[a][1];
-                if ((j & 3) == 2) v = p[a][2];
-                if ((j & 3) == 3) v = p[a][3];
-                cb[4 * ty + a] = v;
-            }
-        }
-        __syncthreads();
-        double dd = cb[j];
-        if (!(dd > 0.0)) {
-            fail = true;
-            dd = 1.0;
-        }
-        const double rs = 1.0 / sqrt(dd);
-        if (tid == 0) rs_sh[j] = rs;
-        if (4 * tx + 3 > j && tx <= ty) {   // some column of the patch is still to the right of j, patch on or below the diagonal
-            double li[4], lk[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) li[a] = cb[4 * ty + a] * rs;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) lk[b] = cb[4 * tx + b] * rs;
+    for (int sb = 0; sb < NB / PB; ++sb) {
+        const int c0 = PB * sb;
+        // the panel's columns leave the registers (rows above the panel are not needed any more)
+        if ((4 * tx) / PB == sb && ty >= tx) {
 #pragma unroll
             for (int a = 0; a < 4; ++a)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int i = 4 * ty + a, k = 4 * tx + b;
-                    if (k > j && k <= i) p[a][b] -= li[a] * lk[b];
+                for (int b = 0; b < 4; ++b) As[4 * ty + a][4 * tx + b] = p[a][b];
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane r < 16 holds row c0 + r of the diagonal part; entries right of the diagonal are never used
+            const int r = tid & (PB - 1);
+            double a[PB];
+#pragma unroll
+            for (int k = 0; k < PB; ++k) a[k] = As[c0 + r][c0 + k];
+#pragma unroll
+            for (int c = 0; c < PB; ++c) {
+                double dd = lane_read64(a[c], c);
+                if (!(dd > 0.0)) {
+                    fail = true;
+                    dd = 1.0;
                 }
+                const double rs = rsqrt64(dd);
+                if (tid == 0) rs_sh[c0 + c] = rs;
+                a[c] *= rs;
+#pragma unroll
+                for (int k = c + 1; k < PB; ++k) a[k] = fma(-a[c], lane_read64(a[c], k), a[k]);
+            }
+            if (tid < PB) {
+#pragma unroll
+                for (int k = 0; k < PB; ++k) As[c0 + r][c0 + k] = a[k];
+            }
+        }
+        __syncthreads();
+        // rows below the diagonal part: x L11^T = a, a thread per row
+        const int below = NB - c0 - PB;
+        if (tid < below) {
+            const int r = c0 + PB + tid;
+            double x[PB];
+#pragma unroll
+            for (int k = 0; k < PB; ++k) x[k] = As[r][c0 + k];
+#pragma unroll
+            for (int q = 0; q < PB; ++q) {   // column q is final: take it out of the columns to its right
+                x[q] *= rs_sh[c0 + q];
+#pragma unroll
+                for (int k = q + 1; k < PB; ++k) x[k] = fma(-x[q], As[c0 + k][c0 + q], x[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < PB; ++k) As[r][c0 + k] = x[k];
+        }
+        __syncthreads();
+        // columns to the right of the panel, on or below the diagonal
+        if (4 * tx >= c0 + PB && tx <= ty) {
+#pragma unroll
+            for (int kk = 0; kk < PB; ++kk) {
+                double li[4], lk[4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) li[a] = As[4 * ty + a][c0 + kk];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) lk[b] = As[4 * tx + b][c0 + kk];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) p[a][b] = fma(-li[a], lk[b], p[a][b]);
+            }
         }
     }
     if (fail && tid == 0) *fail_flag = 1;
-    __syncthreads();   // rs_sh complete
+    // As holds L on and below the diagonal
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const int i = 4 * ty + a, k = 4 * tx + b;
-            const double v = k <= i ? p[a][b] * rs_sh[k] : 0.0;   // column k was final once step k - 1 was done
-            Ls[i][k] = v;
-            if (i < nb && k <= i) Lm[(long long)(j0 + i) * l + j0 + k] = v;
+            if (i < nb && k <= i) Lm[(long long)(j0 + i) * l + j0 + k] = As[i][k];
         }
-    __syncthreads();
+    // inverses of the four diagonal parts: thread c takes column c % 16 of part c / 16
     if (tid < NB) {
-        const int c = tid;
-        double xc[NB];
+        const int base = tid & ~(CB - 1), cc = tid & (CB - 1);
+        double x[CB];
 #pragma unroll
-        for (int r = 0; r < NB; ++r) {
-            double t = (r == c) ? 1.0 : 0.0;
+        for (int r = 0; r < CB; ++r) x[r] = (r == cc) ? 1.0 : 0.0;
 #pragma unroll
-            for (int k = 0; k < r; ++k) t = fma(-Ls[r][k], xc[k], t);   // xc[k] = 0 for k < c
-            xc[r] = r >= c ? t * rs_sh[r] : 0.0;
+        for (int k = 0; k < CB; ++k) {   // x[k] is final (zero above row cc): take it out of the rows below
+            x[k] *= rs_sh[base + k];
+#pragma unroll
+            for (int r = k + 1; r < CB; ++r) x[r] = fma(-As[base + r][base + k], x[k], x[r]);
         }
 #pragma unroll
-        for (int r = 0; r < NB; ++r) Dinv[r * NB + c] = (r < nb && c < nb) ? xc[r] : 0.0;
+        for (int r = 0; r < CB; ++r) Xs[base + r][base + cc] = x[r];
     }
+    __syncthreads();
+    // parts further and further below the diagonal
+    const int er = tid >> 4, ec = tid & 15;
+    for (int dist = 1; dist < NB / CB; ++dist) {
+        for (int i = dist; i < NB / CB; ++i) {
+            const int j = i - dist;
+            double t = 0.0;
+            for (int kb = j; kb < i; ++kb) {
+#pragma unroll
+                for (int k = 0; k < CB; ++k) t = fma(As[CB * i + er][CB * kb + k], Xs[CB * kb + k][CB * j + ec], t);
+            }
+            Ts[i - dist][er][ec] = t;
+        }
+        __syncthreads();
+        for (int i = dist; i < NB / CB; ++i) {
+            const int j = i - dist;
+            double t = 0.0;
+#pragma unroll
+            for (int k = 0; k < CB; ++k) t = fma(Xs[CB * i + er][CB * i + k], Ts[i - dist][k][ec], t);
+            Xs[CB * i + er][CB * j + ec] = -t;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int i = 4 * ty + a, k = 4 * tx + b;
+            Dinv[i * NB + k] = (i < nb && k < nb) ? Xs[i][k] : 0.0;
+        }
 }
 
 __global__ void copy_f64_kernel(const double *src, double *dst, long long count)
@@ -413,12 +501,15 @@ hipError_t launch_spd_inverse(double *A, int l, double ridge, double *Lm, double
     hipLaunchKernelGGL(copy_f64_kernel, dim3((unsigned)((ll + 255) / 256)), dim3(256), 0, s, A, Lm, ll);
     hipError_t e = hipMemsetAsync(Xm, 0, sizeof(double) * (size_t)ll, s);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)chol_diag_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)CHOL_LDS);
+    if (e != hipSuccess) return e;
     const int panels = (l + NB - 1) / NB;
     for (int p = 0; p < panels; ++p) {
         const int j0 = p * NB;
         const int nb = l - j0 < NB ? l - j0 : NB;
         double *Dp = Dinv + (long long)p * NB * NB;
-        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(256), 0, s, Lm, l, j0, nb, ridge, Dp, fail_flag);
+        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(256), CHOL_LDS, s, Lm, l, j0, nb, ridge, Dp, fail_flag);
         const int below = l - j0 - nb;
         if (below > 0) {
             double *A21 = Lm + (long long)(j0 + nb) * l + j0;

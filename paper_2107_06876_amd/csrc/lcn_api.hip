@@ -431,8 +431,11 @@ lcn_status init_state(Handle &h)
     return LCN_OK;
 }
 
-// KM_LANES streams per device for the process (default priority, not synchronising with the null
-// stream), created on first use and never destroyed.  False if they cannot be had.
+// KM_LANES - 1 streams per device for the process (default priority, not synchronising with the null
+// stream), created on first use and never destroyed; the last lane is the caller's stream, which
+// would otherwise idle while the lanes work (a process has four hardware queues by default, and a
+// fifth stream would share one of them with another lane and run in turn with it).  False if they
+// cannot be had.
 bool lane_streams(hipStream_t (&out)[KM_LANES])
 {
     static std::mutex mu;
@@ -442,7 +445,7 @@ bool lane_streams(hipStream_t (&out)[KM_LANES])
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
     std::lock_guard<std::mutex> lock(mu);
     if (!ready[dev]) {
-        for (int q = 0; q < KM_LANES; ++q) {
+        for (int q = 0; q < KM_LANES - 1; ++q) {
             if (!streams[dev][q] && hipStreamCreateWithFlags(&streams[dev][q], hipStreamNonBlocking) != hipSuccess) {
                 (void)hipGetLastError();
                 streams[dev][q] = nullptr;
@@ -451,7 +454,7 @@ bool lane_streams(hipStream_t (&out)[KM_LANES])
         }
         ready[dev] = true;
     }
-    for (int q = 0; q < KM_LANES; ++q) out[q] = streams[dev][q];
+    for (int q = 0; q < KM_LANES - 1; ++q) out[q] = streams[dev][q];
     return true;
 }
 
@@ -522,6 +525,7 @@ struct Builder {
     {
         (void)hipGetDevice(&device_id);
         forked = overlap && lane_streams(lane);
+        lane[KM_LANES - 1] = h.stream;
         if (!forked)
             for (int q = 0; q < KM_LANES; ++q) lane[q] = h.stream;
         HIPCHK(hipEventCreate(&h.ev0));
