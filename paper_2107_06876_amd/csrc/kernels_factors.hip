@@ -80,21 +80,55 @@ __device__ inline void stage_rows(float (*dst)[LDT], const float *__restrict__ b
     }
 }
 
+// The same in two halves, so that a chunk's loads are in flight while the chunk before it is
+// multiplied: 64 rows x KCH features into registers (row index + rowoff, absent if negative) ...
+__device__ inline void fetch_rows(float (&v)[8], const float *__restrict__ base, long long ld,
+                                  const long long *rowidx, long long rowoff, int k0, int kmax)
+{
+    const int kk = threadIdx.x & 31, r0 = threadIdx.x >> 5;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+        const long long src = rowidx[r0 + pass * 8];
+        v[pass] = (src >= 0 && k0 + kk < kmax) ? base[(src + rowoff) * ld + k0 + kk] : 0.f;
+    }
+}
+
+// ... and from the registers into dst[k][row]
+__device__ inline void store_rows(float (*dst)[LDT], const float (&v)[8])
+{
+    const int kk = threadIdx.x & 31, r0 = threadIdx.x >> 5;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) dst[kk][r0 + pass * 8] = v[pass];
+}
+
 // acc += P_chunk Q_chunk^T for the KCH staged features (dot products; the staged values are fp32,
-// products and sums fp64)
-__device__ inline void tile_mma(TileAcc &acc, const float (*Ps)[LDT], const float (*Cs)[LDT])
+// products and sums fp64).  Only the first `rows` rows and `cols` columns of the tile hold points:
+// an instruction tile of 16 x 16 that lies wholly outside is skipped (its accumulators stay zero).
+__device__ inline void tile_mma(TileAcc &acc, const float (*Ps)[LDT], const float (*Cs)[LDT], int rows = TILE,
+                                int cols = TILE)
 {
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
-    const int r0 = 32 * (w >> 1) + (l & 15), c0 = 32 * (w & 1) + (l & 15), kq = l >> 4;
+    const int rw = 32 * (w >> 1), cw = 32 * (w & 1);
+    const int r0 = rw + (l & 15), c0 = cw + (l & 15), kq = l >> 4;
+    const bool ra = rw < rows, rb = rw + 16 < rows, ca = cw < cols, cb = cw + 16 < cols;   // wave-uniform
+    if (!ra || !ca) return;
 #pragma unroll
     for (int ks = 0; ks < KCH / 4; ++ks) {
         const int k = 4 * ks + kq;
-        const double a0 = (double)Ps[k][r0], a1 = (double)Ps[k][r0 + 16];
-        const double b0 = (double)Cs[k][c0], b1 = (double)Cs[k][c0 + 16];
+        const double a0 = (double)Ps[k][r0], b0 = (double)Cs[k][c0];
         acc.t[0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc.t[0], 0, 0, 0);
-        acc.t[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc.t[1], 0, 0, 0);
-        acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.t[2], 0, 0, 0);
-        acc.t[3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc.t[3], 0, 0, 0);
+        if (cb) {
+            const double b1 = (double)Cs[k][c0 + 16];
+            acc.t[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc.t[1], 0, 0, 0);
+            if (rb) {
+                const double a1 = (double)Ps[k][r0 + 16];
+                acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.t[2], 0, 0, 0);
+                acc.t[3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc.t[3], 0, 0, 0);
+            }
+        } else if (rb) {
+            const double a1 = (double)Ps[k][r0 + 16];
+            acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.t[2], 0, 0, 0);
+        }
     }
 }
 
@@ -609,45 +643,52 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
         for (int q = 0; q < r; ++q) by[q][t] = gj >= 0 ? B.bucket[(long long)q * N + B.n + gj] : -2;
     }
     if (tid == 0) cnt_sh = 0;
+    const int rows_here = nx - ti * 64 < 64 ? nx - ti * 64 : 64;   // members of the bucket in this piece
+    const int cols_here = ny - tj * 64 < 64 ? ny - tj * 64 : 64;
 
+    // One run of chunks: the features of the points (exact cost), then, in the lcn mode, the
+    // Nystrom value on the same pairs, sum_k U[i][k] Wt[j][k].  The loads of a chunk are requested
+    // before the chunk ahead of it is multiplied.
+    const int nd = (d + KCH - 1) / KCH, nl = U ? (lp + KCH - 1) / KCH : 0;
+    float pv[8], cv[8];
+    auto fetch = [&](int c) {
+        if (c < nd) {
+            fetch_rows(pv, Z, d, xi, 0, c * KCH, d);
+            fetch_rows(cv, Z, d, yj, 0, c * KCH, d);
+        } else {
+            fetch_rows(pv, U, lp, xi, 0, (c - nd) * KCH, lp);
+            fetch_rows(cv, Wt, lp, yj, -(long long)B.n, (c - nd) * KCH, lp);   // yj: rows of Z; Wt has the rows of Y
+        }
+    };
     TileAcc acc;
     tile_zero(acc);
-    for (int k0 = 0; k0 < d; k0 += KCH) {
-        __syncthreads();
-        stage_rows(Ps, Z, d, xi, k0, d);
-        stage_rows(Cs, Z, d, yj, k0, d);
-        __syncthreads();
-        tile_mma(acc, Ps, Cs);
-    }
     double kv[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const long long gi = xi[tile_row(e)], gj = yj[tile_col(e)];
-        double v = 0.0;
-        if (gi >= 0 && gj >= 0) {
-            const double c = cost_from_dot(acc.get(e), cost, zn[gi], zn[gj]);
-            v = log_values ? -c * inv_lambda : exp(-c * inv_lambda);
-        }
-        kv[e] = v;
-    }
-    if (U) {
-        // Nystrom value on the same pairs: sum_k U[i][k] * Wt[j][k]
+    __syncthreads();   // xi, yj
+    fetch(0);
+    for (int c = 0; c < nd + nl; ++c) {
         __syncthreads();
-        if (tid < TILE) {
-            if (yj[tid] >= 0) yj[tid] -= B.n;  // back to a row of Wt
-        }
-        tile_zero(acc);
-        for (int k0 = 0; k0 < lp; k0 += KCH) {
-            __syncthreads();
-            stage_rows(Ps, U, lp, xi, k0, lp);
-            stage_rows(Cs, Wt, lp, yj, k0, lp);
-            __syncthreads();
-            tile_mma(acc, Ps, Cs);
-        }
-        if (!bw.lin_u) {
+        store_rows(Ps, pv);
+        store_rows(Cs, cv);
+        __syncthreads();
+        if (c + 1 < nd + nl) fetch(c + 1);
+        tile_mma(acc, Ps, Cs, rows_here, cols_here);
+        if (c == nd - 1) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) kv[e] -= acc.get(e);
+            for (int e = 0; e < 16; ++e) {
+                const long long gi = xi[tile_row(e)], gj = yj[tile_col(e)];
+                double v = 0.0;
+                if (gi >= 0 && gj >= 0) {
+                    const double cc = cost_from_dot(acc.get(e), cost, zn[gi], zn[gj]);
+                    v = log_values ? -cc * inv_lambda : exp(-cc * inv_lambda);
+                }
+                kv[e] = v;
+            }
+            tile_zero(acc);
         }
+    }
+    if (U && !bw.lin_u) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) kv[e] -= acc.get(e);
     }
     if (bw.lin_u) {
         // derivatives instead of kernel values (Prop. 1): -lambda u_i K^sp_ij v_j and, from the
@@ -661,7 +702,7 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
                 const long long gi = xi[li], gj = yj[lj];
                 double g = 0.0;
                 if (gi >= 0 && gj >= 0) {
-                    const double uv = bw.lin_u[gi] * bw.lin_v[U ? gj : gj - B.n] * scale;
+                    const double uv = bw.lin_u[gi] * bw.lin_v[gj - B.n] * scale;
                     g = which == 0 ? -uv * kv[e] : uv * acc.get(e);
                 }
                 vals[li][lj] = (float)g;
