@@ -10,7 +10,7 @@ namespace lcn {
 
 constexpr int TILE = 64;
 constexpr int KCH = 32;
-constexpr int LDT = TILE + 4;
+constexpr int LDK = KCH + 4;   // row stride of a staged chunk: rows 36 words apart put a wave's 64 operand reads on 64 banks
 
 // ------------------------------------------------------------ row norms --
 
@@ -63,8 +63,8 @@ __device__ inline int tile_col(int e)
     return 32 * (w & 1) + 16 * ((e >> 2) & 1) + (l & 15);
 }
 
-// stage 64 rows x KCH features of a row-major matrix into dst[k][row]
-__device__ inline void stage_rows(float (*dst)[LDT], const float *__restrict__ base, long long ld,
+// stage 64 rows x KCH features of a row-major matrix into dst[row][k]
+__device__ inline void stage_rows(float (*dst)[LDK], const float *__restrict__ base, long long ld,
                                   const long long *rowidx /* LDS, 64 entries, -1 = absent */, int k0, int kmax)
 {
     const int tid = threadIdx.x;
@@ -76,7 +76,7 @@ __device__ inline void stage_rows(float (*dst)[LDT], const float *__restrict__ b
         long long src = rowidx[r];
         float v = 0.f;
         if (src >= 0 && k0 + kk < kmax) v = base[src * ld + k0 + kk];
-        dst[kk][r] = v;
+        dst[r][kk] = v;
     }
 }
 
@@ -93,18 +93,18 @@ __device__ inline void fetch_rows(float (&v)[8], const float *__restrict__ base,
     }
 }
 
-// ... and from the registers into dst[k][row]
-__device__ inline void store_rows(float (*dst)[LDT], const float (&v)[8])
+// ... and from the registers into dst[row][k]
+__device__ inline void store_rows(float (*dst)[LDK], const float (&v)[8])
 {
     const int kk = threadIdx.x & 31, r0 = threadIdx.x >> 5;
 #pragma unroll
-    for (int pass = 0; pass < 8; ++pass) dst[kk][r0 + pass * 8] = v[pass];
+    for (int pass = 0; pass < 8; ++pass) dst[r0 + pass * 8][kk] = v[pass];
 }
 
 // acc += P_chunk Q_chunk^T for the KCH staged features (dot products; the staged values are fp32,
 // products and sums fp64).  Only the first `rows` rows and `cols` columns of the tile hold points:
 // an instruction tile of 16 x 16 that lies wholly outside is skipped (its accumulators stay zero).
-__device__ inline void tile_mma(TileAcc &acc, const float (*Ps)[LDT], const float (*Cs)[LDT], int rows = TILE,
+__device__ inline void tile_mma(TileAcc &acc, const float (*Ps)[LDK], const float (*Cs)[LDK], int rows = TILE,
                                 int cols = TILE)
 {
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
@@ -112,23 +112,24 @@ __device__ inline void tile_mma(TileAcc &acc, const float (*Ps)[LDT], const floa
     const int r0 = rw + (l & 15), c0 = cw + (l & 15), kq = l >> 4;
     const bool ra = rw < rows, rb = rw + 16 < rows, ca = cw < cols, cb = cw + 16 < cols;   // wave-uniform
     if (!ra || !ca) return;
+    // Lane quarter kq feeds features 8 kq .. 8 kq + 7 of the chunk, one per instruction (the order
+    // in which a dot product's terms are added is free): eight consecutive floats per operand row.
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    auto row8 = [&](const float (*M)[LDK], int r, float (&o)[8]) {
+        const f4 lo = *(const f4 *)&M[r][8 * kq], hi = *(const f4 *)&M[r][8 * kq + 4];
+        o[0] = lo.x, o[1] = lo.y, o[2] = lo.z, o[3] = lo.w, o[4] = hi.x, o[5] = hi.y, o[6] = hi.z, o[7] = hi.w;
+    };
+    float a0[8], b0[8], a1[8] = {}, b1[8] = {};
+    row8(Ps, r0, a0);
+    row8(Cs, c0, b0);
+    if (rb) row8(Ps, r0 + 16, a1);
+    if (cb) row8(Cs, c0 + 16, b1);
 #pragma unroll
     for (int ks = 0; ks < KCH / 4; ++ks) {
-        const int k = 4 * ks + kq;
-        const double a0 = (double)Ps[k][r0], b0 = (double)Cs[k][c0];
-        acc.t[0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc.t[0], 0, 0, 0);
-        if (cb) {
-            const double b1 = (double)Cs[k][c0 + 16];
-            acc.t[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc.t[1], 0, 0, 0);
-            if (rb) {
-                const double a1 = (double)Ps[k][r0 + 16];
-                acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.t[2], 0, 0, 0);
-                acc.t[3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc.t[3], 0, 0, 0);
-            }
-        } else if (rb) {
-            const double a1 = (double)Ps[k][r0 + 16];
-            acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.t[2], 0, 0, 0);
-        }
+        acc.t[0] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a0[ks], (double)b0[ks], acc.t[0], 0, 0, 0);
+        if (cb) acc.t[1] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a0[ks], (double)b1[ks], acc.t[1], 0, 0, 0);
+        if (rb) acc.t[2] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a1[ks], (double)b0[ks], acc.t[2], 0, 0, 0);
+        if (rb && cb) acc.t[3] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a1[ks], (double)b1[ks], acc.t[3], 0, 0, 0);
     }
 }
 
@@ -175,8 +176,8 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
                                                             const double *__restrict__ qn, float *out32,
                                                             double *out64, int ldo)
 {
-    __shared__ float Ps[KCH][LDT];
-    __shared__ float Cs[KCH][LDT];
+    __shared__ __align__(16) float Ps[TILE][LDK];
+    __shared__ __align__(16) float Cs[TILE][LDK];
     __shared__ long long pidx[TILE], qidx[TILE];
     const int tid = threadIdx.x;
     long long ptile;
@@ -586,8 +587,8 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
                                                          int lp, int log_values, float *vals_x, float *vals_y,
                                                          unsigned long long *unique_counter, BackwardArgs bw)
 {
-    __shared__ float Ps[KCH][LDT];
-    __shared__ float Cs[KCH][LDT];
+    __shared__ __align__(16) float Ps[TILE][LDK];
+    __shared__ __align__(16) float Cs[TILE][LDK];
     __shared__ float vals[TILE][TILE + 1];
     __shared__ long long xi[TILE], yj[TILE];
     __shared__ long long xdst[TILE], ydst[TILE];  // where each row's / column's slice of this block starts
@@ -805,8 +806,8 @@ __global__ __launch_bounds__(256) void plan_nystrom_kernel(const float *__restri
                                                            const double *__restrict__ acc_y,
                                                            const double *__restrict__ acc_z, float *__restrict__ out)
 {
-    __shared__ float Ps[KCH][LDT];
-    __shared__ float Cs[KCH][LDT];
+    __shared__ __align__(16) float Ps[TILE][LDK];
+    __shared__ __align__(16) float Cs[TILE][LDK];
     __shared__ long long xi[TILE], yj[TILE];
     const int tid = threadIdx.x;
     if (tid < TILE) {
