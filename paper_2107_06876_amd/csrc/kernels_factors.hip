@@ -101,6 +101,33 @@ __device__ inline void store_rows(float (*dst)[LDK], const float (&v)[8])
     for (int pass = 0; pass < 8; ++pass) dst[r0 + pass * 8][kk] = v[pass];
 }
 
+// The same for rows whose chunks start on 16-byte boundaries (ld a multiple of 4): thread t takes
+// floats 4 (t % 8) .. + 3 of rows t / 8 and t / 8 + 32, one 16-byte load each.
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+__device__ inline void fetch_rows4(float (&v)[8], const float *__restrict__ base, long long ld,
+                                   const long long *rowidx, long long rowoff, int k0, int kmax)
+{
+    const int q = threadIdx.x & 7, r = threadIdx.x >> 3;
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const long long src = rowidx[r + 32 * hh];
+        float4_t x = {0.f, 0.f, 0.f, 0.f};
+        if (src >= 0 && k0 + 4 * q < kmax) x = *(const float4_t *)(base + (src + rowoff) * ld + k0 + 4 * q);
+        v[4 * hh + 0] = x.x, v[4 * hh + 1] = x.y, v[4 * hh + 2] = x.z, v[4 * hh + 3] = x.w;
+    }
+}
+
+__device__ inline void store_rows4(float (*dst)[LDK], const float (&v)[8])
+{
+    const int q = threadIdx.x & 7, r = threadIdx.x >> 3;
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const float4_t x = {v[4 * hh + 0], v[4 * hh + 1], v[4 * hh + 2], v[4 * hh + 3]};
+        *(float4_t *)&dst[r + 32 * hh][4 * q] = x;
+    }
+}
+
 // acc += P_chunk Q_chunk^T for the KCH staged features (dot products; the staged values are fp32,
 // products and sums fp64).  Only the first `rows` rows and `cols` columns of the tile hold points:
 // an instruction tile of 16 x 16 that lies wholly outside is skipped (its accumulators stay zero).
@@ -255,25 +282,22 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const double *A, int lda, i
     const int ar = 32 * (wv >> 1) + (ln & 15), bc = 32 * (wv & 1) + (ln & 15), kq4 = ln >> 4;
     TileAcc acc;
     tile_zero(acc);
-    for (int k0 = 0; k0 < K; k0 += KC) {
-        __syncthreads();
+    // a chunk's loads are requested before the chunk ahead of it is multiplied
+    double ra[4], rb[4];
+    auto fetch = [&](int k0) {
         if (transA) {
             const int rr = tid & 63, kq = tid >> 6;
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
                 const int kk = kq + pass * 4;
-                double v = 0.0;
-                if (r0 + rr < M && k0 + kk < K) v = A[(long long)(k0 + kk) * lda + r0 + rr];
-                As[kk][rr] = v;
+                ra[pass] = (r0 + rr < M && k0 + kk < K) ? A[(long long)(k0 + kk) * lda + r0 + rr] : 0.0;
             }
         } else {
             const int kk = tid & 15, rq = tid >> 4;
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
                 const int rr = rq + pass * 16;
-                double v = 0.0;
-                if (r0 + rr < M && k0 + kk < K) v = A[(r0 + rr) * lda + k0 + kk];
-                As[kk][rr] = v;
+                ra[pass] = (r0 + rr < M && k0 + kk < K) ? A[(r0 + rr) * lda + k0 + kk] : 0.0;
             }
         }
         if (transB) {
@@ -281,21 +305,33 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const double *A, int lda, i
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
                 const int cc = cq + pass * 16;
-                double v = 0.0;
-                if (c0 + cc < N && k0 + kk < K) v = B[(long long)(c0 + cc) * ldb + k0 + kk];
-                Bs[kk][cc] = v;
+                rb[pass] = (c0 + cc < N && k0 + kk < K) ? B[(long long)(c0 + cc) * ldb + k0 + kk] : 0.0;
             }
         } else {
             const int cc = tid & 63, kq = tid >> 6;
 #pragma unroll
             for (int pass = 0; pass < 4; ++pass) {
                 const int kk = kq + pass * 4;
-                double v = 0.0;
-                if (c0 + cc < N && k0 + kk < K) v = B[(long long)(k0 + kk) * ldb + c0 + cc];
-                Bs[kk][cc] = v;
+                rb[pass] = (c0 + cc < N && k0 + kk < K) ? B[(long long)(k0 + kk) * ldb + c0 + cc] : 0.0;
             }
         }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += KC) {
         __syncthreads();
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            if (transA)
+                As[(tid >> 6) + pass * 4][tid & 63] = ra[pass];
+            else
+                As[tid & 15][(tid >> 4) + pass * 16] = ra[pass];
+            if (transB)
+                Bs[tid & 15][(tid >> 4) + pass * 16] = rb[pass];
+            else
+                Bs[(tid >> 6) + pass * 4][tid & 63] = rb[pass];
+        }
+        __syncthreads();
+        if (k0 + KC < K) fetch(k0 + KC);
 #pragma unroll
         for (int ks = 0; ks < KC / 4; ++ks) {
             const int k = 4 * ks + kq4;
@@ -651,27 +687,39 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
     // Nystrom value on the same pairs, sum_k U[i][k] Wt[j][k].  The loads of a chunk are requested
     // before the chunk ahead of it is multiplied.
     const int nd = (d + KCH - 1) / KCH, nl = U ? (lp + KCH - 1) / KCH : 0;
-    float pv[8], cv[8];
-    auto fetch = [&](int c) {
-        if (c < nd) {
-            fetch_rows(pv, Z, d, xi, 0, c * KCH, d);
-            fetch_rows(cv, Z, d, yj, 0, c * KCH, d);
+    constexpr int DEPTH = 2;          // chunks whose loads are in flight (3 measured slower: registers)
+    const bool vecz = (d & 3) == 0;   // rows of Z start on 16-byte boundaries (lp is a multiple of 64)
+    struct Chunk {
+        float p[8], c[8];
+    };
+    auto fetch = [&](Chunk &C, int c) {
+        if (c >= nd + nl) return;
+        if (c >= nd) {
+            fetch_rows4(C.p, U, lp, xi, 0, (c - nd) * KCH, lp);
+            fetch_rows4(C.c, Wt, lp, yj, -(long long)B.n, (c - nd) * KCH, lp);   // yj: rows of Z; Wt has the rows of Y
+        } else if (vecz) {
+            fetch_rows4(C.p, Z, d, xi, 0, c * KCH, d);
+            fetch_rows4(C.c, Z, d, yj, 0, c * KCH, d);
         } else {
-            fetch_rows(pv, U, lp, xi, 0, (c - nd) * KCH, lp);
-            fetch_rows(cv, Wt, lp, yj, -(long long)B.n, (c - nd) * KCH, lp);   // yj: rows of Z; Wt has the rows of Y
+            fetch_rows(C.p, Z, d, xi, 0, c * KCH, d);
+            fetch_rows(C.c, Z, d, yj, 0, c * KCH, d);
         }
     };
     TileAcc acc;
     tile_zero(acc);
     double kv[16];
-    __syncthreads();   // xi, yj
-    fetch(0);
-    for (int c = 0; c < nd + nl; ++c) {
+    // chunk c: its registers go to LDS, the loads of chunk c + DEPTH take their place, chunk c is multiplied
+    auto step = [&](Chunk &C, int c) {
         __syncthreads();
-        store_rows(Ps, pv);
-        store_rows(Cs, cv);
+        if (c >= nd || vecz) {
+            store_rows4(Ps, C.p);
+            store_rows4(Cs, C.c);
+        } else {
+            store_rows(Ps, C.p);
+            store_rows(Cs, C.c);
+        }
         __syncthreads();
-        if (c + 1 < nd + nl) fetch(c + 1);
+        fetch(C, c + DEPTH);
         tile_mma(acc, Ps, Cs, rows_here, cols_here);
         if (c == nd - 1) {
 #pragma unroll
@@ -686,6 +734,15 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
             }
             tile_zero(acc);
         }
+    };
+    Chunk ch[DEPTH] = {};
+    __syncthreads();   // xi, yj
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j) fetch(ch[j], j);
+    for (int c = 0; c < nd + nl; c += DEPTH) {
+#pragma unroll
+        for (int j = 0; j < DEPTH; ++j)
+            if (c + j < nd + nl) step(ch[j], c + j);
     }
     if (U && !bw.lin_u) {
 #pragma unroll
