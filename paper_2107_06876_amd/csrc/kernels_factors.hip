@@ -219,12 +219,42 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
     }
     TileAcc acc;
     tile_zero(acc);
-    for (int k0 = 0; k0 < d; k0 += KCH) {
+    // the loads of two chunks are in flight while a chunk is multiplied
+    const int nd = (d + KCH - 1) / KCH;
+    const bool vec = (d & 3) == 0 && (((size_t)P | (size_t)Q) & 15) == 0;   // rows start on 16-byte boundaries
+    struct Chunk {
+        float p[8], c[8];
+    };
+    auto fetch = [&](Chunk &C, int c) {
+        if (c >= nd) return;
+        if (vec) {
+            fetch_rows4(C.p, P, d, pidx, 0, c * KCH, d);
+            fetch_rows4(C.c, Q, d, qidx, 0, c * KCH, d);
+        } else {
+            fetch_rows(C.p, P, d, pidx, 0, c * KCH, d);
+            fetch_rows(C.c, Q, d, qidx, 0, c * KCH, d);
+        }
+    };
+    auto step = [&](Chunk &C, int c) {
         __syncthreads();
-        stage_rows(Ps, P, d, pidx, k0, d);
-        stage_rows(Cs, Q, d, qidx, k0, d);
+        if (vec) {
+            store_rows4(Ps, C.p);
+            store_rows4(Cs, C.c);
+        } else {
+            store_rows(Ps, C.p);
+            store_rows(Cs, C.c);
+        }
         __syncthreads();
+        fetch(C, c + 2);
         tile_mma(acc, Ps, Cs);
+    };
+    Chunk ch[2] = {};
+    __syncthreads();   // pidx, qidx
+    fetch(ch[0], 0);
+    fetch(ch[1], 1);
+    for (int c = 0; c < nd; c += 2) {
+        step(ch[0], c);
+        if (c + 1 < nd) step(ch[1], c + 1);
     }
 #pragma unroll
     for (int e = 0; e < 16; ++e) {

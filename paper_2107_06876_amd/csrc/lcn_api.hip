@@ -676,17 +676,21 @@ struct Builder {
             HIPCHK(hipStreamWaitEvent(us, extra[0], 0));
             HIPCHK(hipStreamWaitEvent(vs, extra[0], 0));
         }
+        // A and its inverse first: a chain of small launches that the two big ones would otherwise
+        // keep waiting for compute units; U and V are enqueued behind it and run beside its second half
+        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
+        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, sc.ln, sc.ln,
+                                    nullptr, sc.A64, h.l, fs));
+        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
         HIPCHK(hipMemsetAsync(h.U, 0, sizeof(float) * (size_t)n * h.lp, us));
         HIPCHK(launch_kernel_matrix(Xz, n, h.L, h.l, d, cost, h.lambda, h.zn, sc.ln,
                                     h.U, nullptr, h.lp, us));
         HIPCHK(launch_kernel_matrix(Yz, m, h.L, h.l, d, cost, h.lambda, h.zn + n, sc.ln,
                                     nullptr, sc.Vt64, h.l, vs));
-        if (forked) HIPCHK(hipEventRecord(extra[1], vs));   // V done
-        HIPCHK(hipMemsetAsync(h.Wt, 0, sizeof(float) * (size_t)m * h.lp, fs));
-        HIPCHK(launch_kernel_matrix(h.L, h.l, h.L, h.l, d, cost, h.lambda, sc.ln, sc.ln,
-                                    nullptr, sc.A64, h.l, fs));
-        HIPCHK(launch_spd_inverse(sc.A64, h.l, h.ridge, sc.Lt, sc.Li, sc.Ainv, sc.Dinv, sc.Tm, sc.fail_flag, fs));
-        if (forked) HIPCHK(hipStreamWaitEvent(fs, extra[1], 0));
+        if (forked) {
+            HIPCHK(hipEventRecord(extra[1], vs));   // V done
+            HIPCHK(hipStreamWaitEvent(fs, extra[1], 0));
+        }
         // W^T = V^T A^{-1} (A^{-1} is symmetric)
         HIPCHK(launch_gemm_f64(sc.Vt64, sc.Ainv, m, h.l, h.l, h.Wt, h.lp, fs));
         return LCN_OK;
