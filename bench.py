@@ -221,7 +221,7 @@ def main():
     achieved = bytes_launch / (launch_us * 1e-6) / 1e9
     # HBM bytes per pass_kernel launch from the rocprofv3 counter runs (FETCH_SIZE scaled by 2.000 plus
     # WRITE_SIZE scaled by 1.000 against a 256 MiB device copy); see profiles/lcn_sinkhorn_c*.md
-    traffic = {3: 37.37e6 + 2.40e6, 5: 674.73e6 + 29.39e6}.get(args.config) if args.mode == "lcn" else None
+    traffic = {3: 35.92e6 + 2.10e6, 5: 615.90e6 + 29.13e6}.get(args.config) if args.mode == "lcn" else None
     out = {
         "metric": "LCN-Sinkhorn iterations/s (n=20k,d=300); build ms; % HBM peak; cost rel.err",
         "value": its_per_s, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

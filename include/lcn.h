@@ -23,7 +23,9 @@
  *     hipStream_t passed as void*; NULL = the default stream); during a build
  *     parts of it run on streams of the library's own that fork from and
  *     join that stream through events, enqueued by short-lived host threads
- *     that end before lcn_build returns.  Calls that return host scalars
+ *     (one of which enqueues on the given stream itself) that end before
+ *     lcn_build returns: enqueue nothing on that stream from another thread
+ *     while lcn_build runs.  Calls that return host scalars
  *     synchronise that stream.
  *   - Every function returns an lcn_status and never throws or aborts.  On
  *     LCN_ERR_INVALID_ARG nothing has been written or launched.
