@@ -7,8 +7,11 @@ correction) + sinkhorn_run(iters) + transport_cost.  The headline value is
 Sinkhorn iterations per second inside sinkhorn_run (HIP events on the
 library's stream); build time and the whole step are reported beside it.
 
-Prints ONE JSON line.  See DESIGN.md ("Measurement") for the definitions of
-the roofline figures.
+Prints ONE JSON line.  roofline.achieved = algorithmic bytes of one
+half-iteration launch (every factor entry and every sparse value once) divided
+by the average duration of such a launch, from HIP events around sinkhorn_run;
+roofline.traffic = HBM bytes per launch from the hardware counters (a stored
+figure from the rocprofv3 runs whose summaries sit under profiles/).
 """
 from __future__ import annotations
 
