@@ -370,3 +370,37 @@ def test_overlapped_build_gives_the_same_bits(monkeypatch):
             assert len(got) == len(ref)
             for a, b in zip(got, ref):
                 assert torch.equal(a, b)
+
+
+def test_build_on_a_stream_of_the_callers_own():
+    """A handle built and run on a stream the caller made (the build uses that stream as one of its
+    lanes, with a host thread of the library enqueuing on it) against one on the default stream:
+    buckets, pattern, factors and scalings bit for bit."""
+    import torch
+    import paper_2107_06876_amd as lcn
+    from parity import gpu_build
+    p = workloads.config3(n=3000, d=48, landmarks=96, buckets=12, rounds=3, iters=6, name="C3 reduced")
+
+    def snapshot():
+        h = gpu_build(p, "lcn")
+        lcn.sinkhorn_run(h, 4)
+        out = [x.clone() for x in lcn.lcn_get_scalings(h)]
+        out.append(lcn.lcn_get_buckets(h).clone())
+        out.extend(x.clone() for x in lcn.lcn_get_csr(h))
+        out.append(lcn.lcn_get_landmarks(h).clone())
+        out.extend(x.clone() for x in lcn.lcn_get_factors(h))
+        d = lcn.transport_cost(h)
+        lcn.lcn_destroy(h)
+        return out, d
+
+    ref, dref = snapshot()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        got, dgot = snapshot()
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert dgot == dref
+    assert len(got) == len(ref)
+    for a, b in zip(got, ref):
+        assert torch.equal(a, b)
+
