@@ -4,6 +4,10 @@
 // K^sp for sparse Sinkhorn (Sec. 3, eq. 3) or the correction K^sp - K^sp_Nys of
 // K_LCN (Sec. 4).  Everything that feeds the inverse or a difference of nearly
 // equal numbers is accumulated in fp64; only the stored factors are fp32.
+// The contractions (point . landmark, point . point within a bucket, U . W, and
+// the GEMMs of the inverse) run on the fp64 matrix instruction, 64 x 64 output
+// tiles per workgroup, operands staged through LDS with the next chunks' global
+// loads in flight; costs are formed from the dot product and fp64 squared norms.
 #include "lcn_internal.h"
 
 namespace lcn {
