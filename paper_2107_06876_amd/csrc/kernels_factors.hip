@@ -266,7 +266,18 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
         const int q = q0 + tile_col(e);
         if (p >= rows || q >= cols) continue;
         // a point against itself (the diagonal of the landmarks' matrix) is at cost zero exactly
-        const double c = (P == Q && p == q) ? 0.0 : cost_from_dot(acc.get(e), cost, pn[p], qn[q]);
+        double c = (P == Q && p == q) ? 0.0 : cost_from_dot(acc.get(e), cost, pn[p], qn[q]);
+        const double sq_est = cost == LCN_COST_EUCLID ? c * c : c;
+        if (P == Q && p != q && cost != LCN_COST_COSINE && sq_est <= 1e-9 * (pn[p] + qn[q])) {
+            // two landmarks (nearly) on top of each other: the norms cancel, so the squared distance is
+            // taken from the differences; coinciding landmarks give exactly zero and a singular matrix
+            double sq = 0.0;
+            for (int kk = 0; kk < d; ++kk) {
+                const double df = (double)P[p * d + kk] - (double)Q[(long long)q * d + kk];
+                sq = fma(df, df, sq);
+            }
+            c = cost == LCN_COST_EUCLID ? sqrt(sq) : sq;
+        }
         const double kv = exp(-c * inv_lambda);
         if (out32) out32[p * ldo + q] = (float)kv;
         if (out64) out64[p * cols + q] = kv;

@@ -404,3 +404,27 @@ def test_build_on_a_stream_of_the_callers_own():
     for a, b in zip(got, ref):
         assert torch.equal(a, b)
 
+
+def test_coinciding_landmarks_with_a_ridge():
+    """Two landmarks on top of each other make the landmark kernel matrix singular (what either side
+    does with it unregularised depends on rounding in the last place); with a ridge both sides invert
+    it and the factors agree.  The coinciding pair's distance is exactly zero on both sides."""
+    import torch
+    import oracle
+    import paper_2107_06876_amd as lcn
+    rng = np.random.default_rng(11)
+    X = rng.standard_normal((40, 6)).astype(np.float32)
+    Y = rng.standard_normal((30, 6)).astype(np.float32)
+    L = np.concatenate([X[:5], X[2:3], Y[:4]]).astype(np.float32)   # landmark 5 repeats landmark 2
+    a = torch.full((len(X),), 1.0 / len(X), device="cuda")
+    b = torch.full((len(Y),), 1.0 / len(Y), device="cuda")
+    for cost, ocost in ((lcn.COST_SQEUCLID, workloads.COST_SQEUCLID), (lcn.COST_EUCLID, workloads.COST_EUCLID)):
+        lm = dict(num_landmarks=len(L), kmeans_iters=0, seed=1, init=lcn.INIT_GIVEN,
+                  init_centroids=torch.from_numpy(L).cuda(), ridge=1e-3)
+        Uo, Wo = oracle.nystrom(X, Y, L, ocost, 2.0, 1e-3)
+        h = lcn.lcn_build(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda(), a, b, 2.0, cost, lcn.MODE_NYSTROM,
+                          landmarks=lm)
+        U, Wt = lcn.lcn_get_factors(h)
+        np.testing.assert_allclose(U.cpu().numpy(), Uo, rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(Wt.cpu().numpy().T, Wo, rtol=0, atol=1e-6 * np.abs(Wo).max())
+        lcn.lcn_destroy(h)
