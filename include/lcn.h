@@ -28,7 +28,11 @@
  *     while lcn_build runs.  Calls that return host scalars
  *     synchronise that stream.
  *   - Every function returns an lcn_status and never throws or aborts.  On
- *     LCN_ERR_INVALID_ARG nothing has been written or launched.
+ *     LCN_ERR_INVALID_ARG nothing has been written or launched, with one
+ *     exception: whether the points are finite and inside the range k-means
+ *     needs (see lcn_build) is only known once the device has read them, so
+ *     that INVALID_ARG comes after the build has used the workspace (no handle
+ *     is returned and the caller's inputs are never written).
  *   - Same inputs and seeds give bit-identical landmarks, buckets, block
  *     structure, factors and scalings.
  *   - A handle must not be used from two threads at once.
@@ -49,14 +53,22 @@ typedef enum {
     LCN_OK = 0,
     LCN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size/lambda, l > n + m, odd bucket count ... */
     LCN_ERR_ALLOC = 2,       /* workspace too small; *bytes_needed says how much is required */
-    LCN_ERR_DEVICE = 3,      /* a HIP call failed */
+    LCN_ERR_DEVICE = 3,      /* a HIP call failed, or a sweep gave up its bounded wait for another workgroup's
+                                totals; the latter is remembered: every later sinkhorn_run, lcn_get_info and
+                                lcn_last_error_counts on the handle returns LCN_ERR_DEVICE, its scalings are
+                                not to be used, and only lcn_destroy and a fresh lcn_build recover */
     LCN_ERR_STATE = 4,       /* handle is null, destroyed, or of the wrong kind for this call */
     LCN_ERR_SINGULAR = 5,    /* A (+ ridge I) is not positive definite (App. "Limitations") */
     LCN_ERR_NONPOSITIVE = 6, /* some (K~ v)_i or (K~^T u)_j was <= 0: the Nystrom part is not
                                 guaranteed non-negative (App. "Limitations") */
-    LCN_WARN_NO_SUPPORT = 7  /* sparse kernel only: some row/column has no entry at all; such points
+    LCN_WARN_NO_SUPPORT = 7, /* sparse kernel only: some row/column has no entry at all; such points
                                 get scaling 0 and carry no mass (App. "Limitations") -- the results
                                 are still valid */
+    LCN_ERR_RANGE = 8        /* nystrom / lcn: between two iterations some scaling grew by more than e^43
+                                relative to its vector's largest entry (the vectors are held as
+                                exp(log x - max log x) with the maximum of one iteration earlier, App.
+                                "Implementational details"; the sparse part reads single-precision copies
+                                that cover e^-131 .. e^43 around that maximum): the results are invalid */
 } lcn_status;
 
 typedef enum { LCN_COST_SQEUCLID = 0, LCN_COST_EUCLID = 1, LCN_COST_COSINE = 2 } lcn_cost;
@@ -278,6 +290,18 @@ typedef struct {
     int64_t undecided_last; /* points the MFMA filter left to the exact rule in the last k-means assignment */
 } lcn_info;
 lcn_status lcn_get_info(lcn_handle h, lcn_info *info_host);
+
+/* The failure modes of App. "Limitations" as counts, accumulated over every
+ * sweep since the build (a point that stays unsupported for N iterations is
+ * counted N times): sums (K~ v)_i or (K~^T u)_j that were <= 0 although the
+ * kernel has signed parts (Nystrom, LCN, or deletion entries: the scaling is
+ * NaN and sinkhorn_run returns LCN_ERR_NONPOSITIVE), and rows / columns of a
+ * kernel without signed parts (sparse, dense) whose sum was exactly zero
+ * because no stored entry reaches them (scaling 0, no mass,
+ * LCN_WARN_NO_SUPPORT).  Host outputs, each nullable.  Works on handles of
+ * lcn_build and of lcn_build_batched (there: totals over all problems).
+ * Synchronises the stream. */
+lcn_status lcn_last_error_counts(lcn_handle h, int64_t *nonpositive, int64_t *empty_rows, int64_t *empty_cols);
 
 /* Elapsed GPU time in milliseconds of the kernels of the last sinkhorn_run on
  * this handle, measured with HIP events on the handle's stream, and the

@@ -17,7 +17,7 @@ HASH_KMEANS, HASH_CROSSPOLYTOPE = 0, 1
 INIT_SAMPLE, INIT_KMEANSPP, INIT_GIVEN = 0, 1, 2
 F32, BF16 = 0, 1
 
-OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_DEVICE, ERR_STATE, ERR_SINGULAR, ERR_NONPOSITIVE, WARN_NO_SUPPORT = range(8)
+OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_DEVICE, ERR_STATE, ERR_SINGULAR, ERR_NONPOSITIVE, WARN_NO_SUPPORT, ERR_RANGE = range(9)
 
 
 class LandmarkParams(ctypes.Structure):
@@ -99,7 +99,7 @@ def load_library():
         for name in ("lcn_build_batched", "lcn_batched_results", "lcn_batched_get", "lcn_deletion_costs",
                      "lcn_head_lambdas", "lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
-                     "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing"):
+                     "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing", "lcn_last_error_counts"):
             getattr(lib, name).restype = i32
         _lib = lib
     return _lib
@@ -341,6 +341,16 @@ def lcn_get_info(h: LcnHandle) -> Info:
     if st != OK:
         raise LcnError(st, "lcn_get_info")
     return info
+
+
+def lcn_last_error_counts(h):
+    """(nonpositive, empty_rows, empty_cols) accumulated over every sweep since the build; raises on
+    LCN_ERR_DEVICE (a sweep gave up its bounded wait)."""
+    c = [ctypes.c_int64(0) for _ in range(3)]
+    st = load_library().lcn_last_error_counts(h.raw, *[ctypes.byref(x) for x in c])
+    if st != OK:
+        raise LcnError(st, "lcn_last_error_counts")
+    return tuple(int(x.value) for x in c)
 
 
 def lcn_last_run_timing(h: LcnHandle):

@@ -11,6 +11,9 @@ namespace lcn {
 constexpr int PASS_THREADS = 1024;
 constexpr int PASS_WAVES = PASS_THREADS / 64;
 constexpr int MAXR = 8;
+// what the single-precision bucket-ordered copies of a scaling vector are stored times, and its inverse
+constexpr double PERM_SCALE = 18446744073709551616.0;          // 2^64
+constexpr double PERM_UNSCALE = 1.0 / 18446744073709551616.0;  // 2^-64
 #ifndef PASS_MIN_WAVES
 #define PASS_MIN_WAVES 1
 #endif
@@ -170,6 +173,7 @@ struct FuseArgs {
     const double *shift_self;    // exponent of this side's vector
     double *mark_pending;        // accumulator the NEXT sweep reduces into (nullable): filled with ACC_PENDING
     unsigned long long *timeouts;
+    unsigned long long wait_ticks;  // how long a workgroup re-reads pending totals before it gives up (100 MHz clock)
 };
 
 // Marks the accumulator that the next sweep will fill as pending (one wavefront of
@@ -243,7 +247,7 @@ __device__ inline void fused_fetch(const FuseArgs &Fz, const double *acc, int lp
             ((unsigned long long *)ysh)[k] = v;
         }
         if (!__any(pending) || give_up) break;
-        if (wall_clock64() - t0 > 20000000ull) {  // 0.2 s of the 100 MHz clock
+        if (wall_clock64() - t0 > Fz.wait_ticks) {
             if (lane == 0) atomicAdd(Fz.timeouts, 1ull);
             give_up = true;
         }

@@ -46,7 +46,7 @@ struct BatchDev {
     int *buckets;                 // per pair [R][n_p + m_p], pairs back to back at R * (x_off + y_off)
     double *log_u, *log_v;        // per pair at x_off + y_off, length n + m each (n resp. m without BP)
     double *dist, *resid;         // [P]
-    unsigned long long *counters; // [0] non-positive sums
+    unsigned long long *counters; // [0] non-positive sums, [1] / [2] sums of exactly zero without signed terms (rows / columns), per sweep
     int *fail;
 };
 
@@ -368,7 +368,12 @@ __global__ __launch_bounds__(64) void batched_run_kernel(BatchDev B, int iters, 
     const bool has_vp = lane < m, has_vd = bp && lane < n;   // ... and of v
     double *gu = B.log_u + x0 + y0, *gv = B.log_v + x0 + y0;
     const double a_each = 1.0 / (double)len_u, b_each = 1.0 / (double)len_v;   // uniform marginals
-    unsigned long long nonpos = 0;
+    unsigned long long nonpos = 0, empty_u = 0, empty_v = 0;
+    // A kernel without a Nystrom part and without deletion entries has no signed terms: a sum of
+    // exactly zero means the point shares no bucket with any point of the other set (or only
+    // vanished entries).  Such a point gets scaling 0 (log = -infinity), carries no mass and is
+    // counted apart from the non-positive sums (App. "Limitations": ignored, not a failure).
+    const bool unsupported_is_zero = !bp && B.l == 0;
 
     // stored logs -> x * 2^E
     auto load_vec = [&](double lp, bool hp, double ld, bool hd, double &xp, double &xd) -> int {
@@ -405,9 +410,13 @@ __global__ __launch_bounds__(64) void batched_run_kernel(BatchDev B, int iters, 
         s_p = (acc[0] + acc[1]) + (acc[2] + acc[3]) + k_p * xd;
         s_d = k_d * xp + tail;
     };
-    auto scale = [&](double marg, double s, bool exists) -> double {
+    auto scale = [&](double marg, double s, bool exists, unsigned long long &empty) -> double {
         if (!exists) return 0.0;
         if (s > 0.0) return marg * rcp64(s);
+        if (unsupported_is_zero && s == 0.0) {
+            ++empty;
+            return 0.0;
+        }
         ++nonpos;
         return NAN;
     };
@@ -418,12 +427,12 @@ __global__ __launch_bounds__(64) void batched_run_kernel(BatchDev B, int iters, 
     if (iters == 0) Eu = load_vec(has_up ? gu[lane] : 0.0, has_up, has_ud ? gu[n + lane] : 0.0, has_ud, xu_p, xu_d);
     for (int it = 0; it < iters; ++it) {
         product(Kr, m, xv_p, xv_d, kpe, keq, s_p, s_d);        // u = a ./ (K_BP v), eq. 2
-        xu_p = scale(a_each, s_p, has_up);
-        xu_d = scale(a_each, s_d, has_ud);
+        xu_p = scale(a_each, s_p, has_up, empty_u);
+        xu_d = scale(a_each, s_d, has_ud, empty_u);
         Eu = -Ev + renorm(xu_p, xu_d);
         product(Kc, n, xu_p, xu_d, keq, kpe, s_p, s_d);        // v = b ./ (K_BP^T u)
-        xv_p = scale(b_each, s_p, has_vp);
-        xv_d = scale(b_each, s_d, has_vd);
+        xv_p = scale(b_each, s_p, has_vp, empty_v);
+        xv_d = scale(b_each, s_d, has_vd, empty_v);
         Ev = -Eu + renorm(xv_p, xv_d);
     }
     const double lu_p = log(xu_p) + (double)Eu * LN2, lu_d = log(xu_d) + (double)Eu * LN2;
@@ -434,7 +443,11 @@ __global__ __launch_bounds__(64) void batched_run_kernel(BatchDev B, int iters, 
         if (has_vp) gv[lane] = lv_p;
         if (has_vd) gv[m + lane] = lv_d;
         nonpos = (unsigned long long)wave_sum((double)nonpos);
+        empty_u = (unsigned long long)wave_sum((double)empty_u);
+        empty_v = (unsigned long long)wave_sum((double)empty_v);
         if (lane == 0 && nonpos) atomicAdd(&B.counters[0], nonpos);
+        if (lane == 0 && empty_u) atomicAdd(&B.counters[1], empty_u);
+        if (lane == 0 && empty_v) atomicAdd(&B.counters[2], empty_v);
     }
 
     // marginals r = u .* (K_BP v), c = v .* (K_BP^T u); distance and residual
@@ -442,7 +455,7 @@ __global__ __launch_bounds__(64) void batched_run_kernel(BatchDev B, int iters, 
     product(Kr, m, xv_p, xv_d, kpe, keq, s_p, s_d);
     if (has_up) {
         const double r = ldexp(xu_p * s_p, Eu + Ev);
-        dsum += r * lu_p;
+        if (r != 0.0) dsum += r * lu_p;   // a point without mass (log u = -infinity) adds nothing
         esum += fabs(r - a_each);
         if (row_marg) row_marg[x0 + y0 + lane] = (float)r;
     }
@@ -455,7 +468,7 @@ __global__ __launch_bounds__(64) void batched_run_kernel(BatchDev B, int iters, 
     product(Kc, n, xu_p, xu_d, keq, kpe, s_p, s_d);
     if (has_vp) {
         const double c = ldexp(xv_p * s_p, Eu + Ev);
-        dsum += c * lv_p;
+        if (c != 0.0) dsum += c * lv_p;
         esum += fabs(c - b_each);
         if (col_marg) col_marg[x0 + y0 + lane] = (float)c;
     }
@@ -523,11 +536,12 @@ lcn_status batched_run(void *hh, int iters)
                        (float *)nullptr);
     BHIPCHK(hipGetLastError());
     BHIPCHK(hipEventRecord(h.ev1, h.stream));
-    unsigned long long c = 0;
-    BHIPCHK(hipMemcpyAsync(&c, h.dev.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
+    unsigned long long c[3] = {0, 0, 0};
+    BHIPCHK(hipMemcpyAsync(c, h.dev.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
     BHIPCHK(hipStreamSynchronize(h.stream));
     BHIPCHK(hipEventElapsedTime(&h.last_ms, h.ev0, h.ev1));
-    return c ? LCN_ERR_NONPOSITIVE : LCN_OK;
+    if (c[0]) return LCN_ERR_NONPOSITIVE;
+    return (c[1] | c[2]) ? LCN_WARN_NO_SUPPORT : LCN_OK;
 }
 
 lcn_status batched_query(void *hh, double *dist_host, double *resid_host, float *row_dev, float *col_dev)
@@ -539,6 +553,14 @@ lcn_status batched_query(void *hh, double *dist_host, double *resid_host, float 
         BHIPCHK(hipMemcpyAsync(dist_host, h.dev.dist, sizeof(double) * h.dev.P, hipMemcpyDeviceToHost, h.stream));
     if (resid_host)
         BHIPCHK(hipMemcpyAsync(resid_host, h.dev.resid, sizeof(double) * h.dev.P, hipMemcpyDeviceToHost, h.stream));
+    BHIPCHK(hipStreamSynchronize(h.stream));
+    return LCN_OK;
+}
+
+lcn_status batched_counts(void *hh, unsigned long long c[3])
+{
+    BatchHandle &h = *(BatchHandle *)hh;
+    BHIPCHK(hipMemcpyAsync(c, h.dev.counters, 3 * sizeof(unsigned long long), hipMemcpyDeviceToHost, h.stream));
     BHIPCHK(hipStreamSynchronize(h.stream));
     return LCN_OK;
 }

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
             yreg[t] = (T > 0 && MODE != PASS_INIT) ? S.acc_in[FRow<T>::kidx(t, lane)] : 0.0;
     }
     double q0 = 0.0, q1 = 0.0;
-    unsigned long long nonpos = 0, empty = 0;
+    unsigned long long nonpos = 0, empty = 0, range = 0;
 
     // Three-stage software pipeline over the rows a wave owns: metadata is read
     // two rows ahead (scalar loads), the factor row and the first 64 entries of
@@ -82,8 +82,11 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
     // The bucket-ordered copies of the scalings are single precision in this kernel (the buffers are
     // sized for doubles; the logarithmic kernels keep doubles there): they are gathered once per
     // stored value, and at half the size they stay in the per-die cache beside the streamed rows.
-    // The exponent taken out keeps the largest entry near one; an entry 2^-126 below it counts as zero,
-    // like a kernel value of that size in the single-precision factors and sparse values.
+    // The exponent taken out keeps the largest entry near one, and the copies are stored times
+    // PERM_SCALE = 2^64 (exact): single precision then holds entries from 2^-190 (e^-131) below the
+    // vector's largest up to 2^63 (e^43) above it.  A sum's sparse part is scaled back before the
+    // factor part is added.  An entry that grows past that within one iteration overflows its copy:
+    // counted, and the run is reported as failed (LCN_ERR_RANGE).
     const float *__restrict__ perm_in = reinterpret_cast<const float *>(S.perm_in);
     float *__restrict__ perm_out = reinterpret_cast<float *>(S.perm_out);
     // Loads are issued for whole wavefront-wide chunks without predication: lanes
@@ -170,6 +173,7 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
                     off += mc.len[q];
                 }
             }
+            acc *= PERM_UNSCALE;
             if (T > 0) {
 #pragma unroll
                 for (int t = 0; t < TT; ++t) acc = fma((double)C.f.f[t], yreg[t], acc);
@@ -203,7 +207,9 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
         }
         if (MODE != PASS_QUERY) {
             if (lane == 0) S.lin_out[row] = out;
-            if (lane < R) perm_out[(long long)lane * S.rows + mc.pos] = (float)out;
+            const float outf = (float)(out * PERM_SCALE);
+            if (R > 0 && outf == INFINITY) ++range;   // without hash rounds nothing reads the copies
+            if (lane < R) perm_out[(long long)lane * S.rows + mc.pos] = outf;
             if (T > 0) {
 #pragma unroll
                 for (int t = 0; t < TT; ++t) zacc[t] = fma((double)C.f.f[t], out, zacc[t]);
@@ -264,9 +270,10 @@ __global__ __launch_bounds__(PASS_THREADS, PASS_MIN_WAVES) void pass_kernel(Pass
         for (int w = 0; w < HALF; ++w) s = k == lp + 2 ? fmax(s, zsh[w * stride + k]) : s + zsh[w * stride + k];
         partial[(long long)blockIdx.x * stride + k] = s;
     }
-    if (lane == 0 && (nonpos | empty)) {
+    if (lane == 0 && (nonpos | empty | range)) {
         if (nonpos) atomicAdd(&counters[0], nonpos);
         if (empty) atomicAdd(&counters[empty_slot], empty);
+        if (range) atomicAdd(&counters[6], range);
     }
 }
 
@@ -714,7 +721,8 @@ int pass_grid(const Handle &h)
 
 template <int T, int RR>
 static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, int mode, const FuseArgs *fuse,
-                                 bool fused_in, bool reduce_after, double *partial, hipStream_t s)
+                                 bool fused_in, bool reduce_after, double *partial, unsigned long long *cnt,
+                                 hipStream_t s)
 {
     long long g = (S.rows + PASS_WAVES - 1) / PASS_WAVES;
     int grid = (int)(g < h.grid ? g : h.grid);
@@ -726,17 +734,17 @@ static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, i
         hipLaunchKernelGGL(max_log_kernel, dim3(1), dim3(1024), 0, s, S.log_out, S.rows, S.shift_self);
     if (mode == PASS_UPDATE && fused_in)
         hipLaunchKernelGGL((pass_kernel<T, RR, PASS_UPDATE, true>), dim3(grid), dim3(PASS_THREADS),
-                           pass_lds_bytes(h.lp, true), s, S, h.R, h.lp, partial, h.counters, empty_slot, *fuse);
+                           pass_lds_bytes(h.lp, true), s, S, h.R, h.lp, partial, cnt, empty_slot, *fuse);
     else if (mode == PASS_UPDATE)
         hipLaunchKernelGGL((pass_kernel<T, RR, PASS_UPDATE, false>), dim3(grid), dim3(PASS_THREADS),
-                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, h.counters, empty_slot,
+                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, cnt, empty_slot,
                            fuse ? *fuse : none);
     else if (mode == PASS_QUERY)
         hipLaunchKernelGGL((pass_kernel<T, RR, PASS_QUERY, false>), dim3(grid), dim3(PASS_THREADS),
-                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, h.counters, empty_slot, none);
+                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, cnt, empty_slot, none);
     else
         hipLaunchKernelGGL((pass_kernel<T, RR, PASS_INIT, false>), dim3(grid), dim3(PASS_THREADS),
-                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, h.counters, empty_slot, none);
+                           pass_lds_bytes(h.lp, false), s, S, h.R, h.lp, partial, cnt, empty_slot, none);
     if (reduce_after)
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((stride + 63) / 64), dim3(1024), 0, s, partial, grid, stride,
                            h.lp, S.acc_out, qout, S.shift_self, mode);
@@ -745,10 +753,11 @@ static hipError_t launch_pass_tr(const PassSide &S, const Handle &h, int side, i
 
 template <int T>
 static hipError_t launch_pass_t(const PassSide &S, const Handle &h, int side, int mode, const FuseArgs *fuse,
-                                bool fused_in, bool reduce_after, double *partial, hipStream_t s)
+                                bool fused_in, bool reduce_after, double *partial, unsigned long long *cnt,
+                                hipStream_t s)
 {
-    if (h.R <= 4) return launch_pass_tr<T, 4>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-    return launch_pass_tr<T, 8>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+    if (h.R <= 4) return launch_pass_tr<T, 4>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+    return launch_pass_tr<T, 8>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
 }
 
 // side 0: rows of X (updates u, consumes y = W v, produces z = U^T u); side 1: rows of Y.
@@ -842,18 +851,20 @@ static int sweep_groups(const Handle &h, long long rows)
 }
 
 static hipError_t dispatch_pass(const PassSide &S, const Handle &h, int side, int mode, const FuseArgs *fuse,
-                                bool fused_in, bool reduce_after, double *partial, hipStream_t s)
+                                bool fused_in, bool reduce_after, double *partial, hipStream_t s,
+                                unsigned long long *cnt = nullptr)
 {
+    if (!cnt) cnt = h.counters;
     switch (h.lp / 64) {
-        case 0: return launch_pass_t<0>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 1: return launch_pass_t<1>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 2: return launch_pass_t<2>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 3: return launch_pass_t<3>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 4: return launch_pass_t<4>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 5: return launch_pass_t<5>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 6: return launch_pass_t<6>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 7: return launch_pass_t<7>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
-        case 8: return launch_pass_t<8>(S, h, side, mode, fuse, fused_in, reduce_after, partial, s);
+        case 0: return launch_pass_t<0>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 1: return launch_pass_t<1>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 2: return launch_pass_t<2>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 3: return launch_pass_t<3>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 4: return launch_pass_t<4>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 5: return launch_pass_t<5>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 6: return launch_pass_t<6>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 7: return launch_pass_t<7>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
+        case 8: return launch_pass_t<8>(S, h, side, mode, fuse, fused_in, reduce_after, partial, cnt, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -869,6 +880,15 @@ hipError_t launch_pass(const Handle &h, int side, int mode, int acc_in, int acc_
 // fused reduction every sweep but the first adds up its predecessor's partial
 // sums itself (two partial buffers alternate) and one reduction launch at the end
 // completes the state; otherwise every sweep is followed by its reduction launch.
+//
+// A state that has not been iterated yet (after the build or after new scalings
+// were set) has exponents that say nothing about the vectors the first sweeps
+// produce: from u = v = 1 the first u is of the order of 1 / (K 1), possibly
+// e^(+-hundreds).  For such a state each side's first sweep is run twice: once
+// only to learn the largest log of its result (everything else it writes is
+// overwritten, its fault counts go to slots nobody reads), then for real with
+// that exponent.  From then on a vector's exponent is its largest log one
+// iteration earlier, and logs move little per iteration.
 hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s)
 {
     // a sweep's first ceil((lp + 3) / 64) workgroups add up its predecessor's partial sums: a side with
@@ -876,7 +896,18 @@ hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s)
     const int reducers = (h.lp + 3 + 63) / 64;
     const bool fused = h.fused_reduce && !h.log_domain && sweep_groups(h, h.n) >= reducers &&
                        sweep_groups(h, h.m) >= reducers;
-    for (int t = 0; t < 2 * iters; ++t) {
+    int first = 0;
+    if (h.fresh && h.double_first && !h.log_domain && iters > 0) {
+        unsigned long long *discard = h.counters + 8;
+        const PassSide SX = make_side(h, 0, 0, 1, nullptr), SY = make_side(h, 1, 1, 0, nullptr);
+        hipError_t e = dispatch_pass(SX, h, 0, PASS_UPDATE, nullptr, false, true, h.partial, s, discard);
+        if (e == hipSuccess) e = dispatch_pass(SX, h, 0, PASS_UPDATE, nullptr, false, true, h.partial, s);
+        if (e == hipSuccess) e = dispatch_pass(SY, h, 1, PASS_UPDATE, nullptr, false, true, h.partial, s, discard);
+        if (e != hipSuccess) return e;
+        first = 1;   // the loop below starts with the sweep over Y, now with its exponent known
+    }
+    if (iters > 0) h.fresh = 0;
+    for (int t = first; t < 2 * iters; ++t) {
         const int side = t & 1;
         const PassSide S = make_side(h, side, side == 0 ? 0 : 1, side == 0 ? 1 : 0, nullptr);
         hipError_t e;
@@ -887,10 +918,10 @@ hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s)
         } else {
             double *mine = (t & 1) ? h.partial2 : h.partial;
             const bool last = t == 2 * iters - 1;
-            if (t == 0) {
+            if (t == first) {
                 // not fused itself, but its successor reduces into this sweep's output accumulator
                 FuseArgs F{};
-                F.mark_pending = last ? nullptr : h.acc[1];
+                F.mark_pending = last ? nullptr : h.acc[side == 0 ? 1 : 0];
                 e = dispatch_pass(S, h, side, PASS_UPDATE, &F, false, last, mine, s);
             } else {
                 const long long rows_prev = side == 0 ? h.m : h.n;
@@ -902,6 +933,7 @@ hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s)
                 F.shift_self = h.shift + side;
                 F.mark_pending = last ? nullptr : h.acc[side == 0 ? 1 : 0];
                 F.timeouts = h.counters + 5;
+                F.wait_ticks = h.wait_ticks;
                 e = dispatch_pass(S, h, side, PASS_UPDATE, &F, true, last, mine, s);
             }
         }

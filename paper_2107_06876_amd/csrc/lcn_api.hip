@@ -101,7 +101,7 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
     h.zn = bump.take<double>((size_t)N);
     h.a = bump.take<float>((size_t)h.n);
     h.b_marg = bump.take<float>((size_t)h.m);
-    h.counters = bump.take<unsigned long long>(8);
+    h.counters = bump.take<unsigned long long>(16);
     h.query_out = bump.take<double>(4);
     sc.fail_flag = bump.take<int>(4);
     sc.totals = bump.take<long long>(4);
@@ -404,10 +404,13 @@ lcn_status run_hier_kmeans(Handle &h, Scratch &sc, KmScratch &km, hipStream_t s,
 
 lcn_status status_from_counters(Handle &h)
 {
-    unsigned long long c[6];
+    unsigned long long c[7];
     HIPCHK(hipMemcpyAsync(c, h.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
     HIPCHK(hipStreamSynchronize(h.stream));
     if (c[5]) return LCN_ERR_DEVICE;  // a sweep gave up waiting for its totals
+    // a scaling that outgrew the single-precision copy the sparse part reads turns later sums into
+    // NaN, which count as non-positive too: the overflow is the cause and is reported
+    if (c[6]) return LCN_ERR_RANGE;
     if (c[0]) return LCN_ERR_NONPOSITIVE;
     if (c[1] | c[2]) return LCN_WARN_NO_SUPPORT;
     return LCN_OK;
@@ -428,6 +431,7 @@ lcn_status init_state(Handle &h)
     }
     HIPCHK(launch_pass(h, 0, PASS_INIT, -1, 1, nullptr, h.stream));
     HIPCHK(launch_pass(h, 1, PASS_INIT, -1, 0, nullptr, h.stream));
+    h.fresh = 1;
     return LCN_OK;
 }
 
@@ -530,7 +534,7 @@ struct Builder {
             for (int q = 0; q < KM_LANES; ++q) lane[q] = h.stream;
         HIPCHK(hipEventCreate(&h.ev0));
         HIPCHK(hipEventCreate(&h.ev1));
-        HIPCHK(hipMemsetAsync(h.counters, 0, 8 * sizeof(unsigned long long), h.stream));
+        HIPCHK(hipMemsetAsync(h.counters, 0, 16 * sizeof(unsigned long long), h.stream));
         HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
         HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
         HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
@@ -859,6 +863,10 @@ static lcn_status build_one(const void *X, int64_t n, const void *Y, int64_t m, 
         h.exact_assign_only = env ? atoi(env) : 0;
         env = getenv("LCN_FUSED_REDUCE");
         h.fused_reduce = env ? atoi(env) : 1;
+        env = getenv("LCN_WAIT_TICKS");
+        h.wait_ticks = env ? strtoull(env, nullptr, 10) : 20000000ull;
+        env = getenv("LCN_DOUBLE_FIRST_SWEEP");
+        h.double_first = env ? atoi(env) : 1;
         env = getenv("LCN_BUILD_OVERLAP");
         build_overlap = env ? atoi(env) != 0 : true;
         h.cus = device_compute_units();
@@ -1038,10 +1046,12 @@ lcn_status lcn_backward(lcn_handle hh, float *gU_dev, float *gWt_dev, float *gsp
     if ((gU_dev || gWt_dev) && h.l == 0) return LCN_ERR_STATE;
     if (gsp_dev && h.R == 0) return LCN_ERR_STATE;
     if (gnys_dev && (h.R == 0 || h.l == 0)) return LCN_ERR_STATE;
-    if (gU_dev || gWt_dev) HIPCHK(launch_backward_factors(h, gU_dev, gWt_dev, h.stream));
-    if (gsp_dev || gnys_dev) {
+    if (gsp_dev || gnys_dev) {   // checked before anything is launched: an error leaves every output untouched
         if (!scratch_dev || ((uintptr_t)scratch_dev & 255)) return LCN_ERR_INVALID_ARG;
         if (scratch_bytes < backward_scratch(h)) return LCN_ERR_ALLOC;
+    }
+    if (gU_dev || gWt_dev) HIPCHK(launch_backward_factors(h, gU_dev, gWt_dev, h.stream));
+    if (gsp_dev || gnys_dev) {
         const size_t rowptr_bytes = ((sizeof(long long) * (size_t)(h.n + 1)) + 255) / 256 * 256;
         const size_t rec_bytes = ((sizeof(float) * (size_t)(h.nnz_stored + 64)) + 255) / 256 * 256;
         long long *rowptr = (long long *)scratch_dev;
@@ -1100,6 +1110,24 @@ lcn_status lcn_get_info(lcn_handle hh, lcn_info *info)
     return LCN_OK;
 }
 
+lcn_status lcn_last_error_counts(lcn_handle hh, int64_t *nonpositive, int64_t *empty_rows, int64_t *empty_cols)
+{
+    unsigned long long c[6] = {0, 0, 0, 0, 0, 0};
+    if (is_batched_handle(hh)) {
+        const lcn_status st = batched_counts(hh, c);
+        if (st != LCN_OK) return st;
+    } else {
+        if (!valid(hh)) return LCN_ERR_STATE;
+        Handle &h = *(Handle *)hh;
+        HIPCHK(hipMemcpyAsync(c, h.counters, sizeof(c), hipMemcpyDeviceToHost, h.stream));
+        HIPCHK(hipStreamSynchronize(h.stream));
+    }
+    if (nonpositive) *nonpositive = (int64_t)c[0];
+    if (empty_rows) *empty_rows = (int64_t)c[1];
+    if (empty_cols) *empty_cols = (int64_t)c[2];
+    return c[5] ? LCN_ERR_DEVICE : LCN_OK;   // a sweep gave up waiting for its totals
+}
+
 lcn_status lcn_last_run_timing(lcn_handle hh, float *ms_host, int32_t *launches_host)
 {
     if (is_batched_handle(hh)) return batched_timing(hh, ms_host, launches_host);
@@ -1136,6 +1164,7 @@ const char *lcn_status_string(int32_t status)
         case LCN_ERR_SINGULAR: return "landmark kernel matrix is not positive definite";
         case LCN_ERR_NONPOSITIVE: return "non-positive kernel-vector product";
         case LCN_WARN_NO_SUPPORT: return "sparse kernel has rows or columns without entries";
+        case LCN_ERR_RANGE: return "a scaling grew by more than e^43 within one iteration";
         default: return "unknown status";
     }
 }

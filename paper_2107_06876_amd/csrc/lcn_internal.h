@@ -147,6 +147,7 @@ bool is_batched_handle(const void *h);
 lcn_status batched_run(void *h, int iters);
 lcn_status batched_query(void *h, double *dist_host, double *resid_host, float *row_dev, float *col_dev);
 lcn_status batched_timing(void *h, float *ms, int *launches);
+lcn_status batched_counts(void *h, unsigned long long c[3]);
 void batched_destroy(void *h);
 
 struct Handle {
@@ -188,9 +189,15 @@ struct Handle {
     double *partial;           // [grid][lp + 3] per-workgroup partial sums of a sweep
     double *partial2;          // second buffer: consecutive sweeps alternate when the reduction is fused
     int fused_reduce;          // sweeps add up their predecessor's partial sums themselves
+    int fresh;                 // the scalings have not been iterated since they were set: their exponents are stale
+    unsigned long long wait_ticks;  // bound of a sweep's wait for its totals, in ticks of the 100 MHz clock (default 0.2 s)
+    int double_first;          // run the first sweeps of a fresh state twice (on unless switched off for tests)
     int cus;                   // compute units of the device
     double *query_out;         // [2 sides][2]: sum r log u, sum |r - a|
-    unsigned long long *counters;  // nonpositive, empty rows, empty cols, unique nnz, range flag, wait timeouts
+    // [0] non-positive sums, [1] empty rows, [2] empty columns, [3] unique pairs, [4] input range flag,
+    // [5] expired waits, [6] overflowed single-precision scaling copies, [8..15] counts of sweeps whose
+    // results are discarded
+    unsigned long long *counters;
     int grid;
     int grid_cap;              // upper bound on the workgroups of a sweep (0 = default)
     int exact_assign_only;     // skip the MFMA filter and decide every bucket by the exact rule

@@ -24,6 +24,7 @@ MODES = {"dense": lcn.MODE_DENSE, "sparse": lcn.MODE_SPARSE, "nystrom": lcn.MODE
 TOL_LOG = 1e-4
 TOL_COST_REL = 1e-4
 TOL_RESID = 1e-5
+NONPOS_SLACK = 4
 
 
 def oracle_run(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, iters=None):
@@ -92,16 +93,21 @@ def compare(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, it
         out["val_abs_over_max"] = float(np.max(np.abs(v - B.op.val)) / scale) if v.size else 0.0
         assert out["val_abs_over_max"] < 2e-6
     if st.nonpositive > 0:
-        # the Nystrom part went negative (App. "Limitations"): both sides must say so; the first
-        # sweep's count of non-positive sums may differ by the few sums that are zero to rounding
+        # The Nystrom part went negative (App. "Limitations"): both sides must say so.  Once one sum
+        # is non-positive its scaling is NaN, the next sweep's accumulator is NaN and every later sum
+        # counts, identically on both sides; only the first failing sweep's count can differ, by the
+        # sums that are zero to within the rounding of the stored factors (a relative 1e-7 of their
+        # terms): at most NONPOS_SLACK of them here, none on any configuration of this suite so far.
         status = lcn.sinkhorn_run(h, iters, check=False)
-        info = lcn.lcn_get_info(h)
-        out.update(status=status, nonpositive_gpu=info.nonpositive, nonpositive_oracle=st.nonpositive)
+        nonpos, _, _ = lcn.lcn_last_error_counts(h)
+        out.update(status=status, nonpositive_gpu=nonpos, nonpositive_oracle=st.nonpositive)
         assert status == lcn.binding.ERR_NONPOSITIVE, out
-        assert abs(info.nonpositive - st.nonpositive) <= max(4, 0.02 * st.nonpositive), out
+        assert abs(nonpos - st.nonpositive) <= NONPOS_SLACK, out
         lcn.lcn_destroy(h)
         return out
-    status = lcn.sinkhorn_run(h, iters)
+    status = lcn.sinkhorn_run(h, iters, check=False)
+    want = lcn.binding.WARN_NO_SUPPORT if (st.empty_rows or st.empty_cols) else lcn.binding.OK
+    assert status == want, (status, want, st.empty_rows, st.empty_cols)
     lu, lv = lcn.lcn_get_scalings(h)
     lu, lv = lu.cpu().numpy().astype(np.float64), lv.cpu().numpy().astype(np.float64)
     fin_u, fin_v = np.isfinite(st.log_u), np.isfinite(st.log_v)
@@ -117,7 +123,9 @@ def compare(p: workloads.Problem, mode: str, hash_kind=workloads.HASH_KMEANS, it
     info = lcn.lcn_get_info(h)
     out["status"] = status
     out["empty_rows"], out["empty_cols"] = info.empty_rows, info.empty_cols
-    assert (info.empty_rows > 0) == (st.empty_rows > 0) and (info.empty_cols > 0) == (st.empty_cols > 0)
+    # counted per sweep on both sides: a point without support is counted once per iteration
+    assert (info.empty_rows, info.empty_cols) == (st.empty_rows, st.empty_cols), out
+    assert lcn.lcn_last_error_counts(h) == (0, st.empty_rows, st.empty_cols)
     assert info.nonpositive == 0 and st.nonpositive == 0
     assert out["log_u"] <= TOL_LOG and out["log_v"] <= TOL_LOG, out
     assert out["cost_rel"] <= TOL_COST_REL, out

@@ -24,7 +24,8 @@ def test_header_declares_the_expected_entry_points():
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
                      "lcn_get_factors", "lcn_get_info", "lcn_destroy", "lcn_status_string", "lcn_build_batched",
                      "lcn_batched_results", "lcn_batched_get", "lcn_last_run_timing", "lcn_backward",
-                     "lcn_backward_scratch_bytes", "lcn_plan_rows", "lcn_deletion_costs", "lcn_head_lambdas"):
+                     "lcn_backward_scratch_bytes", "lcn_plan_rows", "lcn_deletion_costs", "lcn_head_lambdas",
+                     "lcn_last_error_counts"):
         assert required in names
 
 
@@ -38,8 +39,8 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 def test_status_strings():
     import paper_2107_06876_amd as lcn
-    seen = {lcn.lcn_status_string(i) for i in range(8)}
-    assert len(seen) == 8 and "unknown status" not in seen
+    seen = {lcn.lcn_status_string(i) for i in range(9)}
+    assert len(seen) == 9 and "unknown status" not in seen
     assert lcn.lcn_status_string(99) == "unknown status"
 
 
@@ -107,9 +108,12 @@ def test_invalid_arguments_are_rejected_before_any_device_work():
     assert lib.transport_cost(None, ctypes.byref(d)) == ERR_STATE
     assert lib.plan_marginals(None, None, None, None) == ERR_STATE
     assert lib.lcn_get_scalings(None, None, None) == ERR_STATE
+    c = ctypes.c_int64(-7)
+    assert lib.lcn_last_error_counts(None, ctypes.byref(c), None, None) == ERR_STATE and c.value == -7
     junk = (ctypes.c_uint32 * 64)()
     assert lib.sinkhorn_run(ctypes.cast(junk, vp), 5) == ERR_STATE
     assert lib.sinkhorn_run(ctypes.cast(junk, vp), -1) == ERR_INVALID_ARG
+    assert lib.lcn_last_error_counts(ctypes.cast(junk, vp), None, None, None) == ERR_STATE
     lib.lcn_destroy(None)                                   # must be a no-op
     lib.lcn_destroy(ctypes.cast(junk, vp))
 

@@ -428,3 +428,151 @@ def test_coinciding_landmarks_with_a_ridge():
         np.testing.assert_allclose(U.cpu().numpy(), Uo, rtol=1e-6, atol=1e-7)
         np.testing.assert_allclose(Wt.cpu().numpy().T, Wo, rtol=0, atol=1e-6 * np.abs(Wo).max())
         lcn.lcn_destroy(h)
+
+
+def _two_clusters(counts_x, counts_y, gap, sigma, d=4, seed=7):
+    rng = np.random.default_rng(seed)
+
+    def pts(counts):
+        out = []
+        for c, k in enumerate(counts):
+            x = sigma * rng.standard_normal((k, d))
+            x[:, 0] += c * gap
+            out.append(x)
+        return np.concatenate(out).astype(np.float32)
+
+    return pts(counts_x), pts(counts_y)
+
+
+def test_scalings_spread_beyond_single_precision_range():
+    """Scalings that span more than single precision's e^87 and matter (App. "Implementational
+    details": log stabilisation).  Two clusters 200 lambda apart: every stored factor and value
+    between them is zero, so the kernel is two independent blocks that share only the exponent
+    taken out of each scaling vector.  The small block carries marginals of 2e-38 per point and
+    starts from log v = 30: its u settles e^110 below the large block's, and the sums of its
+    columns consist of such entries only.  The linear sweeps gather single-precision copies
+    exp(log x - max) * 2^64, which hold entries down to e^-131 below the largest; unscaled copies
+    (floor e^-87, nothing left below e^-103) would leave these sums at zero."""
+    import oracle
+    import torch
+    import paper_2107_06876_amd as lcn
+    from parity import gpu_build
+    X0, Y0 = _two_clusters((64,), (64,), gap=0.0, sigma=0.25, seed=1)
+    X1, Y1 = _two_clusters((192,), (192,), gap=0.0, sigma=1.0, seed=2)
+    X1[:, 0] += 20.0
+    Y1[:, 0] += 20.0
+    a = np.concatenate([np.full(64, 2e-38), np.full(192, 1 / 192)]).astype(np.float32)
+    p = workloads.Problem("two blocks", np.concatenate([X0, X1]), np.concatenate([Y0, Y1]), a, a.copy(), 2.0,
+                          workloads.COST_SQEUCLID, 16, 2, 2, 30)
+    lv0 = np.zeros(256, dtype=np.float32)
+    lv0[:64] = 30.0
+    B = oracle.build_problem(p.X, p.Y, p.cost, p.lam, "lcn", p.num_landmarks, p.landmark_seed, p.kmeans_iters,
+                             p.ridge, 0, p.num_buckets, p.num_rounds, p.lsh_seed, None)
+    st = oracle.sinkhorn(B.op, p.a, p.b, p.iters, oracle.SinkhornState(np.zeros(256), lv0.astype(np.float64)))
+    r_o, c_o, dist_o, resid_o = oracle.marginals(B.op, p.a, p.b, p.lam, st)
+    assert st.nonpositive == 0
+    spread = np.ptp(st.log_u)
+    assert 105.0 < spread < 125.0
+    h = gpu_build(p, "lcn")
+    np.testing.assert_array_equal(lcn.lcn_get_buckets(h).cpu().numpy(), B.buckets)
+    lcn.lcn_set_scalings(h, torch.zeros(256, device="cuda"), torch.from_numpy(lv0).cuda())
+    assert lcn.sinkhorn_run(h, p.iters, check=False) == lcn.binding.OK
+    lu, lv = (t.cpu().numpy().astype(np.float64) for t in lcn.lcn_get_scalings(h))
+    out = dict(spread=spread, log_u=np.abs(lu - st.log_u).max(), log_v=np.abs(lv - st.log_v).max())
+    dist = lcn.transport_cost(h)
+    r, c, resid = lcn.plan_marginals(h)
+    out["cost_rel"] = abs(dist - dist_o) / abs(dist_o)
+    out["resid_abs"] = abs(resid - resid_o)
+    print("spread", out, flush=True)
+    assert out["log_u"] <= 1e-4 and out["log_v"] <= 1e-4 and out["cost_rel"] <= 1e-4 and out["resid_abs"] <= 1e-5, out
+    # the small block's marginals are met to their own scale, not only to the large block's
+    np.testing.assert_allclose(c.cpu().numpy()[:64], c_o[:64], rtol=1e-4, atol=0)
+    np.testing.assert_allclose(r.cpu().numpy()[:64], r_o[:64], rtol=1e-4, atol=0)
+    lcn.lcn_destroy(h)
+
+
+def test_first_sweeps_of_a_fresh_state(monkeypatch):
+    """From u = v = 1 the first u is of the order of 1 / (K 1): with a kernel that is e^-60
+    everywhere (two tight clusters far apart, one bucket, one landmark -- a rank-one Nystrom part is
+    positive) that is e^50 above the exponent the state starts with, more than the copies hold.
+    The library runs each side's first sweep of a fresh state twice (first for the exponent);
+    with that switched off from the host the same run reports LCN_ERR_RANGE."""
+    import paper_2107_06876_amd as lcn
+    from parity import compare, gpu_build
+    X, Y = _two_clusters((128,), (0, 128), gap=7.75, sigma=0.1)
+    u = np.full(128, 1 / 128, np.float32)
+    p = workloads.Problem("far apart", X, Y, u, u, 1.0, workloads.COST_SQEUCLID, 1, 1, 1, 12)
+    # the landmark lies e^-40 from either cluster, so the Nystrom part (e^-80) stays below the kernel (e^-60)
+    p.landmark_init, p.landmark_iters = np.array([[3.875, 5.0, 0.0, 0.0]], dtype=np.float32), 0
+    out = compare(p, "lcn")
+    print("far apart", out, flush=True)
+    assert out["status"] == lcn.binding.OK
+    monkeypatch.setenv("LCN_DOUBLE_FIRST_SWEEP", "0")
+    h = gpu_build(p, "lcn")
+    assert lcn.sinkhorn_run(h, 3, check=False) == lcn.binding.ERR_RANGE
+    lcn.lcn_destroy(h)
+    monkeypatch.setenv("LCN_DOUBLE_FIRST_SWEEP", "1")
+    h = gpu_build(p, "lcn")
+    assert lcn.sinkhorn_run(h, 3, check=False) == lcn.binding.OK
+    lcn.lcn_destroy(h)
+
+
+def test_coinciding_landmarks_without_a_ridge_are_singular():
+    """Two landmarks on top of each other and no ridge: two rows of the landmark kernel matrix are
+    the same numbers, the Cholesky pivot of the second is exactly zero, and both sides refuse
+    (App. "Limitations"; LCN_ERR_SINGULAR from the build)."""
+    import torch
+    import oracle
+    import paper_2107_06876_amd as lcn
+    rng = np.random.default_rng(11)
+    X = rng.standard_normal((40, 6)).astype(np.float32)
+    Y = rng.standard_normal((30, 6)).astype(np.float32)
+    L = np.concatenate([X[:5], X[2:3], Y[:4]]).astype(np.float32)   # landmark 5 repeats landmark 2
+    a = torch.full((len(X),), 1.0 / len(X), device="cuda")
+    b = torch.full((len(Y),), 1.0 / len(Y), device="cuda")
+    for cost, ocost in ((lcn.COST_SQEUCLID, workloads.COST_SQEUCLID), (lcn.COST_COSINE, workloads.COST_COSINE)):
+        with pytest.raises(np.linalg.LinAlgError):
+            oracle.nystrom(X, Y, L, ocost, 2.0, 0.0)
+        lm = dict(num_landmarks=len(L), kmeans_iters=0, seed=1, init=lcn.INIT_GIVEN,
+                  init_centroids=torch.from_numpy(L).cuda(), ridge=0.0)
+        with pytest.raises(lcn.LcnError) as err:
+            lcn.lcn_build(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda(), a, b, 2.0, cost, lcn.MODE_NYSTROM,
+                          landmarks=lm)
+        assert err.value.status == lcn.binding.ERR_SINGULAR
+
+
+def test_a_sweep_that_gives_up_its_wait_reports_a_device_error(monkeypatch):
+    """The hand-over of a sweep's totals between workgroups is a bounded wait.  With the bound set to
+    zero ticks from the host, a workgroup that finds its totals still pending gives up at once:
+    every kernel still runs to its end, the run reports LCN_ERR_DEVICE, and the handle stays failed
+    (later calls on it keep saying so) while a fresh handle works."""
+    import paper_2107_06876_amd as lcn
+    from parity import gpu_build
+    p = workloads.config3(n=3000, d=48, landmarks=96, buckets=12, rounds=3, iters=6, name="C3 reduced")
+    monkeypatch.setenv("LCN_WAIT_TICKS", "0")
+    h = gpu_build(p, "lcn")
+    assert lcn.sinkhorn_run(h, 20, check=False) == lcn.binding.ERR_DEVICE
+    assert lcn.sinkhorn_run(h, 1, check=False) == lcn.binding.ERR_DEVICE
+    with pytest.raises(lcn.LcnError) as err:
+        lcn.lcn_last_error_counts(h)
+    assert err.value.status == lcn.binding.ERR_DEVICE
+    lcn.lcn_destroy(h)
+    monkeypatch.delenv("LCN_WAIT_TICKS")
+    h = gpu_build(p, "lcn")
+    assert lcn.sinkhorn_run(h, 20, check=False) == lcn.binding.OK
+    lcn.lcn_destroy(h)
+
+
+@pytest.mark.parametrize("mode,lam_factor", [("lcn", 0.5), ("nystrom", 0.5), ("lcn", 0.1), ("nystrom", 0.1),
+                                             ("lcn", 0.075)])
+def test_config2_full_size_lcn_and_nystrom(mode, lam_factor):
+    """Config 2 at its own size (n = m = 10 000, d = 64, l = 128, 64 buckets x 2 rounds, 100
+    iterations) with numbers: at the configuration's lambda = 0.05 * median both sides end in
+    non-positive sums (test_config2_full_size_dense_and_sparse), so the Nystrom and LCN paths are
+    compared where the oracle stays positive: 0.5 and 0.1 * median for both, and 0.075 * median for
+    LCN alone (there the Nystrom part by itself already fails; the correction keeps the sums
+    positive)."""
+    from parity import compare
+    p = workloads.config2(lam_factor=lam_factor)
+    out = compare(p, mode)
+    print("C2 full", mode, lam_factor, out, flush=True)

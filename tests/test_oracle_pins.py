@@ -312,6 +312,34 @@ def test_lcn_is_exact_on_the_pattern_and_nystrom_off_it():
     assert (Ksp[~mask] == 0).all()
 
 
+def test_nystrom_values_on_the_pattern_are_the_materialised_product():
+    """K^sp_Nys (Sec. 4: the Nystrom approximation restricted to the pattern) against the
+    materialised U W with n != m and l != n, m (a transposed or mis-strided operand fails), and
+    the decomposition K^sp_Delta = K^sp - K^sp_Nys of the three value modes."""
+    X, Y = _small_problem(12, n=23, m=17)
+    lam = 1.3
+    B = oracle.build_problem(X, Y, COST_SQEUCLID, lam, "lcn", num_landmarks=7, num_buckets=4, num_rounds=2,
+                             kmeans_iters=4)
+    rowptr, colidx = B.op.rowptr, B.op.colidx
+    assert 0 < colidx.size < 23 * 17
+    rows = np.repeat(np.arange(23), np.diff(rowptr))
+    UW = B.op.U @ B.op.W
+    knys = oracle.pattern_values(X, Y, COST_SQEUCLID, lam, rowptr, colidx, B.op.U, B.op.W, nystrom_only=True)
+    np.testing.assert_allclose(knys, UW[rows, colidx], rtol=1e-13, atol=1e-300)
+    # W read with the stride of its transpose is a different matrix, so the comparison can tell
+    wrong = B.op.U @ np.ascontiguousarray(B.op.W).reshape(17, 7).T
+    assert np.abs(knys - wrong[rows, colidx]).max() > 1e-3 * np.abs(knys).max()
+    ksp = oracle.pattern_values(X, Y, COST_SQEUCLID, lam, rowptr, colidx)
+    kdelta = oracle.pattern_values(X, Y, COST_SQEUCLID, lam, rowptr, colidx, B.op.U, B.op.W)
+    np.testing.assert_allclose(ksp - knys, kdelta, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(ksp, oracle.gibbs_kernel(X, Y, COST_SQEUCLID, lam)[rows, colidx], rtol=1e-14)
+    # a pattern of one entry per row (no bucket structure) picks the same entries
+    rp = np.arange(24, dtype=np.int64)
+    ci = ((5 * np.arange(23) + 3) % 17).astype(np.int32)
+    one = oracle.pattern_values(X, Y, COST_SQEUCLID, lam, rp, ci, B.op.U, B.op.W, nystrom_only=True)
+    np.testing.assert_allclose(one, UW[np.arange(23), ci], rtol=1e-13, atol=1e-300)
+
+
 def test_single_bucket_makes_sparse_and_lcn_equal_dense():
     X, Y = _small_problem(11, n=30, m=30)
     lam = 2.0
