@@ -518,19 +518,20 @@ def test_first_sweeps_of_a_fresh_state(monkeypatch):
 
 
 def test_coinciding_landmarks_without_a_ridge_are_singular():
-    """Two landmarks on top of each other and no ridge: two rows of the landmark kernel matrix are
-    the same numbers, the Cholesky pivot of the second is exactly zero, and both sides refuse
-    (App. "Limitations"; LCN_ERR_SINGULAR from the build)."""
+    """The first two landmarks on top of each other and no ridge: A_00 = A_10 = A_11 = exp(0) = 1
+    exactly, so the second Cholesky pivot is 1 - 1 * 1 = 0 whatever the order of operations, and
+    both sides refuse (App. "Limitations"; LCN_ERR_SINGULAR from the build).  (A repeated landmark
+    further down leaves a pivot that is zero only up to rounding: see the test with a ridge.)"""
     import torch
     import oracle
     import paper_2107_06876_amd as lcn
     rng = np.random.default_rng(11)
     X = rng.standard_normal((40, 6)).astype(np.float32)
     Y = rng.standard_normal((30, 6)).astype(np.float32)
-    L = np.concatenate([X[:5], X[2:3], Y[:4]]).astype(np.float32)   # landmark 5 repeats landmark 2
+    L = np.concatenate([X[:1], X[:1], X[1:5], Y[:4]]).astype(np.float32)   # landmark 1 repeats landmark 0
     a = torch.full((len(X),), 1.0 / len(X), device="cuda")
     b = torch.full((len(Y),), 1.0 / len(Y), device="cuda")
-    for cost, ocost in ((lcn.COST_SQEUCLID, workloads.COST_SQEUCLID), (lcn.COST_COSINE, workloads.COST_COSINE)):
+    for cost, ocost in ((lcn.COST_SQEUCLID, workloads.COST_SQEUCLID), (lcn.COST_EUCLID, workloads.COST_EUCLID)):
         with pytest.raises(np.linalg.LinAlgError):
             oracle.nystrom(X, Y, L, ocost, 2.0, 0.0)
         lm = dict(num_landmarks=len(L), kmeans_iters=0, seed=1, init=lcn.INIT_GIVEN,
