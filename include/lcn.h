@@ -271,6 +271,21 @@ lcn_status lcn_backward_scratch_bytes(lcn_handle h, size_t *bytes);
 lcn_status lcn_backward(lcn_handle h, float *gU_dev, float *gWt_dev, float *gsp_dev, float *gnys_dev,
                         void *scratch_dev, size_t scratch_bytes);
 
+/* lcn_backward for callers that cannot allocate device memory or hand over a
+ * scratch buffer: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same outputs, same kernels, same results as
+ * lcn_backward; the scratch is an array of LCN_STATIC_SCRATCH_BYTES that the
+ * library's device image holds on every GPU it runs on until the process ends.
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine) and still synchronises the handle's stream.  A handle that needs
+ * more than the array holds (lcn_backward_scratch_bytes: 8 (n + 1) +
+ * 8 (nnz_stored + 64) bytes, rounded up) gets LCN_ERR_ALLOC and nothing is
+ * launched.  All calls on one GPU share that GPU's array, whatever their handle
+ * or stream, and it keeps the last call's contents: two calls that overlap on
+ * one GPU race and corrupt each other's pattern outputs -- serialise them. */
+#define LCN_STATIC_SCRATCH_BYTES (32u << 20)
+lcn_status lcn_backward_static(lcn_handle h, float *gU_dev, float *gWt_dev, float *gsp_dev, float *gnys_dev);
+
 /* Rows i0 .. i0 + nrows - 1 of the current transport plan P = diag(u) K~ diag(v)
  * (Sec. 2; for the lcn mode the decomposed plan of Sec. 4 eq. 4 written out),
  * as a dense nrows x m block, row-major, device fp32.  For inspection and for

@@ -99,7 +99,8 @@ def load_library():
         for name in ("lcn_build_batched", "lcn_batched_results", "lcn_batched_get", "lcn_deletion_costs",
                      "lcn_head_lambdas", "lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
-                     "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing", "lcn_last_error_counts"):
+                     "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing", "lcn_last_error_counts",
+                     "lcn_backward_static"):
             getattr(lib, name).restype = i32
         _lib = lib
     return _lib
@@ -323,6 +324,13 @@ def lcn_backward(h: LcnHandle, nnz: int = 0, factors: bool = True, pattern: bool
     if st != OK:
         raise LcnError(st, "lcn_backward")
     return gU, gWt, gsp, gnys
+
+
+def lcn_backward_static(h: LcnHandle, gU=None, gWt=None, gsp=None, gnys=None) -> int:
+    """lcn_backward into the caller's outputs (each may be None) with the library's own static
+    scratch: the call itself allocates nothing.  Returns the status."""
+    outs = [None if t is None else _dev(t, torch.float32) for t in (gU, gWt, gsp, gnys)]
+    return load_library().lcn_backward_static(h.raw, *[_ptr(t) for t in outs])
 
 
 def lcn_plan_rows(h: LcnHandle, i0: int, nrows: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -771,6 +771,33 @@ struct Builder {
 
 bool valid(lcn_handle hh) { return hh && ((Handle *)hh)->magic == HANDLE_MAGIC; }
 
+// Scratch of lcn_backward_static: one array per device in the library's own device image, there from
+// the moment the image is loaded until the process ends.  Host code never uses the array's name as an
+// address: the device address is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[LCN_STATIC_SCRATCH_BYTES];
+
+lcn_status static_scratch(void **out)
+{
+    static std::mutex mu;
+    static void *ptr_of_device[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return LCN_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of_device[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return LCN_ERR_DEVICE;
+        }
+        ptr_of_device[dev] = ptr;
+    }
+    *out = ptr_of_device[dev];
+    return LCN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1068,6 +1095,21 @@ lcn_status lcn_backward(lcn_handle hh, float *gU_dev, float *gWt_dev, float *gsp
     }
     HIPCHK(hipStreamSynchronize(h.stream));
     return LCN_OK;
+}
+
+lcn_status lcn_backward_static(lcn_handle hh, float *gU_dev, float *gWt_dev, float *gsp_dev, float *gnys_dev)
+{
+    if (!valid(hh)) return LCN_ERR_STATE;
+    const Handle &h = *(Handle *)hh;
+    void *ptr = nullptr;
+    if ((gsp_dev || gnys_dev) && h.R > 0) {
+        if (backward_scratch(h) > (size_t)LCN_STATIC_SCRATCH_BYTES) return LCN_ERR_ALLOC;
+        const lcn_status st = static_scratch(&ptr);
+        if (st != LCN_OK) return st;
+    }
+    // every word of the scratch that is read is written first by the same call (row pointers by the
+    // count and scan, the two record arrays by the pattern kernels): nothing has to start at zero
+    return lcn_backward(hh, gU_dev, gWt_dev, gsp_dev, gnys_dev, ptr, ptr ? (size_t)LCN_STATIC_SCRATCH_BYTES : 0);
 }
 
 lcn_status lcn_plan_rows(lcn_handle hh, int64_t i0, int64_t nrows, float *out_dev)

@@ -25,7 +25,7 @@ def test_header_declares_the_expected_entry_points():
                      "lcn_get_factors", "lcn_get_info", "lcn_destroy", "lcn_status_string", "lcn_build_batched",
                      "lcn_batched_results", "lcn_batched_get", "lcn_last_run_timing", "lcn_backward",
                      "lcn_backward_scratch_bytes", "lcn_plan_rows", "lcn_deletion_costs", "lcn_head_lambdas",
-                     "lcn_last_error_counts"):
+                     "lcn_last_error_counts", "lcn_backward_static"):
         assert required in names
 
 
@@ -114,6 +114,8 @@ def test_invalid_arguments_are_rejected_before_any_device_work():
     assert lib.sinkhorn_run(ctypes.cast(junk, vp), 5) == ERR_STATE
     assert lib.sinkhorn_run(ctypes.cast(junk, vp), -1) == ERR_INVALID_ARG
     assert lib.lcn_last_error_counts(ctypes.cast(junk, vp), None, None, None) == ERR_STATE
+    assert lib.lcn_backward_static(None, None, None, None, None) == ERR_STATE
+    assert lib.lcn_backward_static(ctypes.cast(junk, vp), None, None, None, None) == ERR_STATE
     lib.lcn_destroy(None)                                   # must be a no-op
     lib.lcn_destroy(ctypes.cast(junk, vp))
 
