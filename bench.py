@@ -10,8 +10,13 @@ library's stream); build time and the whole step are reported beside it.
 Prints ONE JSON line.  roofline.achieved = algorithmic bytes of one
 half-iteration launch (every factor entry and every sparse value once) divided
 by the average duration of such a launch, from HIP events around sinkhorn_run;
-roofline.traffic = HBM bytes per launch from the hardware counters (a stored
-figure from the rocprofv3 runs whose summaries sit under profiles/).
+roofline.traffic = HBM bytes per launch from the hardware counters: read, at
+run time, from the counter table of the rocprofv3 summary under profiles/ that
+covers the workload (null if that file has no such row).
+
+The default run (configuration 3, the metric's) also carries a short record
+"c5" for configuration 5 (n = m = 200 000, where the sweep is bound by HBM and
+not by launch latency) and times the oracle twice: on all host cores and on one.
 """
 from __future__ import annotations
 
@@ -41,11 +46,40 @@ def make_problem(config: int):
     raise SystemExit("unknown --config %d" % config)
 
 
-def cpu_baseline(p, sample_iters: int):
+def _omp_threads(n=None):
+    """Thread count of the OpenMP runtime the oracle runs on; sets it first if n is given."""
+    import ctypes
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        if n is not None:
+            gomp.omp_set_num_threads(int(n))
+        return int(gomp.omp_get_max_threads())
+    except OSError:
+        return int(os.environ.get("OMP_NUM_THREADS", "0")) or os.cpu_count()
+
+
+def counter_traffic(config: int):
+    """HBM bytes per pass_kernel launch from the counter table of the profile summary of this
+    configuration (scaled read MB + scaled write MB of the fused update sweep), or None."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "lcn_sinkhorn_c%d_*.md" % config))):
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 6 and re.match(r"`pass_kernel<.*true>`", cells[1]):
+                try:
+                    return (float(cells[5]) + float(cells[6])) * 1e6
+                except ValueError:
+                    pass
+    return None
+
+
+def cpu_baseline(p, sample_iters: int, one_thread_iters: int = 0):
     """The oracle as it stands on the host cores: full build of the same
-    problem, then a few iterations."""
+    problem, then a few iterations; then (one_thread_iters > 0) a shorter run on
+    one thread."""
     import oracle
-    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or os.cpu_count()
+    threads = _omp_threads()
     t0 = time.perf_counter()
     B = oracle.build_problem(p.X, p.Y, p.cost, p.lam, "lcn", p.num_landmarks, p.landmark_seed, p.kmeans_iters,
                              p.ridge, 0, p.num_buckets, p.num_rounds, p.lsh_seed, p.projections,
@@ -54,12 +88,135 @@ def cpu_baseline(p, sample_iters: int):
     st = oracle.sinkhorn(B.op, p.a, p.b, sample_iters)
     t2 = time.perf_counter()
     _, _, dist, resid = oracle.marginals(B.op, p.a, p.b, p.lam, st)
-    return {
+    out = {
         "value": sample_iters / (t2 - t1), "unit": "iterations/s", "cores": threads, "kind": "oracle",
         "sample": "full oracle build of the same problem (%.1f s) then %d Sinkhorn iterations (%.2f s)"
                   % (t1 - t0, sample_iters, t2 - t1),
         "build_ms": 1e3 * (t1 - t0),
-    }, (st, dist, resid)
+    }
+    if one_thread_iters > 0:
+        _omp_threads(1)
+        t3 = time.perf_counter()
+        oracle.sinkhorn(B.op, p.a, p.b, one_thread_iters)
+        t4 = time.perf_counter()
+        _omp_threads(threads)
+        out["one_thread"] = {"value": one_thread_iters / (t4 - t3), "unit": "iterations/s", "cores": 1,
+                             "sample": "%d Sinkhorn iterations of the same problem on one thread (%.2f s)"
+                                       % (one_thread_iters, t4 - t3)}
+    return out, (st, dist, resid)
+
+
+def timed_run(config: int, mode_name: str, steps: int, warmup: int):
+    """A short run of the whole path on another configuration (same step as the main loop:
+    lcn_build + sinkhorn_run + transport_cost, inputs resident, workspace reused): its iterations/s,
+    build time and the roofline of its half-iteration kernel."""
+    import numpy as np
+    import torch
+
+    import paper_2107_06876_amd as lcn
+
+    p, wl = make_problem(config)
+    dev = "cuda:0"
+    dt = torch.bfloat16 if p.bf16_inputs else torch.float32
+    X = torch.from_numpy(p.X).to(dev).to(dt)
+    Y = torch.from_numpy(p.Y).to(dev).to(dt)
+    a = torch.from_numpy(p.a).to(dev)
+    b = torch.from_numpy(p.b).to(dev)
+    mode = {"lcn": lcn.MODE_LCN, "sparse": lcn.MODE_SPARSE, "nystrom": lcn.MODE_NYSTROM, "dense": lcn.MODE_DENSE}[mode_name]
+    lm = dict(num_landmarks=p.num_landmarks, kmeans_iters=p.kmeans_iters, seed=p.landmark_seed, ridge=p.ridge)
+    lsh = dict(hash=lcn.HASH_KMEANS, num_buckets=p.num_buckets, num_rounds=p.num_rounds,
+               kmeans_iters=p.kmeans_iters, seed=p.lsh_seed)
+    h = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh)
+    ws = h.workspace
+    info = lcn.lcn_get_info(h)
+    lcn.lcn_destroy(h)
+    build_ms, run_ms, launches, dist = [], [], 0, None
+    t0 = None
+    for it in range(warmup + steps):
+        if it == warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        tb = time.perf_counter()
+        hh = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh, workspace=ws)
+        te = time.perf_counter()
+        lcn.sinkhorn_run(hh, p.iters)
+        ms, launches = lcn.lcn_last_run_timing(hh)
+        dist = lcn.transport_cost(hh)
+        lcn.lcn_destroy(hh)
+        if it >= warmup:
+            build_ms.append(1e3 * (te - tb))
+            run_ms.append(ms)
+    torch.cuda.synchronize()
+    ms_per_step = 1e3 * (time.perf_counter() - t0) / steps
+    run_mean = float(np.mean(run_ms))
+    bytes_launch = (4.0 * (p.n * info.l + info.l * p.m) + 8.0 * info.nnz_unique) / 2.0
+    launch_us = run_mean * 1e3 / max(launches, 1)
+    achieved = bytes_launch / (launch_us * 1e-6) / 1e9
+    del X, Y, ws
+    torch.cuda.empty_cache()
+    return {"workload": wl, "steps": steps, "warmup": warmup, "value": p.iters / (run_mean * 1e-3),
+            "unit": "iterations/s", "ms_per_step": ms_per_step, "build_ms": float(np.mean(build_ms)),
+            "sinkhorn_ms": run_mean, "distance": dist, "nnz_unique": info.nnz_unique,
+            "roofline": {"bound": "hbm", "kernel": "pass_kernel (one half-iteration)", "achieved": achieved,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                         "traffic": counter_traffic(config), "bytes_per_launch": bytes_launch,
+                         "launch_us": launch_us}}
+
+
+def plan_measures(h_approx, h_exact, n):
+    """Pearson correlation of all plan entries and overlap (IoU) of the 0.1 % largest ones between an
+    approximate plan and the dense one (the other two columns of the paper's accuracy table, Sec. 8)."""
+    import torch
+
+    import paper_2107_06876_amd as lcn
+    Pa = lcn.lcn_plan_rows(h_approx, 0, n).flatten()
+    Pe = lcn.lcn_plan_rows(h_exact, 0, n).flatten()
+    x, y = Pa.double(), Pe.double()
+    xm, ym = x.mean(), y.mean()
+    pcc = float(((x - xm) * (y - ym)).sum() / torch.sqrt(((x - xm) ** 2).sum() * ((y - ym) ** 2).sum()))
+    k = max(Pa.numel() // 1000, 1)
+    ta = torch.topk(Pa, k).indices
+    te = torch.topk(Pe, k).indices
+    inter = int(torch.isin(ta, te).sum())
+    return pcc, inter / (2 * k - inter)
+
+
+def accuracy_table():
+    """Relative error of the Sinkhorn distance, PCC and IoU of LCN-Sinkhorn against dense Sinkhorn
+    (Table 1's three columns) on configuration 1, on configuration 2 at the largest-but-one lambda
+    where its LCN path stays positive (0.5 x median; at the configuration's own 0.05 x median both sides
+    report non-positive sums), and on the paper's own synthetic workload (uniform in the d-ball,
+    d = 16, n = 10^4, lambda = 0.05: Table 1 prints 0.435 / 0.328 / 0.079 for LCN).  Outside the timed
+    region; everything through the library."""
+    import torch
+
+    import paper_2107_06876_amd as lcn
+    import workloads
+    out = {}
+    dev = "cuda:0"
+    for name, p in (("c1", workloads.config1()), ("c2_lambda_0.5_median", workloads.config2(lam_factor=0.5)),
+                    ("dball", workloads.dball())):
+        X, Y = torch.from_numpy(p.X).to(dev), torch.from_numpy(p.Y).to(dev)
+        a, b = torch.from_numpy(p.a).to(dev), torch.from_numpy(p.b).to(dev)
+        lm = dict(num_landmarks=p.num_landmarks, kmeans_iters=p.kmeans_iters, seed=p.landmark_seed, ridge=p.ridge)
+        lsh = dict(hash=lcn.HASH_KMEANS, num_buckets=p.num_buckets, num_rounds=p.num_rounds,
+                   kmeans_iters=p.kmeans_iters, seed=p.lsh_seed)
+        try:
+            hd = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, lcn.MODE_DENSE)
+            lcn.sinkhorn_run(hd, p.iters)
+            hl = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, lcn.MODE_LCN, landmarks=lm, lsh=lsh)
+            lcn.sinkhorn_run(hl, p.iters)
+            d_d, d_l = lcn.transport_cost(hd), lcn.transport_cost(hl)
+            pcc, iou = plan_measures(hl, hd, p.n)
+            out[name] = {"cost_rel_err_vs_dense": abs(d_l - d_d) / abs(d_d), "pcc": pcc, "iou_top_0.1pct": iou,
+                         "distance_lcn": d_l, "distance_dense": d_d}
+            lcn.lcn_destroy(hl)
+            lcn.lcn_destroy(hd)
+            del hl, hd
+        except lcn.LcnError as e:
+            out[name] = {"note": str(e)}
+        torch.cuda.empty_cache()
+    return out
 
 
 def bench_batched(args):
@@ -133,6 +290,8 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
+    ap.add_argument("--no-c5", action="store_true",
+                    help="leave out the short record for configuration 5 that the default run carries")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 256 MiB device-to-device copy so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "can be scaled by what the same counter reads for a copy of known size")
@@ -182,6 +341,11 @@ def main():
     lm = lm if args.mode in ("lcn", "nystrom") else None
     lsh = lsh if args.mode in ("lcn", "sparse") else None
 
+    if args.config == 3 and args.mode == "lcn" and not args.no_c5:
+        c5 = timed_run(5, "lcn", 3, 1)
+    else:
+        c5 = None
+
     # first build sizes the workspace; every later build reuses it (no allocation in the timed region)
     h = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh)
     ws = h.workspace
@@ -224,7 +388,7 @@ def main():
     achieved = bytes_launch / (launch_us * 1e-6) / 1e9
     # HBM bytes per pass_kernel launch from the rocprofv3 counter runs (FETCH_SIZE scaled by 2.000 plus
     # WRITE_SIZE scaled by 1.000 against a 256 MiB device copy); see profiles/lcn_sinkhorn_c*.md
-    traffic = {3: 35.92e6 + 2.10e6, 5: 615.90e6 + 29.13e6}.get(args.config) if args.mode == "lcn" else None
+    traffic = counter_traffic(args.config) if args.mode == "lcn" else None
     out = {
         "metric": "LCN-Sinkhorn iterations/s (n=20k,d=300); build ms; % HBM peak; cost rel.err",
         "value": its_per_s, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -237,6 +401,8 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": bytes_launch, "launch_us": launch_us},
     }
+    if c5 is not None:
+        out["c5"] = c5
     if args.copy_calibration:
         src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -278,6 +444,8 @@ def main():
                                  "cost_rel_err_vs_dense": abs(d_l - d_d) / abs(d_d)}
         except lcn.LcnError as e:
             out["prealigned"] = {"note": str(e)}
+    if args.config == 3 and args.mode == "lcn" and not args.no_accuracy:
+        out["accuracy_table"] = accuracy_table()
     if args.mode in ("lcn", "nystrom") and not args.no_accuracy:
         # analytic derivatives (Prop. 1) of the converged state, outside the timed region
         hb = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh, workspace=ws)
@@ -290,7 +458,7 @@ def main():
         out["backward_ms"] = 1e3 * (time.perf_counter() - tb)
         lcn.lcn_destroy(hb)
     if not args.no_cpu_baseline:
-        base, (st, dist_o, resid_o) = cpu_baseline(p, args.cpu_iters)
+        base, (st, dist_o, resid_o) = cpu_baseline(p, args.cpu_iters, max(1, args.cpu_iters // 8))
         out["cpu_baseline"] = base
         # parity of a short GPU run against the same oracle run (outside the timed region)
         hh = lcn.lcn_build(X, Y, a, b, p.lam, p.cost, mode, landmarks=lm, lsh=lsh, workspace=ws)

@@ -320,7 +320,9 @@ lcn_status lcn_last_error_counts(lcn_handle h, int64_t *nonpositive, int64_t *em
 
 /* Elapsed GPU time in milliseconds of the kernels of the last sinkhorn_run on
  * this handle, measured with HIP events on the handle's stream, and the
- * number of half-iteration launches it covered. */
+ * number of half-iteration launches it covered (2 per iteration, plus 2 for the
+ * first run after a build or lcn_set_scalings, whose first sweep over each side
+ * runs twice: once to learn the exponent of its result). */
 lcn_status lcn_last_run_timing(lcn_handle h, float *ms_host, int32_t *launches_host);
 
 void lcn_destroy(lcn_handle h); /* frees host memory only; the workspace is the caller's */

@@ -906,6 +906,7 @@ hipError_t launch_update_sweeps(Handle &h, int iters, hipStream_t s)
         if (e != hipSuccess) return e;
         first = 1;   // the loop below starts with the sweep over Y, now with its exponent known
     }
+    h.last_launches = 2 * iters + (first ? 2 : 0);   // half-iteration launches of this run, the repeated ones included
     if (iters > 0) h.fresh = 0;
     for (int t = first; t < 2 * iters; ++t) {
         const int side = t & 1;

@@ -932,8 +932,7 @@ lcn_status sinkhorn_run(lcn_handle hh, int32_t iters)
     if (st == LCN_ERR_DEVICE) return st;
     float ms = 0.f;
     HIPCHK(hipEventElapsedTime(&ms, h.ev0, h.ev1));
-    h.last_ms = ms;
-    h.last_launches = 2 * iters;
+    h.last_ms = ms;   // h.last_launches: set by launch_update_sweeps
     return st;
 }
 
