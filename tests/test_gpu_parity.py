@@ -577,3 +577,38 @@ def test_config2_full_size_lcn_and_nystrom(mode, lam_factor):
     p = workloads.config2(lam_factor=lam_factor)
     out = compare(p, mode)
     print("C2 full", mode, lam_factor, out, flush=True)
+
+
+@pytest.mark.parametrize("case", ["config1", "config2 reduced", "config3 reduced", "unequal sides", "five rounds",
+                                  "ragged", "one by one", "long buckets"])
+def test_block_sweep_parity(case, monkeypatch):
+    """The sparse part of a half-iteration taken bucket block by bucket block in a launch of its own
+    (what large problems use) against the oracle, forced here on small problems: blocks of fewer and
+    more than 64 rows, more than four hash rounds, a single point per side, buckets longer than one
+    column chunk (more than 256 members of the other side), empty buckets."""
+    from parity import compare
+    monkeypatch.setenv("LCN_SPLIT_SWEEP", "1")
+    if case == "config1":
+        p = workloads.config1()
+    elif case == "config2 reduced":
+        p = workloads.config2(n=1500, landmarks=100, buckets=24, lam_factor=0.5)
+        p.iters = 40
+    elif case == "config3 reduced":
+        p = workloads.config3(n=3000, landmarks=96, buckets=20, iters=60)
+    elif case == "unequal sides":
+        rng = np.random.default_rng(5)
+        p = workloads.config1(n=700, d=9)
+        p.Y = p.Y[:450].copy()
+        b = rng.random(450) + 0.2
+        p.b = (b / b.sum()).astype(np.float32)
+        p.num_landmarks, p.num_buckets, p.iters = 37, 7, 30
+    elif case == "five rounds":
+        p = _edge_problem(129, 127, 64, 33, 5, 5)
+    elif case == "ragged":
+        p = _edge_problem(300, 200, 5, 7, 3, 6)
+    elif case == "one by one":
+        p = _edge_problem(1, 1, 1, 1, 1, 1)
+    else:
+        p = workloads.config3(n=2500, d=40, landmarks=64, buckets=3, rounds=2, iters=20, name="C3 reduced")
+    out = compare(p, "lcn")
+    print("block sweep", case, out, flush=True)
