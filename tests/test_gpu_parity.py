@@ -581,13 +581,11 @@ def test_config2_full_size_lcn_and_nystrom(mode, lam_factor):
 
 @pytest.mark.parametrize("case", ["config1", "config2 reduced", "config3 reduced", "unequal sides", "five rounds",
                                   "ragged", "one by one", "long buckets"])
-def test_block_sweep_parity(case, monkeypatch):
-    """The sparse part of a half-iteration taken bucket block by bucket block in a launch of its own
-    (what large problems use) against the oracle, forced here on small problems: blocks of fewer and
-    more than 64 rows, more than four hash rounds, a single point per side, buckets longer than one
-    column chunk (more than 256 members of the other side), empty buckets."""
+def test_bucket_shapes(case):
+    """More shapes of the bucket blocks against the oracle: blocks of fewer and more than 64 rows,
+    more than four hash rounds, a single point per side, buckets of more than 256 members of the
+    other side (record segments far longer than a wavefront), empty buckets."""
     from parity import compare
-    monkeypatch.setenv("LCN_SPLIT_SWEEP", "1")
     if case == "config1":
         p = workloads.config1()
     elif case == "config2 reduced":
@@ -611,4 +609,4 @@ def test_block_sweep_parity(case, monkeypatch):
     else:
         p = workloads.config3(n=2500, d=40, landmarks=64, buckets=3, rounds=2, iters=20, name="C3 reduced")
     out = compare(p, "lcn")
-    print("block sweep", case, out, flush=True)
+    print("bucket shapes", case, out, flush=True)
