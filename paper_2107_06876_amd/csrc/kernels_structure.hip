@@ -855,6 +855,83 @@ __global__ __launch_bounds__(64 * WPB) void kmeans_sum_kernel(const float *__res
     }
 }
 
+// Many clusters (at least two workgroups per compute unit without slicing): one workgroup per cluster
+// takes whole rows.  A slice of 64 dimensions of a row of d floats starts at no particular alignment, so
+// a 256-byte read of it touches three 128-byte lines and leaves half a line on either side to be fetched
+// again by the workgroup of the neighbouring slice, much later; a whole row is contiguous and its lines
+// are fetched once.  Lane j holds the sums of dimensions j, 64 + j, ...; NS = ceil(d / 64) <= 8.
+template <int NS, int WPB>
+__global__ __launch_bounds__(64 * WPB) void kmeans_sum_rows_kernel(const float *__restrict__ Z, int d, int k,
+                                                               const int *__restrict__ counts,
+                                                               const int *__restrict__ offs,
+                                                               const int *__restrict__ order, float *__restrict__ cent,
+                                                               int *__restrict__ counts_next,
+                                                               int *__restrict__ cursor_next, unsigned *reset_a,
+                                                               int *reset_b)
+{
+    __shared__ long long red[WPB][NS][64];
+    const int c = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (threadIdx.x == 0) {  // scratch of the next assignment and update steps starts from zero
+        counts_next[c] = 0;
+        cursor_next[c] = 0;
+        if (c == 0) {
+            if (reset_a) *reset_a = 0u;
+            if (reset_b) {
+                reset_b[0] = 0;
+                reset_b[1] = 0;
+            }
+        }
+    }
+    const int cnt = counts[c];
+    const int *__restrict__ mem = order + offs[c];
+    long long sum[NS];
+#pragma unroll
+    for (int q = 0; q < NS; ++q) sum[q] = 0;
+    // the wavefronts share out the members in contiguous runs; a wave reads up to 64 member indices at
+    // once (one per lane) and then requests four members' rows before the first is added
+    const int per = (cnt + WPB - 1) / WPB;
+    const int beg = wave * per;
+    const int end = beg + per < cnt ? beg + per : cnt;
+    for (int base = beg; base < end; base += 64) {
+        const int nloc = end - base < 64 ? end - base : 64;
+        const int myidx = lane < nloc ? mem[base + lane] : 0;
+        for (int u0 = 0; u0 < nloc; u0 += 4) {
+            float z[4][NS];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int uu = u0 + u < 64 ? u0 + u : 63;
+                const long long row = __builtin_amdgcn_readlane(myidx, uu);
+#pragma unroll
+                for (int q = 0; q < NS; ++q) {
+                    const int j = 64 * q + lane;
+                    z[u][q] = (u0 + u < nloc && j < d) ? Z[row * d + j] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int q = 0; q < NS; ++q) sum[q] += __double2ll_rn((double)z[u][q] * 4294967296.0);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < NS; ++q) red[wave][q][lane] = sum[q];
+    __syncthreads();
+    if (cnt > 0) {  // an empty cluster keeps its centroid
+        for (int t = threadIdx.x; t < 64 * NS; t += 64 * WPB) {
+            const int q = t >> 6, jl = t & 63, j = 64 * q + jl;
+            if (j < d) {
+                long long tot = 0;
+#pragma unroll
+                for (int w = 0; w < WPB; ++w) tot += red[w][q][jl];
+                const double mean = ((double)tot * (1.0 / 4294967296.0)) / (double)cnt;
+                cent[(long long)c * d + j] = (float)mean;
+            }
+        }
+    }
+}
+
 // counts2 / cursor2: [2][k] each, zero on the first call of a k-means run; offs: [k]; `parity` alternates per call.
 // reset_a / reset_b (nullable) are cleared for the next assignment step.
 hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, int *counts2,
@@ -867,12 +944,28 @@ hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_
     hipLaunchKernelGGL(kmeans_count_kernel, dim3(blocks), dim3(256), sizeof(int) * (size_t)k, s, assign, N, k, counts);
     hipLaunchKernelGGL(kmeans_scatter_kernel, dim3(blocks), dim3(256), 2 * sizeof(int) * (size_t)k, s, assign, N, k,
                        counts, cursor, order, offs);
-    if ((long long)k * ((d + 63) / 64) >= 512)
+    const int ns = (d + 63) / 64;
+#define LCN_SUM_ROWS(NS_)                                                                                           \
+    hipLaunchKernelGGL((kmeans_sum_rows_kernel<NS_, 8>), dim3((unsigned)k), dim3(512), 0, s, Z, d, k, counts, offs, \
+                       order, cent, counts_next, cursor_next, reset_a, reset_b)
+    if (k >= 512 && ns <= 8) {
+        switch (ns) {
+            case 1: LCN_SUM_ROWS(1); break;
+            case 2: LCN_SUM_ROWS(2); break;
+            case 3: LCN_SUM_ROWS(3); break;
+            case 4: LCN_SUM_ROWS(4); break;
+            case 5: LCN_SUM_ROWS(5); break;
+            case 6: LCN_SUM_ROWS(6); break;
+            case 7: LCN_SUM_ROWS(7); break;
+            default: LCN_SUM_ROWS(8); break;
+        }
+    } else if ((long long)k * ((d + 63) / 64) >= 512)
         hipLaunchKernelGGL((kmeans_sum_kernel<64, 16>), dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(1024), 0, s, Z,
                            d, k, counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
     else   // few clusters: narrower slices, four times the workgroups
         hipLaunchKernelGGL((kmeans_sum_kernel<16, 16>), dim3((unsigned)k, (unsigned)((d + 15) / 16)), dim3(1024), 0, s, Z,
                            d, k, counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
+#undef LCN_SUM_ROWS
     return hipGetLastError();
 }
 
