@@ -837,7 +837,10 @@ __global__ __launch_bounds__(64 * WPB) void kmeans_sum_kernel(const float *__res
                     row = __builtin_amdgcn_readlane(myidx, uu < 64 ? uu : 63);
                 else
                     row = __shfl(myidx, uu < 64 ? uu : 63, 64);
-                z[u] = (uu < nloc && jin) ? Z[row * d + j] : 0.f;
+                // an unconditional load (a slot beyond the run reads row 0, a lane beyond the row's end
+                // its last entry) keeps all sixteen in flight; what does not count is zeroed afterwards
+                const float v = Z[row * d + (jin ? j : d - 1)];
+                z[u] = (uu < nloc && jin) ? v : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < 16; ++u) sum += __double2ll_rn((double)z[u] * 4294967296.0);
@@ -855,21 +858,115 @@ __global__ __launch_bounds__(64 * WPB) void kmeans_sum_kernel(const float *__res
     }
 }
 
-// Many clusters (at least two workgroups per compute unit without slicing): one workgroup per cluster
-// takes whole rows.  A slice of 64 dimensions of a row of d floats starts at no particular alignment, so
-// a 256-byte read of it touches three 128-byte lines and leaves half a line on either side to be fetched
-// again by the workgroup of the neighbouring slice, much later; a whole row is contiguous and its lines
-// are fetched once.  Lane j holds the sums of dimensions j, 64 + j, ...; NS = ceil(d / 64) <= 8.
-template <int NS, int WPB>
-__global__ __launch_bounds__(64 * WPB) void kmeans_sum_rows_kernel(const float *__restrict__ Z, int d, int k,
-                                                               const int *__restrict__ counts,
-                                                               const int *__restrict__ offs,
-                                                               const int *__restrict__ order, float *__restrict__ cent,
-                                                               int *__restrict__ counts_next,
-                                                               int *__restrict__ cursor_next, unsigned *reset_a,
-                                                               int *reset_b)
+// Rows of up to 512 dimensions: the sums are taken in two steps that do not depend on how the members
+// are spread over the clusters.  The member list (grouped by cluster) is cut into chunks of M
+// consecutive entries, one wavefront per chunk; the wavefront reads whole rows (lane j holds dimensions
+// j, 64 + j, ...: every line of a row is fetched once, eight rows requested before the first is added)
+// and, whenever the cluster changes and at its end, writes the sums so far as a partial: chunk g's
+// part of cluster c goes to slot g + c, which no other pair shares (chunks and clusters both advance
+// along the list).  One workgroup per cluster then adds the partials of the chunks its members lie in
+// and writes the mean.  No atomics, every launch as long as the others whatever the cluster sizes.
+// The fixed-point value of an entry: z 2^32 + 1.5 2^52 rounds to an integer (to nearest even, as rint
+// does) whose low mantissa bits are that integer in two's complement, so the bit patterns are added
+// as they are and the constants' share is taken off per member (all modulo 2^64).
+int kmeans_sum_chunk(long long N) { return N <= 65536 ? 16 : N <= 131072 ? 32 : N <= 262144 ? 64 : 128; }
+
+size_t kmeans_partial_elems(long long N, int kmax, int d)
 {
-    __shared__ long long red[WPB][NS][64];
+    if (d > 512) return 1;   // wider rows take the sliced kernel, which needs none
+    const int M = kmeans_sum_chunk(N);
+    return (size_t)((N + M - 1) / M + kmax) * (size_t)d;
+}
+
+constexpr unsigned long long FIX_MAGIC_BITS = 0x4338000000000000ull;   // 1.5 * 2^52
+
+template <int NS>
+__global__ __launch_bounds__(256) void kmeans_partial_kernel(const float *__restrict__ Z, long long N, int d, int M,
+                                                             const int32_t *__restrict__ assign,
+                                                             const int *__restrict__ order,
+                                                             unsigned long long *__restrict__ part)
+{
+    const int lane = threadIdx.x & 63;
+    const long long g = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long first = g * M;
+    if (first >= N) return;
+    const int mine = N - first < M ? (int)(N - first) : M;
+    unsigned long long sum[NS];
+#pragma unroll
+    for (int q = 0; q < NS; ++q) sum[q] = 0ull;
+    int cur = -1, held = 0;
+    auto flush = [&]() {
+        unsigned long long *dst = part + (size_t)(g + cur) * (size_t)d;
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            const int j = 64 * q + lane;
+            if (j < d) dst[j] = sum[q] - (unsigned long long)held * FIX_MAGIC_BITS;
+            sum[q] = 0ull;
+        }
+        held = 0;
+    };
+    // Every load below is unconditional: a lane beyond the row's end re-reads the row's last entry and
+    // a slot beyond the chunk's end the chunk's last member (what they add is never stored), so the
+    // forty loads of eight rows are in flight together.
+    int jc[NS];
+#pragma unroll
+    for (int q = 0; q < NS; ++q) jc[q] = 64 * q + lane < d ? 64 * q + lane : d - 1;
+    auto add_row = [&](const float (&zr)[NS]) {
+        ++held;
+#pragma unroll
+        for (int q = 0; q < NS; ++q)
+            sum[q] += (unsigned long long)__double_as_longlong(fma((double)zr[q], 4294967296.0, 6755399441055744.0));
+    };
+    for (int base = 0; base < mine; base += 64) {
+        const int nloc = mine - base < 64 ? mine - base : 64;
+        const int at = lane < nloc ? lane : nloc - 1;
+        const int myidx = order[first + base + at];
+        const int mycl = assign[myidx];
+        for (int u0 = 0; u0 < nloc; u0 += 8) {
+            float z[8][NS];
+            int cl[8];
+            bool same = u0 + 8 <= nloc;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int uu = u0 + u < nloc ? u0 + u : nloc - 1;
+                const float *__restrict__ zrow = Z + (long long)__builtin_amdgcn_readlane(myidx, uu) * d;
+                cl[u] = __builtin_amdgcn_readlane(mycl, uu);
+                same = same && cl[u] == cur;
+#pragma unroll
+                for (int q = 0; q < NS; ++q) z[u][q] = zrow[jc[q]];
+            }
+            if (same) {   // the usual case: eight more members of the current cluster
+#pragma unroll
+                for (int u = 0; u < 8; ++u) add_row(z[u]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (u0 + u < nloc) {   // the same in every lane
+                        if (cl[u] != cur) {
+                            if (cur >= 0) flush();
+                            cur = cl[u];
+                        }
+                        add_row(z[u]);
+                    }
+                }
+            }
+        }
+    }
+    if (cur >= 0) flush();
+}
+
+// One workgroup of eight wavefronts per cluster: the wavefronts share out the chunks the cluster's
+// members lie in, four chunks' partials (whole rows, lane j dimensions j, 64 + j, ...) requested
+// together; a chunk index beyond the last is clamped and its row not added.
+template <int NS>
+__global__ __launch_bounds__(512) void kmeans_mean_kernel(const unsigned long long *__restrict__ part, int d, int M,
+                                                          const int *__restrict__ counts,
+                                                          const int *__restrict__ offs, float *__restrict__ cent,
+                                                          int *__restrict__ counts_next,
+                                                          int *__restrict__ cursor_next, unsigned *reset_a,
+                                                          int *reset_b)
+{
+    __shared__ unsigned long long red[8][NS][64];
     const int c = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -885,58 +982,52 @@ __global__ __launch_bounds__(64 * WPB) void kmeans_sum_rows_kernel(const float *
         }
     }
     const int cnt = counts[c];
-    const int *__restrict__ mem = order + offs[c];
-    long long sum[NS];
+    if (cnt == 0) return;  // an empty cluster keeps its centroid (the same in every thread)
+    const int g0 = offs[c] / M, g1 = (offs[c] + cnt - 1) / M;
+    int jc[NS];
+    unsigned long long sum[NS];
 #pragma unroll
-    for (int q = 0; q < NS; ++q) sum[q] = 0;
-    // the wavefronts share out the members in contiguous runs; a wave reads up to 64 member indices at
-    // once (one per lane) and then requests four members' rows before the first is added
-    const int per = (cnt + WPB - 1) / WPB;
-    const int beg = wave * per;
-    const int end = beg + per < cnt ? beg + per : cnt;
-    for (int base = beg; base < end; base += 64) {
-        const int nloc = end - base < 64 ? end - base : 64;
-        const int myidx = lane < nloc ? mem[base + lane] : 0;
-        for (int u0 = 0; u0 < nloc; u0 += 4) {
-            float z[4][NS];
+    for (int q = 0; q < NS; ++q) {
+        jc[q] = 64 * q + lane < d ? 64 * q + lane : d - 1;
+        sum[q] = 0ull;
+    }
+    for (int g = g0 + wave; g <= g1; g += 32) {
+        unsigned long long v[4][NS];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int uu = u0 + u < 64 ? u0 + u : 63;
-                const long long row = __builtin_amdgcn_readlane(myidx, uu);
+        for (int u = 0; u < 4; ++u) {
+            const int gg = g + 8 * u <= g1 ? g + 8 * u : g1;
+            const unsigned long long *__restrict__ row = part + (size_t)(gg + c) * (size_t)d;
 #pragma unroll
-                for (int q = 0; q < NS; ++q) {
-                    const int j = 64 * q + lane;
-                    z[u][q] = (u0 + u < nloc && j < d) ? Z[row * d + j] : 0.f;
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int q = 0; q < NS; ++q) sum[q] += __double2ll_rn((double)z[u][q] * 4294967296.0);
+            for (int q = 0; q < NS; ++q) v[u][q] = row[jc[q]];
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (g + 8 * u <= g1) {   // the same in every lane
+#pragma unroll
+                for (int q = 0; q < NS; ++q) sum[q] += v[u][q];
+            }
     }
 #pragma unroll
     for (int q = 0; q < NS; ++q) red[wave][q][lane] = sum[q];
     __syncthreads();
-    if (cnt > 0) {  // an empty cluster keeps its centroid
-        for (int t = threadIdx.x; t < 64 * NS; t += 64 * WPB) {
-            const int q = t >> 6, jl = t & 63, j = 64 * q + jl;
-            if (j < d) {
-                long long tot = 0;
+    for (int t = threadIdx.x; t < 64 * NS; t += 512) {
+        const int q = t >> 6, jl = t & 63, j = 64 * q + jl;
+        if (j < d) {
+            unsigned long long tot = 0ull;
 #pragma unroll
-                for (int w = 0; w < WPB; ++w) tot += red[w][q][jl];
-                const double mean = ((double)tot * (1.0 / 4294967296.0)) / (double)cnt;
-                cent[(long long)c * d + j] = (float)mean;
-            }
+            for (int w = 0; w < 8; ++w) tot += red[w][q][jl];
+            const double mean = ((double)(long long)tot * (1.0 / 4294967296.0)) / (double)cnt;
+            cent[(long long)c * d + j] = (float)mean;
         }
     }
 }
 
 // counts2 / cursor2: [2][k] each, zero on the first call of a k-means run; offs: [k]; `parity` alternates per call.
+// part: kmeans_partial_elems(N, k, d) 64-bit words of scratch (rows of up to 512 dimensions).
 // reset_a / reset_b (nullable) are cleared for the next assignment step.
 hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, int *counts2,
-                                int *cursor2, int *order, int *offs, int parity, float *cent, unsigned *reset_a,
-                                int *reset_b, hipStream_t s)
+                                int *cursor2, int *order, int *offs, long long *part, int parity, float *cent,
+                                unsigned *reset_a, int *reset_b, hipStream_t s)
 {
     int *counts = counts2 + (size_t)(parity & 1) * k, *counts_next = counts2 + (size_t)((parity + 1) & 1) * k;
     int *cursor = cursor2 + (size_t)(parity & 1) * k, *cursor_next = cursor2 + (size_t)((parity + 1) & 1) * k;
@@ -945,27 +1036,32 @@ hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_
     hipLaunchKernelGGL(kmeans_scatter_kernel, dim3(blocks), dim3(256), 2 * sizeof(int) * (size_t)k, s, assign, N, k,
                        counts, cursor, order, offs);
     const int ns = (d + 63) / 64;
-#define LCN_SUM_ROWS(NS_)                                                                                           \
-    hipLaunchKernelGGL((kmeans_sum_rows_kernel<NS_, 8>), dim3((unsigned)k), dim3(512), 0, s, Z, d, k, counts, offs, \
-                       order, cent, counts_next, cursor_next, reset_a, reset_b)
-    if (k >= 512 && ns <= 8) {
+    if (ns <= 8) {
+        const int M = kmeans_sum_chunk(N);
+        const unsigned pblocks = (unsigned)(((N + M - 1) / M + 3) / 4);
+#define LCN_SUM_PARTIAL(NS_)                                                                                       \
+    hipLaunchKernelGGL((kmeans_partial_kernel<NS_>), dim3(pblocks), dim3(256), 0, s, Z, N, d, M, assign, order,       \
+                       (unsigned long long *)part);                                                                    \
+    hipLaunchKernelGGL((kmeans_mean_kernel<NS_>), dim3((unsigned)k), dim3(512), 0, s,                                  \
+                       (const unsigned long long *)part, d, M, counts, offs, cent, counts_next, cursor_next, reset_a, \
+                       reset_b)
         switch (ns) {
-            case 1: LCN_SUM_ROWS(1); break;
-            case 2: LCN_SUM_ROWS(2); break;
-            case 3: LCN_SUM_ROWS(3); break;
-            case 4: LCN_SUM_ROWS(4); break;
-            case 5: LCN_SUM_ROWS(5); break;
-            case 6: LCN_SUM_ROWS(6); break;
-            case 7: LCN_SUM_ROWS(7); break;
-            default: LCN_SUM_ROWS(8); break;
+            case 1: LCN_SUM_PARTIAL(1); break;
+            case 2: LCN_SUM_PARTIAL(2); break;
+            case 3: LCN_SUM_PARTIAL(3); break;
+            case 4: LCN_SUM_PARTIAL(4); break;
+            case 5: LCN_SUM_PARTIAL(5); break;
+            case 6: LCN_SUM_PARTIAL(6); break;
+            case 7: LCN_SUM_PARTIAL(7); break;
+            default: LCN_SUM_PARTIAL(8); break;
         }
+#undef LCN_SUM_PARTIAL
     } else if ((long long)k * ((d + 63) / 64) >= 512)
         hipLaunchKernelGGL((kmeans_sum_kernel<64, 16>), dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(1024), 0, s, Z,
                            d, k, counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
     else   // few clusters: narrower slices, four times the workgroups
         hipLaunchKernelGGL((kmeans_sum_kernel<16, 16>), dim3((unsigned)k, (unsigned)((d + 15) / 16)), dim3(1024), 0, s, Z,
                            d, k, counts, offs, order, cent, counts_next, cursor_next, reset_a, reset_b);
-#undef LCN_SUM_ROWS
     return hipGetLastError();
 }
 

@@ -71,6 +71,7 @@ struct KmScratch {  // what one k-means run needs for itself
     long long *idx;
     float *cent;
     int *counts2, *cursor2, *order, *offs;  // k-means update: [2][kmax], [2][kmax], [N], [kmax]
+    long long *part;                        // ... and its partial sums
     int32_t *assign;
     float *cn;
     unsigned *cmax_bits;
@@ -121,6 +122,7 @@ void layout(Handle &h, Bump &bump, Scratch &sc)
         km.nflagged = bump.take<int>(4);
         km.order = bump.take<int>((size_t)N);
         km.offs = bump.take<int>((size_t)kmax);
+        km.part = bump.take<long long>(kmeans_partial_elems(N, kmax, h.d));
         km.assign = bump.take<int32_t>((size_t)N);
         km.cn = bump.take<float>((size_t)kmax);
         km.ct = bump.take<char>(2 * split_plane_bytes(kmax, h.d));
@@ -330,8 +332,8 @@ lcn_status run_kmeans(Handle &h, Scratch &sc, KmScratch &km, hipStream_t s, int 
             HIPCHK(launch_assign_kmeans(h.Z, N, h.d, cent, k, assign, km.flagged, km.nflagged, s));
         }
         // the last iteration leaves the count of undecided points in place for lcn_get_info
-        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, km.counts2, km.cursor2, km.order, km.offs, it, cent, km.cmax_bits,
-                                    it + 1 < T ? km.nflagged : nullptr, s));
+        HIPCHK(launch_kmeans_update(h.Z, N, h.d, assign, k, km.counts2, km.cursor2, km.order, km.offs, km.part, it, cent,
+                                    km.cmax_bits, it + 1 < T ? km.nflagged : nullptr, s));
     }
     return LCN_OK;
 }
@@ -394,8 +396,8 @@ lcn_status run_hier_kmeans(Handle &h, Scratch &sc, KmScratch &km, hipStream_t s,
         for (int it = 0; it < T; ++it) {
             HIPCHK(launch_assign_children(h.Z, h.d, km.cent, parents, bl, km.nchild, km.horder, km.hchunks, nchunks,
                                           km.hcent, dst, s));
-            HIPCHK(launch_kmeans_update(h.Z, N, h.d, dst, (int)k, km.counts2, km.cursor2, km.order, km.offs, it,
-                                        km.cent, nullptr, nullptr, s));
+            HIPCHK(launch_kmeans_update(h.Z, N, h.d, dst, (int)k, km.counts2, km.cursor2, km.order, km.offs, km.part,
+                                        it, km.cent, nullptr, nullptr, s));
         }
         parents = k;
     }

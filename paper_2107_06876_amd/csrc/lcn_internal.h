@@ -78,11 +78,13 @@ hipError_t launch_assign_pairs(const float *Z, int d, const float *cent, int32_t
 hipError_t launch_assign_crosspolytope(const float *Z, long long N, int d, const float *Rm, int b, int32_t *out,
                                        hipStream_t s);
 // counts2 / cursor2: [2][k] ints each, zero before the first update of a k-means run; order: [N], offs: [k] ints;
+// part: kmeans_partial_elems(N, largest k, d) 64-bit words of scratch for the partial sums;
 // `parity` alternates from update to update.  reset_a / reset_b (nullable) are cleared for the next
 // assignment step.
 hipError_t launch_kmeans_update(const float *Z, long long N, int d, const int32_t *assign, int k, int *counts2,
-                                int *cursor2, int *order, int *offs, int parity, float *cent, unsigned *reset_a,
-                                int *reset_b, hipStream_t s);
+                                int *cursor2, int *order, int *offs, long long *part, int parity, float *cent,
+                                unsigned *reset_a, int *reset_b, hipStream_t s);
+size_t kmeans_partial_elems(long long N, int kmax, int d);
 
 struct SortBuffers {
     int R, b;
