@@ -112,6 +112,34 @@ hipError_t launch_split_planes(const float *src, long long rows, int d, int plan
     return hipGetLastError();
 }
 
+// What the filter makes of a point's three smallest scores.
+// |score - exact score| <= delta = err_coef (||z||^2 + max ||c||^2), see launch_assign_filter.
+// The exact rule's winner scores at most best + 2 delta, so:
+//   second beyond that      -> bidx is the winner;
+//   only third beyond that  -> the winner is bidx or sidx (decided by the exact rule on those two);
+//   otherwise               -> the exact rule over all centroids.
+template <bool TOP3>
+__device__ inline void filter_decide(long long p, float best, float second, float third, int bidx, int sidx,
+                                     const double *__restrict__ zn, const unsigned *__restrict__ cmax_bits,
+                                     float err_coef, int32_t *__restrict__ out, int *__restrict__ flagged,
+                                     int *__restrict__ pairs, int *nflagged)
+{
+    out[p] = bidx;
+    const float cmax = __uint_as_float(*cmax_bits);
+    const float delta = err_coef * ((float)zn[p] * 1.0000002f + cmax);
+    if (!(second - best > 2.f * delta)) {
+        if (TOP3 && third - best > 2.f * delta) {
+            const int slot = atomicAdd(nflagged + 1, 1);
+            pairs[3 * (long long)slot] = (int)p;
+            pairs[3 * (long long)slot + 1] = bidx;
+            pairs[3 * (long long)slot + 2] = sidx;
+        } else {
+            const int slot = atomicAdd(nflagged, 1);
+            flagged[slot] = (int)p;
+        }
+    }
+}
+
 // ZP: planes of the points (2: fp32 input, 1: input exactly representable in bf16).
 // TOP3: also track the third smallest score and the second's centroid, so that a point
 // with exactly two candidates goes to the exact rule on those two; pays off when the
@@ -244,25 +272,217 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
         offer(ot, 0);  // cannot rank above third: two scores of the other half are not larger
     }
     const long long p = P * 32 + col;
-    if (active && half == 0 && p < N) {
-        out[p] = bidx;
-        // |score - exact score| <= delta = err_coef (||z||^2 + max ||c||^2), see launch_assign_filter.
-        // The exact rule's winner scores at most best + 2 delta, so:
-        //   second beyond that      -> bidx is the winner;
-        //   only third beyond that  -> the winner is bidx or sidx (decided by the exact rule on those two);
-        //   otherwise               -> the exact rule over all centroids.
-        const float cmax = __uint_as_float(*cmax_bits);
-        const float delta = err_coef * ((float)zn[p] * 1.0000002f + cmax);
-        if (!(second - best > 2.f * delta)) {
-            if (TOP3 && third - best > 2.f * delta) {
-                const int slot = atomicAdd(nflagged + 1, 1);
-                pairs[3 * (long long)slot] = (int)p;
-                pairs[3 * (long long)slot + 1] = bidx;
-                pairs[3 * (long long)slot + 2] = sidx;
-            } else {
-                const int slot = atomicAdd(nflagged, 1);
-                flagged[slot] = (int)p;
+    if (active && half == 0 && p < N)
+        filter_decide<TOP3>(p, best, second, third, bidx, sidx, zn, cmax_bits, err_coef, out, flagged, pairs, nflagged);
+}
+
+// The filter for points given as bf16 (one plane) against many centroids: the 128 points of a
+// workgroup stay in LDS for the whole launch (4 S KB, read from memory once instead of once per 128
+// centroids), and the roles of the four wavefronts are turned round: a wavefront takes ALL 128
+// points (four accumulator tiles, one per group of 32 points) against ONE group of 32 centroids per
+// pass, whose operands it reads from memory (the cache: every workgroup streams the same 2 k S KB)
+// straight into registers, a few steps ahead in a ring of registers.  Per step a wavefront reads
+// four operands from LDS and two from memory for eight matrix instructions -- half the LDS traffic
+// of the kernel above, and nothing in the loop waits for the workgroup.  Every load is
+// unconditional (indices beyond the end are clamped; what they fetch is not used), so the waits
+// count exactly the loads that must have landed.  A lane tracks the smallest scores of four
+// points, over the centroids its wavefront saw; half-wavefronts and wavefronts are merged at the end.
+constexpr int FR_MERGE_BYTES = 4 * FP * 5 * 4;
+
+template <bool TOP3>
+__global__ __launch_bounds__(256, 2) void assign_filter_resident_kernel(
+    const bf16x8 *__restrict__ Zt, long long N, int S, const bf16x8 *__restrict__ Ct, long long cplane, int k,
+    const float *__restrict__ cn, const double *__restrict__ zn, const unsigned *__restrict__ cmax_bits, float err_coef,
+    int32_t *__restrict__ out, int *__restrict__ flagged, int *__restrict__ pairs, int *nflagged)
+{
+    extern __shared__ __align__(16) unsigned char fr_lds[];
+    bf16x8 *Zs = reinterpret_cast<bf16x8 *>(fr_lds);   // [4 point groups][S][64]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const long long ngroups = (N + 31) / 32;
+    const long long G0 = (long long)blockIdx.x * 4;
+    {   // wavefront w brings in point group G0 + w (the last workgroup repeats the last group)
+        const long long gl = G0 + w < ngroups ? G0 + w : ngroups - 1;
+        const bf16x8 *__restrict__ src = Zt + gl * S * 64 + lane;
+        bf16x8 *dst = Zs + (size_t)w * S * 64 + lane;
+        for (int s0 = 0; s0 < S; s0 += 8) {
+            bf16x8 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = src[(long long)(s0 + u < S ? s0 + u : S - 1) * 64];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < S) dst[(s0 + u) * 64] = t[u];
+        }
+    }
+    __syncthreads();
+
+    const int cgroups = (k + 31) / 32, npass = (k + FC - 1) / FC;
+    // Steps a centroid operand is requested ahead.  Two is enough and best: what bounds the stream is not
+    // its latency but the first-level cache, which holds fewer lines than eight wavefronts can ask for
+    // (a ring of 4, 6, 8 steps measured 2 %, 11 %, 7 % slower; a pass is padded to whole turns).
+    constexpr int RING = 2;
+    const int SP = (S + RING - 1) / RING * RING;  // a pass in whole turns of the ring; steps S .. SP - 1 multiply nothing
+    // where the next request of the ring goes: pass lp (its centroid group's first operand at lbase), step ls
+    // Workgroups take the passes in rotated order (workgroup b starts with pass b mod npass): all of
+    // them stream the same operands at the same pace, and in the same order they would all ask the
+    // same few cache channels at once.
+    const int rot = (int)(blockIdx.x % (unsigned)npass);
+    auto pass_of = [&](int i) {
+        i = i < npass ? i : npass - 1;   // past the last pass: its operands once more, unused
+        i += rot;
+        return i < npass ? i : i - npass;
+    };
+    auto group_base = [&](int i) {
+        const int pass = pass_of(i);
+        int cg = 4 * pass + w;
+        cg = cg < cgroups ? cg : cgroups - 1;
+        return Ct + (long long)cg * S * 64 + lane;
+    };
+    int lp = 0, ls = 0;
+    const bf16x8 *__restrict__ lbase = group_base(0);
+    auto request = [&](bf16x8 &d1, bf16x8 &d2) {
+        const bf16x8 *cp = lbase + (ls < S ? ls : S - 1) * 64;
+        d1 = cp[0];
+        d2 = cp[cplane];
+        if (++ls == SP) {   // the same in every lane; nothing is loaded inside
+            ls = 0;
+            lbase = group_base(++lp);
+        }
+    };
+    float best[4], second[4], third[4];
+    int bidx[4], sidx[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        best[g] = second[g] = third[g] = INFINITY;
+        bidx[g] = sidx[g] = 0;
+    }
+    bf16x8 r1[RING], r2[RING];   // the ring: the centroid group's two planes for the next RING steps
+#pragma unroll
+    for (int u = 0; u < RING; ++u) request(r1[u], r2[u]);
+    // the points' operands of a step are read from LDS one step ahead, into two sets of registers in turn
+    bf16x8 za[4], zb[4];
+    auto zread = [&](bf16x8 (&z)[4], int step) {
+        const int sz = step < S ? step : S - 1;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) z[g] = Zs[((size_t)g * S + sz) * 64 + lane];
+    };
+    zread(za, 0);
+    for (int pi = 0; pi < npass; ++pi) {
+        const int pass = pass_of(pi);
+        // squared norms of the lane's sixteen centroids of this pass (+inf beyond the last centroid:
+        // such a row repeats the last group's operands and never wins)
+        float cnv[16];
+        const int cbase = FC * pass + 32 * w + 4 * half;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ci = cbase + 8 * q + j;
+                const float v = cn[ci < k ? ci : k - 1];
+                cnv[4 * q + j] = ci < k ? v : INFINITY;
             }
+        floatx16 acc[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[g][v] = 0.f;
+        for (int s0 = 0; s0 < SP; s0 += RING) {
+#pragma unroll
+            for (int u = 0; u < RING; ++u) {
+                const int st = s0 + u;
+                bf16x8(&zc)[4] = (u & 1) ? zb : za;
+                bf16x8(&zn)[4] = (u & 1) ? za : zb;
+                zread(zn, st + 1 < SP ? st + 1 : 0);   // after a pass's last step comes the next pass's first
+                const bf16x8 a1 = r1[u], a2 = r2[u];
+                if (st < S) {   // the same in every lane; no load inside
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, zc[g], acc[g], 0, 0, 0);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, zc[g], acc[g], 0, 0, 0);
+                }
+                request(r1[u], r2[u]);
+            }
+        }
+        // element v of tile g: centroid row (v / 4) * 8 + half * 4 + v % 4 of the wavefront's group, for
+        // point column `col` of point group g.  The three smallest stay sorted: the new smallest is the
+        // median of (-inf, best, score), the new second that of (best, second, score), the new third
+        // that of (second, third, score).  A centroid is remembered as 16 pass + v (a scalar) and
+        // turned into its index at the end.
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float b = best[g], s2 = second[g], t3 = third[g];
+            int bi = bidx[g], si = sidx[g];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float sc = fmaf(-2.f, acc[g][v], cnv[v]);
+                const int code = 16 * pass + v;
+                const bool lt1 = sc < b;
+                if (TOP3) {
+                    const bool lt2 = sc < s2;
+                    const int keep = lt2 ? code : si;
+                    t3 = __builtin_amdgcn_fmed3f(s2, t3, sc);
+                    si = lt1 ? bi : keep;
+                }
+                s2 = __builtin_amdgcn_fmed3f(b, s2, sc);
+                bi = lt1 ? code : bi;
+                b = __builtin_amdgcn_fmed3f(-INFINITY, b, sc);
+            }
+            best[g] = b, second[g] = s2, third[g] = t3;
+            bidx[g] = bi, sidx[g] = si;
+        }
+    }
+    // from 16 pass + v to the centroid's index
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        bidx[g] = FC * (bidx[g] >> 4) + 32 * w + 4 * half + ((bidx[g] >> 2) & 3) * 8 + (bidx[g] & 3);
+        sidx[g] = FC * (sidx[g] >> 4) + 32 * w + 4 * half + ((sidx[g] >> 2) & 3) * 8 + (sidx[g] & 3);
+    }
+    // merge: the other half-wavefront's three smallest are offered in turn (the third cannot rank
+    // above third: two scores of its own set are not larger), then the four wavefronts' through LDS
+    auto offer = [&](float &b, float &s2, float &t3, int &bi, int &si, float sc, int c) {
+        const bool lt1 = sc < b, lt2 = sc < s2;
+        if (TOP3) {
+            t3 = fminf(t3, fmaxf(sc, s2));
+            si = lt1 ? bi : (lt2 ? c : si);
+        }
+        s2 = fminf(s2, fmaxf(sc, b));
+        bi = lt1 ? c : bi;
+        b = fminf(b, sc);
+    };
+    __syncthreads();   // every wavefront has finished reading the points
+    float *mf = reinterpret_cast<float *>(fr_lds);             // [3][4 wavefronts][128 points]
+    int *mi = reinterpret_cast<int *>(fr_lds) + 3 * 4 * FP;     // [2][4][128]
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const float ob = __shfl_xor(best[g], 32, 64), os = __shfl_xor(second[g], 32, 64),
+                    ot = __shfl_xor(third[g], 32, 64);
+        const int oi = __shfl_xor(bidx[g], 32, 64), osi = __shfl_xor(sidx[g], 32, 64);
+        offer(best[g], second[g], third[g], bidx[g], sidx[g], ob, oi);
+        offer(best[g], second[g], third[g], bidx[g], sidx[g], os, osi);
+        offer(best[g], second[g], third[g], bidx[g], sidx[g], ot, 0);
+        if (half == 0) {
+            const int pt = 32 * g + col;
+            mf[(0 * 4 + w) * FP + pt] = best[g];
+            mf[(1 * 4 + w) * FP + pt] = second[g];
+            mf[(2 * 4 + w) * FP + pt] = third[g];
+            mi[(0 * 4 + w) * FP + pt] = bidx[g];
+            mi[(1 * 4 + w) * FP + pt] = sidx[g];
+        }
+    }
+    __syncthreads();
+    if (tid < FP) {
+        const long long p = G0 * 32 + tid;
+        if (p < N) {
+            float b = INFINITY, s2 = INFINITY, t3 = INFINITY;
+            int bi = 0, si = 0;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) {
+                offer(b, s2, t3, bi, si, mf[(0 * 4 + ww) * FP + tid], mi[(0 * 4 + ww) * FP + tid]);
+                offer(b, s2, t3, bi, si, mf[(1 * 4 + ww) * FP + tid], mi[(1 * 4 + ww) * FP + tid]);
+                offer(b, s2, t3, bi, si, mf[(2 * 4 + ww) * FP + tid], 0);
+            }
+            filter_decide<TOP3>(p, b, s2, t3, bi, si, zn, cmax_bits, err_coef, out, flagged, pairs, nflagged);
         }
     }
 }
@@ -296,6 +516,27 @@ hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d,
     const long long cplane = (long long)(split_plane_bytes(k, d) / 16);
     const unsigned grid = (unsigned)((N + FP - 1) / FP);
     const bool top3 = filter_uses_pairs(k);
+    // points given as bf16, several passes over the centroids, and two workgroups' points fit the LDS
+    // of a compute unit: the kernel that keeps the points on chip
+    if (zplanes == 1 && k > FC && S <= 19) {
+        const size_t lds = (size_t)4 * S * 1024 > (size_t)FR_MERGE_BYTES ? (size_t)4 * S * 1024 : (size_t)FR_MERGE_BYTES;
+        const unsigned rgrid = (unsigned)(((N + 31) / 32 + 3) / 4);
+#define LCN_RESIDENT_LAUNCH(T3_)                                                                                       \
+    do {                                                                                                               \
+        hipError_t e_ = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_filter_resident_kernel<T3_>),       \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                     \
+        if (e_ != hipSuccess) return e_;                                                                               \
+        hipLaunchKernelGGL((assign_filter_resident_kernel<T3_>), dim3(rgrid), dim3(256), lds, s, (const bf16x8 *)Zt,   \
+                           N, S, (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, pairs,      \
+                           nflagged);                                                                                  \
+    } while (0)
+        if (top3)
+            LCN_RESIDENT_LAUNCH(true);
+        else
+            LCN_RESIDENT_LAUNCH(false);
+#undef LCN_RESIDENT_LAUNCH
+        return hipGetLastError();
+    }
 #define LCN_FILTER_LAUNCH(ZP_, T3_)                                                                                   \
     hipLaunchKernelGGL((assign_filter_kernel<ZP_, T3_>), dim3(grid), dim3(256), 0, s, (const bf16x8 *)Zt, zplane, N,  \
                        S, (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, pairs, nflagged)

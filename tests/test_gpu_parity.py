@@ -134,14 +134,18 @@ def test_filter_plus_exact_rule_equals_exact_rule_everywhere(monkeypatch):
     rule on the undecided points (over two candidates or over all centroids)
     are those of the exact rule applied to every point; 300 buckets exercise
     the two-candidate path (more than 256 centroids), bf16 input the two-product
-    filter."""
+    filter, bf16 input with more than 128 centroids its variant with resident points."""
     import torch
     import paper_2107_06876_amd as lcn
     from parity import gpu_build
     cases = (workloads.config1(),
              workloads.config3(n=3000, d=48, landmarks=96, buckets=300, rounds=2, iters=2, name="C3 reduced"),
              workloads.config3(n=2500, d=70, landmarks=64, buckets=24, rounds=2, iters=2, bf16=True,
-                               name="C5 reduced"))
+                               name="C5 reduced"),
+             # bf16 input against more than 128 centroids: the filter that keeps the points on chip, with
+             # a last group of centroids, a last pass and a last workgroup that are all partly empty
+             workloads.config3(n=2500, d=70, landmarks=200, buckets=300, rounds=2, iters=2, bf16=True,
+                               name="C5 reduced, many centroids"))
     for p in cases:
         got = {}
         for exact in ("0", "1"):
