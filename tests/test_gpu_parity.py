@@ -568,6 +568,20 @@ def test_a_sweep_that_gives_up_its_wait_reports_a_device_error(monkeypatch):
     lcn.lcn_destroy(h)
 
 
+def test_a_sweep_grid_larger_than_what_is_resident(monkeypatch):
+    """By default a sweep's grid is capped at the workgroups that are resident together.  Raised
+    above that from the host (LCN_PASS_GRID), the workgroups beyond start as others finish; the
+    hand-over of the totals needs only the first few workgroups of a launch, which are dispatched
+    first and wait for nothing, so the bounded wait still ends and the results are the oracle's."""
+    from parity import compare
+    import paper_2107_06876_amd as lcn
+    p = workloads.config3(n=6000, d=64, landmarks=128, buckets=32, rounds=2, iters=20, name="C3 reduced")
+    monkeypatch.setenv("LCN_PASS_GRID", "4096")   # 375 workgroups per sweep of 6000 rows
+    out = compare(p, "lcn")
+    assert out["status"] == lcn.binding.OK
+    print("grid above residency", out, flush=True)
+
+
 @pytest.mark.parametrize("mode,lam_factor", [("lcn", 0.5), ("nystrom", 0.5), ("lcn", 0.1), ("nystrom", 0.1),
                                              ("lcn", 0.075)])
 def test_config2_full_size_lcn_and_nystrom(mode, lam_factor):
