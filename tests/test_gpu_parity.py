@@ -157,6 +157,31 @@ def test_filter_plus_exact_rule_equals_exact_rule_everywhere(monkeypatch):
         assert got["1"][2] == 0
 
 
+@pytest.mark.parametrize("n,d,landmarks,buckets", [
+    (70, 8, 129, 130),        # one step of 16 dimensions, one point group past the first workgroup, 129 and 130 centroids
+    (129, 24, 140, 200),      # two workgroups, the second with one point
+    (1000, 304, 160, 512),    # the widest rows the resident kernel takes (19 steps), two-candidate path
+    (1000, 305, 160, 300),    # one dimension more: back to the kernel that streams the points
+    (3000, 100, 500, 1000),   # many passes, a last pass with one group of 8 centroids
+])
+def test_filter_with_resident_points_on_edge_shapes(monkeypatch, n, d, landmarks, buckets):
+    """bf16 points against more than 128 centroids (the filter that keeps a workgroup's points in
+    LDS): landmarks and buckets equal those of the exact rule applied to every point, on shapes with
+    partly empty point groups, centroid groups and passes, and on both sides of its width limit."""
+    import torch
+    import paper_2107_06876_amd as lcn
+    from parity import gpu_build
+    p = workloads.config3(n=n, d=d, landmarks=landmarks, buckets=buckets, rounds=1, iters=1, bf16=True,
+                          name="bf16 %dx%d" % (n, d))
+    got = {}
+    for exact in ("0", "1"):
+        monkeypatch.setenv("LCN_EXACT_ASSIGN_ONLY", exact)
+        h = gpu_build(p, "lcn")
+        got[exact] = (lcn.lcn_get_landmarks(h), lcn.lcn_get_buckets(h))
+        lcn.lcn_destroy(h)
+    assert torch.equal(got["0"][0], got["1"][0]) and torch.equal(got["0"][1], got["1"][1])
+
+
 def test_config3_full_size():
     """The benchmark configuration itself (n = m = 20 000, d = 300, l = 256,
     128 buckets x 3 rounds, 200 iterations), in the launch configuration
