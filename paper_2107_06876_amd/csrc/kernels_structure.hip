@@ -44,6 +44,26 @@ hipError_t launch_convert(const void *X, long long n, const void *Y, long long m
     return hipGetLastError();
 }
 
+// Several small regions cleared by one launch (a clear of its own per region is a launch of its own,
+// and a launch costs more than these clears).  Sizes in 4-byte words.
+__global__ void clear_regions_kernel(ClearRegions R)
+{
+    for (int q = 0; q < R.count; ++q)
+        for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < R.words[q];
+             i += (long long)gridDim.x * blockDim.x)
+            R.ptr[q][i] = 0u;
+}
+
+hipError_t launch_clear_regions(const ClearRegions &R, hipStream_t s)
+{
+    long long most = 0;
+    for (int q = 0; q < R.count; ++q) most = R.words[q] > most ? R.words[q] : most;
+    if (most <= 0) return hipSuccess;
+    const long long blocks = (most + 255) / 256;
+    hipLaunchKernelGGL(clear_regions_kernel, dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0, s, R);
+    return hipGetLastError();
+}
+
 __global__ void gather_rows_kernel(const float *Z, int d, const long long *idx, int k, float *out)
 {
     int c = blockIdx.x;

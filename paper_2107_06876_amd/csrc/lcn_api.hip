@@ -420,17 +420,23 @@ lcn_status status_from_counters(Handle &h)
 
 // From the stored log scalings: working copies, bucket-ordered copies, and the
 // accumulators z = U^T u (buffer 1) and y = W v (buffer 0).
-lcn_status init_state(Handle &h)
+lcn_status init_state(Handle &h, bool clear_logs = false)
 {
     const size_t R1 = (size_t)(h.R > 0 ? h.R : 1);
     // the slot behind the bucket-ordered copies that stays zero: entry R n (R m) of an array of doubles
     // (logarithmic sweeps) or of floats (linear sweeps)
-    HIPCHK(hipMemsetAsync(h.perm_u + R1 * h.n, 0, 8 * sizeof(double), h.stream));
-    HIPCHK(hipMemsetAsync(h.perm_v + R1 * h.m, 0, 8 * sizeof(double), h.stream));
+    ClearRegions cl{};
+    cl.add(h.perm_u + R1 * h.n, 8 * sizeof(double));
+    cl.add(h.perm_v + R1 * h.m, 8 * sizeof(double));
     if (!h.log_domain) {
-        HIPCHK(hipMemsetAsync(reinterpret_cast<float *>(h.perm_u) + R1 * h.n, 0, 8 * sizeof(float), h.stream));
-        HIPCHK(hipMemsetAsync(reinterpret_cast<float *>(h.perm_v) + R1 * h.m, 0, 8 * sizeof(float), h.stream));
+        cl.add(reinterpret_cast<float *>(h.perm_u) + R1 * h.n, 8 * sizeof(float));
+        cl.add(reinterpret_cast<float *>(h.perm_v) + R1 * h.m, 8 * sizeof(float));
     }
+    if (clear_logs) {   // scalings at their start, v = 1 (and u, until the first sweep replaces it)
+        cl.add(h.log_u, sizeof(float) * (size_t)h.n);
+        cl.add(h.log_v, sizeof(float) * (size_t)h.m);
+    }
+    HIPCHK(launch_clear_regions(cl, h.stream));
     HIPCHK(launch_pass(h, 0, PASS_INIT, -1, 1, nullptr, h.stream));
     HIPCHK(launch_pass(h, 1, PASS_INIT, -1, 0, nullptr, h.stream));
     h.fresh = 1;
@@ -536,9 +542,11 @@ struct Builder {
             for (int q = 0; q < KM_LANES; ++q) lane[q] = h.stream;
         HIPCHK(hipEventCreate(&h.ev0));
         HIPCHK(hipEventCreate(&h.ev1));
-        HIPCHK(hipMemsetAsync(h.counters, 0, 16 * sizeof(unsigned long long), h.stream));
-        HIPCHK(hipMemsetAsync(sc.fail_flag, 0, 4 * sizeof(int), h.stream));
-        HIPCHK(hipMemsetAsync(sc.totals, 0, 4 * sizeof(long long), h.stream));
+        ClearRegions cl{};
+        cl.add(h.counters, 16 * sizeof(unsigned long long));
+        cl.add(sc.fail_flag, 4 * sizeof(int));
+        cl.add(sc.totals, 4 * sizeof(long long));
+        HIPCHK(launch_clear_regions(cl, h.stream));
         HIPCHK(hipMemcpyAsync(h.a, a, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, h.stream));
         HIPCHK(hipMemcpyAsync(h.b_marg, b, sizeof(float) * (size_t)m, hipMemcpyDeviceToDevice, h.stream));
         HIPCHK(launch_convert(X, n, Y, m, d, dtype, h.Z, (unsigned *)(h.counters + 4), h.stream));
@@ -756,9 +764,7 @@ struct Builder {
             HIPCHK(hipStreamWaitEvent(h.stream, join[0], 0));
         }
         if (h.R > 0) HIPCHK(launch_correction(h, h.ntiles, h.stream));
-        HIPCHK(hipMemsetAsync(h.log_u, 0, sizeof(float) * (size_t)n, h.stream));
-        HIPCHK(hipMemsetAsync(h.log_v, 0, sizeof(float) * (size_t)m, h.stream));
-        const lcn_status st = init_state(h);
+        const lcn_status st = init_state(h, true);
         if (st != LCN_OK) return st;
         int fail = 0;
         unsigned long long uniq = 0;

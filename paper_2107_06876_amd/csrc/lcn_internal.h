@@ -53,6 +53,18 @@ struct Handle;
 hipError_t launch_convert(const void *X, long long n, const void *Y, long long m, int d, int dtype, float *Z,
                           unsigned *range_flag, hipStream_t s);
 hipError_t launch_gather_rows(const float *Z, int d, const long long *idx, int k, float *out, hipStream_t s);
+// up to eight regions of 4-byte words set to zero by one launch
+struct ClearRegions {
+    unsigned *ptr[8];
+    long long words[8];
+    int count;
+    void add(void *p, size_t bytes)
+    {
+        ptr[count] = (unsigned *)p;
+        words[count++] = (long long)(bytes / 4);
+    }
+};
+hipError_t launch_clear_regions(const ClearRegions &R, hipStream_t s);
 hipError_t launch_assign_children(const float *Z, int d, const float *cent, long long parents, int branch,
                                   const int *nchild, const int *order, const int *chunks, int nchunks, double *centT,
                                   int32_t *out, hipStream_t s);
