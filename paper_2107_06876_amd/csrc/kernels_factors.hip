@@ -174,11 +174,19 @@ __device__ inline void tile_zero(TileAcc &acc)
 
 // cost from the dot product and the squared norms of the two points; the squared distance is
 // |p|^2 + |q|^2 - 2 p.q in fp64 (rounding can leave it a hair below zero for coinciding points)
+// For the cosine cost the callers pass, instead of the squared norms, their inverse roots (taken once
+// per row and column of a tile, not once per pair): 1 - p.q / (|p| |q|).
 __device__ inline double cost_from_dot(double dot, int cost, double pn, double qn)
 {
-    if (cost == LCN_COST_COSINE) return 1.0 - dot / (sqrt(pn) * sqrt(qn));
+    if (cost == LCN_COST_COSINE) return 1.0 - dot * pn * qn;
     const double sq = fmax(pn + qn - 2.0 * dot, 0.0);
     return cost == LCN_COST_EUCLID ? sqrt(sq) : sq;
+}
+
+// what cost_from_dot wants of a point's squared norm
+__device__ inline double norm_term(double sqnorm, int cost)
+{
+    return cost == LCN_COST_COSINE ? 1.0 / sqrt(sqnorm) : sqnorm;
 }
 
 // Which 64 x 64 tile of a (row tiles x col_tiles) grid a workgroup of a one-dimensional launch takes.
@@ -210,6 +218,7 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
     __shared__ __align__(16) float Ps[TILE][LDK];
     __shared__ __align__(16) float Cs[TILE][LDK];
     __shared__ long long pidx[TILE], qidx[TILE];
+    __shared__ double pterm[TILE], qterm[TILE];   // per row / column of the tile: see norm_term
     const int tid = threadIdx.x;
     long long ptile;
     int qtile;
@@ -220,6 +229,10 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
     if (tid < TILE) {
         pidx[tid] = p0 + tid < rows ? p0 + tid : -1;
         qidx[tid] = q0 + tid < cols ? q0 + tid : -1;
+        pterm[tid] = p0 + tid < rows ? norm_term(pn[p0 + tid], cost) : 0.0;
+    } else if (tid < 2 * TILE) {
+        const int t = tid - TILE;
+        qterm[t] = q0 + t < cols ? norm_term(qn[q0 + t], cost) : 0.0;
     }
     TileAcc acc;
     tile_zero(acc);
@@ -266,7 +279,7 @@ __global__ __launch_bounds__(256) void kernel_matrix_kernel(const float *__restr
         const int q = q0 + tile_col(e);
         if (p >= rows || q >= cols) continue;
         // a point against itself (the diagonal of the landmarks' matrix) is at cost zero exactly
-        double c = (P == Q && p == q) ? 0.0 : cost_from_dot(acc.get(e), cost, pn[p], qn[q]);
+        double c = (P == Q && p == q) ? 0.0 : cost_from_dot(acc.get(e), cost, pterm[tile_row(e)], qterm[tile_col(e)]);
         const double sq_est = cost == LCN_COST_EUCLID ? c * c : c;
         if (P == Q && p != q && cost != LCN_COST_COSINE && sq_est <= 1e-9 * (pn[p] + qn[q])) {
             // two landmarks (nearly) on top of each other: the norms cancel, so the squared distance is
@@ -672,6 +685,7 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
     __shared__ __align__(16) float Cs[TILE][LDK];
     __shared__ float vals[TILE][TILE + 1];
     __shared__ long long xi[TILE], yj[TILE];
+    __shared__ double xterm[TILE], yterm[TILE];   // per row / column of the tile: see norm_term
     __shared__ long long xdst[TILE], ydst[TILE];  // where each row's / column's slice of this block starts
     __shared__ int bx[8][TILE], by[8][TILE];
     __shared__ unsigned cnt_sh;
@@ -704,6 +718,7 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
         int li = ti * 64 + tid;
         long long gi = li < nx ? xperm[li] : -1;
         xi[tid] = gi;
+        xterm[tid] = gi >= 0 ? norm_term(zn[gi], cost) : 0.0;
         long long dst = -1;
         if (gi >= 0) {
             dst = B.rowbase_x[gi];
@@ -716,6 +731,7 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
         int lj = tj * 64 + t;
         long long gj = lj < ny ? yperm[lj] : -1;
         yj[t] = gj >= 0 ? B.n + gj : -1;  // row of Z
+        yterm[t] = gj >= 0 ? norm_term(zn[B.n + gj], cost) : 0.0;
         long long dst = -1;
         if (gj >= 0) {
             dst = B.rowbase_y[gj];
@@ -769,10 +785,11 @@ __global__ __launch_bounds__(256) void correction_kernel(SortBuffers B, const fl
         if (c == nd - 1) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const long long gi = xi[tile_row(e)], gj = yj[tile_col(e)];
+                const int li = tile_row(e), lj = tile_col(e);
+                const long long gi = xi[li], gj = yj[lj];
                 double v = 0.0;
                 if (gi >= 0 && gj >= 0) {
-                    const double cc = cost_from_dot(acc.get(e), cost, zn[gi], zn[gj]);
+                    const double cc = cost_from_dot(acc.get(e), cost, xterm[li], yterm[lj]);
                     v = log_values ? -cc * inv_lambda : exp(-cc * inv_lambda);
                 }
                 kv[e] = v;
