@@ -30,6 +30,8 @@
 // accumulator tiles.  With centroids on M a lane holds 16 centroids of ONE
 // point per tile, so the running arg-min needs no cross-lane work until the two
 // half-waves are merged at the end.
+#include <mutex>
+
 #include "lcn_internal.h"
 
 namespace lcn {
@@ -487,6 +489,24 @@ __global__ __launch_bounds__(256, 2) void assign_filter_resident_kernel(
     }
 }
 
+// More than 64 KB of dynamic LDS has to be allowed per kernel and device before the first such launch.
+// Done once per device and kernel (and again only for a larger size), under a lock: the k-means runs
+// of a build launch from several host threads.
+static hipError_t allow_dynamic_lds(const void *kernel, int which, size_t bytes)
+{
+    static std::mutex mu;
+    static size_t allowed[64][2] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    std::lock_guard<std::mutex> lock(mu);
+    if (allowed[dev][which] >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) allowed[dev][which] = bytes;
+    return e;
+}
+
 // Zt: the points' planes (launch_split_planes, `zplanes` of them); Ct: room for two planes of k centroids.
 // flagged: points for the exact rule over all centroids (count nflagged[0]); pairs: (point, centroid, centroid)
 // triples for the exact rule on two centroids (count nflagged[1]).
@@ -523,8 +543,8 @@ hipError_t launch_assign_filter(const void *Zt, int zplanes, long long N, int d,
         const unsigned rgrid = (unsigned)(((N + 31) / 32 + 3) / 4);
 #define LCN_RESIDENT_LAUNCH(T3_)                                                                                       \
     do {                                                                                                               \
-        hipError_t e_ = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_filter_resident_kernel<T3_>),       \
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                     \
+        hipError_t e_ = allow_dynamic_lds(reinterpret_cast<const void *>(&assign_filter_resident_kernel<T3_>),         \
+                                          T3_ ? 1 : 0, lds);                                                           \
         if (e_ != hipSuccess) return e_;                                                                               \
         hipLaunchKernelGGL((assign_filter_resident_kernel<T3_>), dim3(rgrid), dim3(256), lds, s, (const bf16x8 *)Zt,   \
                            N, S, (const bf16x8 *)Ct, cplane, k, cn, zn, cmax_bits, err_safe, out, flagged, pairs,      \
