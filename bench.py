@@ -295,6 +295,9 @@ def main():
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--no-c5", action="store_true",
                     help="leave out the short record for configuration 5 that the default run carries")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="leave out the measured ceilings of the part (copy and read bandwidth, matrix-instruction "
+                         "rates, empty-launch cost) that the line otherwise carries under measured_peaks")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 256 MiB device-to-device copy so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "can be scaled by what the same counter reads for a copy of known size")
@@ -417,6 +420,20 @@ def main():
     }
     if c5 is not None:
         out["c5"] = c5
+    if not args.no_peaks:
+        # what this part reaches in place (lcn_calibrate): the published peaks stay the roofline's denominator
+        try:
+            buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+            out["measured_peaks"] = {
+                "copy_GBs_read_plus_write": lcn.lcn_calibrate(lcn.CAL_COPY_GBS, buf),
+                "read_GBs": lcn.lcn_calibrate(lcn.CAL_READ_GBS, buf),
+                "mfma_bf16_32x32x16_TFLOPs": lcn.lcn_calibrate(lcn.CAL_MFMA_BF16_TFLOPS, buf),
+                "mfma_f64_16x16x4_TFLOPs": lcn.lcn_calibrate(lcn.CAL_MFMA_F64_TFLOPS, buf),
+                "empty_launch_us": lcn.lcn_calibrate(lcn.CAL_LAUNCH_US, buf),
+                "published": {"hbm_GBs": HBM_PEAK_GBS, "mfma_bf16_TFLOPs": 2500.0, "mfma_f64_TFLOPs": 78.6}}
+            del buf
+        except Exception as e:  # noqa: BLE001
+            out["measured_peaks"] = {"note": str(e)}
     if args.copy_calibration:
         src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

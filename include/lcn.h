@@ -325,6 +325,29 @@ lcn_status lcn_last_error_counts(lcn_handle h, int64_t *nonpositive, int64_t *em
  * runs twice: once to learn the exponent of its result). */
 lcn_status lcn_last_run_timing(lcn_handle h, float *ms_host, int32_t *launches_host);
 
+/* What this part reaches, measured in place (the roofline's practical ceilings;
+ * no part of the method).  `what`:
+ *   LCN_CAL_COPY_GBS          device-to-device copy of half the workspace into the
+ *                             other half, read + write bytes per second, GB/s
+ *   LCN_CAL_READ_GBS          read-only sweep over the workspace, GB/s
+ *   LCN_CAL_MFMA_BF16_TFLOPS  independent v_mfma_f32_32x32x16_bf16 on registers
+ *   LCN_CAL_MFMA_F64_TFLOPS   independent v_mfma_f64_16x16x4_f64 on registers
+ *   LCN_CAL_LAUNCH_US         microseconds per launch of an empty kernel in a
+ *                             stream of 2000 dependent launches
+ * workspace: device, 256-byte aligned, at least 64 MiB, overwritten (larger is
+ * better for the two memory figures: what fits the 256 MB last-level cache is
+ * served from there).  Runs on the given stream and synchronises it; allocates
+ * no device memory.  value_host receives the figure.
+ * Errors: INVALID_ARG, DEVICE. */
+typedef enum {
+    LCN_CAL_COPY_GBS = 0,
+    LCN_CAL_READ_GBS = 1,
+    LCN_CAL_MFMA_BF16_TFLOPS = 2,
+    LCN_CAL_MFMA_F64_TFLOPS = 3,
+    LCN_CAL_LAUNCH_US = 4
+} lcn_calibration;
+lcn_status lcn_calibrate(int32_t what, void *workspace, size_t workspace_bytes, void *hip_stream, double *value_host);
+
 void lcn_destroy(lcn_handle h); /* frees host memory only; the workspace is the caller's */
 const char *lcn_status_string(int32_t status);
 

@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     lcn_get_csr, lcn_get_factors, lcn_get_info, lcn_get_landmarks, lcn_get_scalings, lcn_last_run_timing,
     lcn_set_scalings, lcn_status_string, lcn_workspace_bytes, plan_marginals, sinkhorn_run, transport_cost,
     LcnBatchHandle, lcn_batched_get, lcn_batched_results, lcn_build_batched, lcn_backward,
-    lcn_backward_scratch_bytes, lcn_plan_rows, lcn_deletion_costs, lcn_head_lambdas, lcn_last_error_counts, lcn_backward_static)
+    lcn_backward_scratch_bytes, lcn_plan_rows, lcn_deletion_costs, lcn_head_lambdas, lcn_last_error_counts, lcn_backward_static,
+    lcn_calibrate, CAL_COPY_GBS, CAL_READ_GBS, CAL_MFMA_BF16_TFLOPS, CAL_MFMA_F64_TFLOPS, CAL_LAUNCH_US)

@@ -78,6 +78,7 @@ def load_library():
         lib.lcn_batched_get.argtypes = [vp, vp, vp, vp, vp, vp]
         lib.lcn_deletion_costs.argtypes = [vp, i64, i32, vp, vp, vp]
         lib.lcn_head_lambdas.argtypes = [ctypes.c_float, i32, vp]
+        lib.lcn_calibrate.argtypes = [i32, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
         lib.sinkhorn_run.argtypes = [vp, i32]
         lib.transport_cost.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
         lib.plan_marginals.argtypes = [vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
@@ -100,7 +101,7 @@ def load_library():
                      "lcn_head_lambdas", "lcn_workspace_bytes", "lcn_build", "sinkhorn_run", "transport_cost", "plan_marginals",
                      "lcn_get_scalings", "lcn_set_scalings", "lcn_get_landmarks", "lcn_get_buckets", "lcn_get_csr",
                      "lcn_get_factors", "lcn_get_info", "lcn_last_run_timing", "lcn_last_error_counts",
-                     "lcn_backward_static"):
+                     "lcn_backward_static", "lcn_calibrate"):
             getattr(lib, name).restype = i32
         _lib = lib
     return _lib
@@ -473,6 +474,22 @@ def lcn_deletion_costs(X, alpha, out=None, stream=None):
     if st != OK:
         raise LcnError(st, "lcn_deletion_costs")
     return out
+
+
+CAL_COPY_GBS, CAL_READ_GBS, CAL_MFMA_BF16_TFLOPS, CAL_MFMA_F64_TFLOPS, CAL_LAUNCH_US = range(5)
+
+
+def lcn_calibrate(what: int, workspace) -> float:
+    """One of the part's measured ceilings (see lcn.h); `workspace`: a contiguous device tensor of at
+    least 64 MiB, overwritten."""
+    import torch
+    value = ctypes.c_double(0.0)
+    stream = torch.cuda.current_stream(workspace.device).cuda_stream
+    st = load_library().lcn_calibrate(int(what), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                      stream, ctypes.byref(value))
+    if st != OK:
+        raise LcnError(st, "lcn_calibrate")
+    return value.value
 
 
 def lcn_head_lambdas(lam: float, num_heads: int):

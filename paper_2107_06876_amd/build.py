@@ -19,6 +19,7 @@ SOURCES = {
     "kernels_iter.hip": [],
     "kernels_batched.hip": ["-ffp-contract=off"],  # bucket rule again
     "lcn_api.hip": [],
+    "calibrate.hip": [],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,

@@ -25,7 +25,7 @@ def test_header_declares_the_expected_entry_points():
                      "lcn_get_factors", "lcn_get_info", "lcn_destroy", "lcn_status_string", "lcn_build_batched",
                      "lcn_batched_results", "lcn_batched_get", "lcn_last_run_timing", "lcn_backward",
                      "lcn_backward_scratch_bytes", "lcn_plan_rows", "lcn_deletion_costs", "lcn_head_lambdas",
-                     "lcn_last_error_counts", "lcn_backward_static"):
+                     "lcn_last_error_counts", "lcn_backward_static", "lcn_calibrate"):
         assert required in names
 
 
@@ -174,3 +174,16 @@ def test_gpu_entry_points_fail_loudly_without_the_library(monkeypatch, tmp_path)
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError):
         binding.load_library()
+
+
+def test_calibrate_validates_its_arguments_before_it_touches_the_device():
+    import ctypes
+    import paper_2107_06876_amd as lcn
+    from paper_2107_06876_amd.binding import ERR_INVALID_ARG
+    lib = lcn.load_library()
+    v = ctypes.c_double(0.0)
+    assert lib.lcn_calibrate(0, None, 1 << 30, None, ctypes.byref(v)) == ERR_INVALID_ARG     # no workspace
+    assert lib.lcn_calibrate(0, 4096, 1 << 20, None, ctypes.byref(v)) == ERR_INVALID_ARG     # too small
+    assert lib.lcn_calibrate(0, 4097, 1 << 30, None, ctypes.byref(v)) == ERR_INVALID_ARG     # misaligned
+    assert lib.lcn_calibrate(5, 4096, 1 << 30, None, ctypes.byref(v)) == ERR_INVALID_ARG     # no such figure
+    assert lib.lcn_calibrate(0, 4096, 1 << 30, None, None) == ERR_INVALID_ARG                # nowhere to put it
