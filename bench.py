@@ -77,6 +77,16 @@ def counter_traffic(config: int):
     return None
 
 
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(p, sample_iters: int, one_thread_iters: int = 0):
     """The oracle as it stands on the host cores: full build of the same
     problem, then a few iterations; then (one_thread_iters > 0) a shorter run on
@@ -95,7 +105,7 @@ def cpu_baseline(p, sample_iters: int, one_thread_iters: int = 0):
         "value": sample_iters / (t2 - t1), "unit": "iterations/s", "cores": threads, "kind": "oracle",
         "sample": "full oracle build of the same problem (%.1f s) then %d Sinkhorn iterations (%.2f s)"
                   % (t1 - t0, sample_iters, t2 - t1),
-        "build_ms": 1e3 * (t1 - t0),
+        "build_ms": 1e3 * (t1 - t0), "cpu_model": _cpu_model(), "host_cpus": os.cpu_count(),
     }
     if one_thread_iters > 0:
         _omp_threads(1)
