@@ -175,15 +175,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
     // the three smallest scores of the lane's point so far, with the centroids of the first two
     float best = INFINITY, second = INFINITY, third = INFINITY;
     int bidx = 0, sidx = 0;
+    // (kept sorted: the new smallest is the median of (-inf, best, s), the new second that of
+    // (best, second, s), the new third that of (second, third, s); plain selects, no branch)
     auto offer = [&](float s, int c) {
-        const bool lt1 = s < best, lt2 = s < second;
+        const bool lt1 = s < best;
         if (TOP3) {
-            third = fminf(third, fmaxf(s, second));
-            sidx = lt1 ? bidx : (lt2 ? c : sidx);
+            const bool lt2 = s < second;
+            const int keep = lt2 ? c : sidx;
+            third = __builtin_amdgcn_fmed3f(second, third, s);
+            sidx = lt1 ? bidx : keep;
         }
-        second = fminf(second, fmaxf(s, best));
+        second = __builtin_amdgcn_fmed3f(best, second, s);
         bidx = lt1 ? c : bidx;
-        best = fminf(best, s);
+        best = __builtin_amdgcn_fmed3f(-INFINITY, best, s);
     };
 
     for (int c0 = 0; c0 < k; c0 += FC) {
@@ -201,9 +205,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
             for (int j = 0; j < 4; ++j) {
                 const int piece = w + 4 * j;
                 const int ks = piece >> 3, t = (piece >> 1) & 3, pl = piece & 1;
-                const int s = 2 * stage + ks;
-                const int cg = c0 / 32 + t;
-                creg[j] = (s < S && cg < cgroups) ? Ct[pl * cplane + ((long long)cg * S + s) * 64 + lane] : zero;
+                // unconditional: a step past the last repeats the last (the points' operand is zero there),
+                // a group past the last repeats the last (its scores are masked by a norm of +inf)
+                const int s = 2 * stage + ks < S ? 2 * stage + ks : S - 1;
+                const int cg = c0 / 32 + t < cgroups ? c0 / 32 + t : cgroups - 1;
+                creg[j] = Ct[pl * cplane + ((long long)cg * S + s) * 64 + lane];
             }
         };
         auto store_c = [&](int buf) {
@@ -219,7 +225,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
             for (int ks = 0; ks < 2; ++ks) {
                 const int s = 2 * stage + ks;
 #pragma unroll
-                for (int pl = 0; pl < ZP; ++pl) dst[ks][pl] = s < S ? zsrc[pl * zplane + (long long)s * 64] : zero;
+                for (int pl = 0; pl < ZP; ++pl) {
+                    const bf16x8 v = zsrc[pl * zplane + (long long)(s < S ? s : S - 1) * 64];   // unconditional
+                    dst[ks][pl] = s < S ? v : zero;
+                }
             }
         };
         __syncthreads();  // the previous pass has finished reading the buffers
